@@ -1,0 +1,196 @@
+"""ctypes binding of the CPU oracle (oracle/dgq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and
+by bench.py's cpu_baseline leg.  The product package never imports it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dgq_oracle.c")
+_LIB = os.path.join(_HERE, "libdgq_oracle.so")
+GRANULE = 64
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no FMA contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call([
+            "gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11",
+            "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.dgqo_two_means.restype = C.c_int64
+    return _lib
+
+
+def _p(a, t=None):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def two_means(v):
+    """Returns (n_lower, tau, order)."""
+    v = _f32(v)
+    tau = C.c_float()
+    order = np.empty(v.size, dtype=np.int64)
+    k = lib().dgqo_two_means(_p(v), C.c_int64(v.size), C.byref(tau), _p(order))
+    return int(k), np.float32(tau.value), order
+
+
+@dataclass
+class Groups:
+    C: int
+    act_bits: int
+    G: int
+    P: int
+    NG: int
+    Kp: int
+    n_outlier_channels: int
+    n_regular_groups: int
+    dstar: int
+    n_class1_rows: int
+    perm: np.ndarray      # [Kp] int32, -1 = padding
+    goff: np.ndarray      # [NG+1]
+    glen: np.ndarray      # [NG]
+    tau_pix: np.float32
+    s: np.ndarray         # [2, NG]
+    z: np.ndarray
+    inv_s: np.ndarray
+    D_channel: float
+    D_pixel: float
+    cal_row_class: np.ndarray
+
+
+def calibrate(x, act_bits: int, G: int, P: int = 2, granule: int = GRANULE) -> Groups:
+    x = _f32(x)
+    rows, Cc = x.shape
+    ng_cap = 2 * ((Cc + G - 1) // G) + 2
+    kp_cap = Cc + granule * ng_cap
+    scal = np.zeros(8, dtype=np.int32)
+    perm = np.full(kp_cap, -1, dtype=np.int32)
+    goff = np.zeros(ng_cap + 1, dtype=np.int32)
+    glen = np.zeros(ng_cap, dtype=np.int32)
+    tau = C.c_float()
+    s = np.zeros((2, ng_cap), dtype=np.float32)
+    z = np.zeros((2, ng_cap), dtype=np.float32)
+    inv_s = np.zeros((2, ng_cap), dtype=np.float32)
+    D = np.zeros(2, dtype=np.float64)
+    rc_cls = np.zeros(rows, dtype=np.uint8)
+    rc = lib().dgqo_calibrate(_p(x), C.c_int64(rows), C.c_int32(Cc), C.c_int32(act_bits),
+                              C.c_int32(G), C.c_int32(P), C.c_int32(granule),
+                              C.c_int32(ng_cap), C.c_int32(kp_cap), _p(scal), _p(perm),
+                              _p(goff), _p(glen), C.byref(tau), _p(s), _p(z), _p(inv_s),
+                              _p(D), _p(rc_cls))
+    if rc != 0:
+        raise RuntimeError("oracle calibrate: capacity too small")
+    ng, kp = int(scal[0]), int(scal[1])
+    return Groups(C=Cc, act_bits=act_bits, G=G, P=P, NG=ng, Kp=kp,
+                  n_outlier_channels=int(scal[2]), n_regular_groups=int(scal[3]),
+                  dstar=int(scal[4]), n_class1_rows=int(scal[5]),
+                  perm=perm[:kp].copy(), goff=goff[:ng + 1].copy(), glen=glen[:ng].copy(),
+                  tau_pix=np.float32(tau.value),
+                  s=np.ascontiguousarray(s[:, :ng]), z=np.ascontiguousarray(z[:, :ng]),
+                  inv_s=np.ascontiguousarray(inv_s[:, :ng]),
+                  D_channel=float(D[0]), D_pixel=float(D[1]), cal_row_class=rc_cls)
+
+
+def quantize_act(g: Groups, x, want_dq: bool = False):
+    """Returns dict(q [rows,Kp] u8, cls [rows] u8, xdq [rows,C] f64, clip [rows,C] u8)."""
+    x = _f32(x)
+    rows = x.shape[0]
+    assert x.shape[1] == g.C
+    q = np.zeros((rows, g.Kp), dtype=np.uint8)
+    cls = np.zeros(rows, dtype=np.uint8)
+    xdq = np.zeros((rows, g.C), dtype=np.float64) if want_dq else None
+    clip = np.zeros((rows, g.C), dtype=np.uint8) if want_dq else None
+    lib().dgqo_quantize_act(_p(x), C.c_int64(rows), C.c_int32(g.C), C.c_int32(g.act_bits),
+                            C.c_int32(g.NG), C.c_int32(g.NG), _p(g.perm), _p(g.goff),
+                            _p(g.glen), C.c_float(float(g.tau_pix)), _p(g.s), _p(g.z),
+                            _p(g.inv_s), _p(q), _p(cls), _p(xdq), _p(clip))
+    return dict(q=q, cls=cls, xdq=xdq, clip=clip)
+
+
+def quantize_weight(w, w_bits: int):
+    w = _f32(w)
+    O, Cc = w.shape
+    wq = np.zeros((O, Cc), dtype=np.int8)
+    sw = np.zeros(O, dtype=np.float32)
+    lib().dgqo_quantize_weight(_p(w), C.c_int32(O), C.c_int32(Cc), C.c_int32(w_bits),
+                               _p(wq), _p(sw))
+    return wq, sw
+
+
+def linear(g: Groups, q, cls, wq, sw, bias=None, want_acc: bool = False):
+    """q [rows,Kp] u8, cls [rows] u8 -> (Y [rows,O] f32, acc [rows,O,NG] i32 or None)."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    cls = np.ascontiguousarray(cls, dtype=np.uint8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    sw = _f32(sw)
+    rows = q.shape[0]
+    O = wq.shape[0]
+    assert q.shape[1] == g.Kp and wq.shape[1] == g.C
+    y = np.zeros((rows, O), dtype=np.float32)
+    acc = np.zeros((rows, O, g.NG), dtype=np.int32) if want_acc else None
+    b = _f32(bias) if bias is not None else None
+    lib().dgqo_linear(_p(q), _p(cls), C.c_int64(rows), C.c_int32(g.C), C.c_int32(O),
+                      C.c_int32(g.act_bits), C.c_int32(g.NG), C.c_int32(g.NG), _p(g.perm),
+                      _p(g.goff), _p(g.glen), _p(g.s), _p(g.z), _p(wq), _p(sw), _p(b),
+                      _p(y), _p(acc))
+    return y, acc
+
+
+def attn_probs(Q, K, key_bias=None):
+    """Q [B,N,H,d], K [B,nk,H,d] -> A [B,H,N,nk] fp32."""
+    Q = _f32(Q)
+    K = _f32(K)
+    B, N, H, d = Q.shape
+    nk = K.shape[1]
+    kb = _f32(key_bias) if key_bias is not None else None
+    A = np.zeros((B, H, N, nk), dtype=np.float32)
+    lib().dgqo_attn_probs(_p(Q), _p(K), _p(kb), C.c_int32(B), C.c_int32(N), C.c_int32(H),
+                          C.c_int32(d), C.c_int32(nk), _p(A))
+    return A
+
+
+def xattn_logq(A, V, bits: int, want_ahat: bool = False):
+    """A [B,H,N,nk] fp32, V [B,nk,H,d] -> dict(s, codes, margin, ahat, out [B,N,H,d])."""
+    A = _f32(A)
+    V = _f32(V)
+    B, H, N, nk = A.shape
+    d = V.shape[3]
+    s = np.zeros(B, dtype=np.float32)
+    codes = np.zeros((B, H, N, nk - 1), dtype=np.uint8)
+    margin = np.zeros((B, H, N, nk - 1), dtype=np.float32)
+    ahat = np.zeros((B, H, N, nk), dtype=np.float64) if want_ahat else None
+    out = np.zeros((B, N, H, d), dtype=np.float32)
+    lib().dgqo_xattn_logq(_p(A), _p(V), C.c_int32(B), C.c_int32(N), C.c_int32(H),
+                          C.c_int32(d), C.c_int32(nk), C.c_int32(bits), _p(s), _p(codes),
+                          _p(margin), _p(ahat), _p(out))
+    return dict(s=s, codes=codes, margin=margin, ahat=ahat, out=out)
+
+
+def xattn(Q, K, V, key_bias, bits: int, want_ahat: bool = False):
+    A = attn_probs(Q, K, key_bias)
+    r = xattn_logq(A, V, bits, want_ahat)
+    r["A"] = A
+    return r
