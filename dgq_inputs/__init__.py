@@ -43,8 +43,8 @@ def linear_case(seed: int, B: int, N: int, C: int, O: int | None = None,
     """
     rng = np.random.default_rng(np.random.PCG64(seed))
     X = rng.standard_normal((B, N, C), dtype=np.float32)
-    oc = np.sort(rng.choice(C, n_outlier_channels(C), replace=False))
-    ot = np.sort(rng.choice(N, n_outlier_tokens(N), replace=False))
+    oc = np.sort(rng.choice(C, min(C, n_outlier_channels(C)), replace=False))
+    ot = np.sort(rng.choice(N, min(N, n_outlier_tokens(N)), replace=False))
     W = None
     if with_weight and O is not None:
         W = rng.standard_normal((O, C), dtype=np.float32)

@@ -1,0 +1,217 @@
+/*
+ * dgq.h -- C ABI of the MI355X (gfx950) DGQ quantized-inference library.
+ *
+ * DGQ = Distribution-aware Group Quantization for text-to-image diffusion
+ * models (arXiv 2501.04304).  The library implements the inference hot path:
+ *
+ *   dgq_calibrate_groups   offline: pixel classes, channel groups and the
+ *                          per-cell (s, z) table of one layer at one timestep
+ *   dgq_pack_weight        offline: per-output-channel integer weights laid out
+ *                          for the group structure
+ *   dgq_quantize_act       fused row-statistics + pixel-class + group affine
+ *                          quantizer, fp32 -> int8 / packed int4 codes
+ *   dgq_linear             grouped int8 x int8 -> int32 contraction on the
+ *                          matrix cores with a per-(pixel class, channel group)
+ *                          dequantization epilogue
+ *   dgq_xattn_logq         text cross-attention whose softmax probabilities,
+ *                          except the <start> column, are log2-quantized with a
+ *                          prompt-specific scale before the product with V
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer unless the comment says "host".
+ *     Tensors are row-major with the innermost dimension contiguous and a base
+ *     address aligned to 16 bytes (else DGQ_EALIGN).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     The three hot calls (quantize_act, linear, xattn_logq) only enqueue work:
+ *     they neither synchronise nor allocate.  The caller owns every tensor and
+ *     keeps it alive until the stream has passed the call.
+ *   - Return value: DGQ_OK or a negative dgq_status.  Nothing is enqueued when
+ *     an argument error is returned.  dgq_last_error() gives a host string for
+ *     the last failure on the calling thread.
+ *   - Handles (dgq_groups_t, dgq_weight_t) own small device tables; they are
+ *     immutable after creation, may be shared between streams, and are released
+ *     with dgq_groups_free / dgq_weight_free (which synchronise the device).
+ *
+ * Quantization grid.  Section 3.3 of the paper groups the vectors of ONE
+ * dimension d* in {channel, pixel} by their range and gives each group its own
+ * scale s_k = (max - min) / 2^b and offset z_k = min.  This library keeps both
+ * outlier kinds at once: rows (pixels) fall into P <= 2 classes by their range,
+ * channels into NG groups (regular groups of `group_size` channels in order of
+ * range, then the outlier cluster), and every cell (pixel class, channel group)
+ * has its own (s, z).  P = 1 is the paper's channel case, NG = 1 its pixel case.
+ */
+#ifndef DGQ_H
+#define DGQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dgq_status {
+    DGQ_OK = 0,
+    DGQ_EINVAL = -1,        /* null pointer, bad enum value, rows < 1 ...          */
+    DGQ_EALIGN = -2,        /* a tensor base is not 16-byte aligned                */
+    DGQ_ESHAPE = -3,        /* sizes inconsistent with the handle / each other     */
+    DGQ_EUNSUPPORTED = -4,  /* valid but outside what the kernels cover            */
+    DGQ_EHIP = -5,          /* a HIP runtime call failed                           */
+    DGQ_EWORKSPACE = -6     /* workspace missing or too small                      */
+} dgq_status;
+
+typedef struct dgq_groups dgq_groups_t; /* one (layer, timestep) entry of the S, Z tables */
+typedef struct dgq_weight dgq_weight_t;
+
+/* K granule: every channel group is padded to a multiple of this many
+   positions; padded positions carry code 0 and weight 0. */
+#define DGQ_K_GRANULE 64
+
+typedef struct dgq_groups_info {
+    int32_t channels;            /* C                                               */
+    int32_t act_bits;            /* 4 or 8                                          */
+    int32_t group_size;          /* G                                               */
+    int32_t n_pixel_classes;     /* P as requested (1 or 2)                         */
+    int32_t n_groups;            /* NG                                              */
+    int32_t k_padded;            /* K' = padded contraction length                  */
+    int32_t n_outlier_channels;  /* size of the upper range cluster                 */
+    int32_t n_regular_groups;    /* groups cut from the lower cluster               */
+    int32_t dstar;               /* argmax_d D_d: 0 = channel, 1 = pixel            */
+    int32_t code_offset;         /* stored code = q - code_offset (128 / 0)         */
+    int32_t n_class1_rows;       /* calibration rows in the outlier pixel class     */
+    float tau_pix;               /* row-range threshold (+inf: single class)        */
+    double d_channel, d_pixel;   /* D_d of Section 3.3                              */
+} dgq_groups_info_t;
+
+/*
+ * Calibration of one layer (Section 3.3: D_d, d*, K-means grouping by range,
+ * s_k and z_k).  x_cal: device fp32 [rows, channels], one row per pixel with the
+ * batch flattened into rows.
+ *   1. row range w_r = max_c - min_c; exact 1-D 2-means on {w_r} gives the
+ *      threshold tau_pix; class(r) = [w_r > tau_pix]        (n_pixel_classes == 2)
+ *   2. D_channel, D_pixel and d* over the whole tensor (reported)
+ *   3. channel range over class-0 rows; exact 1-D 2-means separates the outlier
+ *      cluster; each cluster, sorted by (range, index), is cut into blocks of
+ *      group_size channels; every block is padded to DGQ_K_GRANULE positions
+ *   4. per cell: s = (max - min) / 2^act_bits (1 if max == min), z = min; a cell
+ *      with no calibration rows copies class 0
+ * act_bits in {4, 8}; group_size a positive multiple of DGQ_K_GRANULE;
+ * channels >= 1; rows >= 1.  Blocks until the tables are built (the reductions
+ * run on `stream`, the clustering on the host).  *out receives a new handle.
+ */
+int dgq_calibrate_groups(const float *x_cal, int64_t rows, int32_t channels,
+                         int32_t act_bits, int32_t group_size,
+                         int32_t n_pixel_classes, void *stream,
+                         dgq_groups_t **out);
+
+/* Host copy of the scalar results.  info: host. */
+int dgq_groups_info(const dgq_groups_t *g, dgq_groups_info_t *info);
+
+/*
+ * Host copy of the tables (any pointer may be NULL to skip it); all host:
+ *   perm [K']   original channel at padded position j, -1 for padding
+ *   goff [NG+1] first padded position of each group (multiples of the granule)
+ *   glen [NG]   channels in each group
+ *   s, z [2*NG] cell tables, class-major: s[p*NG + g]
+ */
+int dgq_groups_tables(const dgq_groups_t *g, int32_t *perm, int32_t *goff,
+                      int32_t *glen, float *s, float *z);
+
+void dgq_groups_free(dgq_groups_t *g);
+
+/*
+ * Weight preparation for dgq_linear.  The paper leaves weight quantization to
+ * other methods (Section 4.1, "Weight quantization"); here it is
+ * per-output-channel symmetric round-to-nearest-even:
+ *   sw[o] = max_c |W[o,c]| / qmax (1 for an all-zero row), qmax = 127 (w_bits 8)
+ *   or 7 (w_bits 4);  wq = clamp(rne(W / sw), -qmax, qmax).
+ * The integer rows are permuted and padded to the K' order of `g`; the
+ * zero-point term of the dequantization
+ *   zb[p][o] = sw[o] * sum_g (z[p,g] + code_offset * s[p,g]) * (sum_{j in g} wq[o,j]) + bias[o]
+ * is precomputed per pixel class.
+ * w: device fp32 [out_channels, channels]; bias: device fp32 [out_channels] or
+ * NULL.  Blocks until done.  The handle stays tied to the group structure of g.
+ */
+int dgq_pack_weight(const dgq_groups_t *g, const float *w, const float *bias,
+                    int32_t out_channels, int32_t w_bits, void *stream,
+                    dgq_weight_t **out);
+
+/* Host copies for inspection: wq host int8 [out_channels, channels] in the
+   ORIGINAL channel order, sw host fp32 [out_channels]; either may be NULL. */
+int dgq_weight_tables(const dgq_weight_t *w, int8_t *wq, float *sw);
+
+void dgq_weight_free(dgq_weight_t *w);
+
+/*
+ * Activation quantizer (linear quantizer of Section 3.1 with the cell
+ * parameters of Section 3.3).  For every row r of x [rows, C]:
+ *   class p = [max_c x - min_c x > tau_pix]                 (decided at run time)
+ *   for every real padded position j in group g, c = perm[j]:
+ *     q = clamp(rne((x[r,c] - z[p,g]) * (1/s[p,g])), 0, 2^b - 1)
+ *     stored code = q - code_offset;  padding positions store 0.
+ * Subtraction and multiplication are separate fp32 operations (no FMA).
+ *   codes: act_bits 8 -> int8 [rows, K'];
+ *          act_bits 4 -> [rows, K'/2] bytes, position 2i in the low nibble and
+ *          2i+1 in the high nibble of byte i, each nibble the unsigned q.
+ *   row_class: uint8 [rows].
+ */
+int dgq_quantize_act(const dgq_groups_t *g, const float *x, int64_t rows,
+                     int8_t *codes, uint8_t *row_class, void *stream);
+
+/*
+ * Quantized linear layer: grouped integer contraction and dequantization.
+ *   acc[r,o,g] = sum_{j in g} code[r,j] * wq[o,j]                         (int32, exact)
+ *   y[r,o]     = sw[o] * sum_g s[class(r),g] * float(acc[r,o,g]) + zb[class(r)][o]
+ * (x_dq = s*(x_q) + z of Section 3.1 applied group by group; fp32 epilogue).
+ *   codes, row_class: as written by dgq_quantize_act with the same g
+ *   y: fp32 [rows, out_channels]
+ *   acc_dump: NULL, or int32 [rows, out_channels, NG] receiving every group
+ *             accumulator (debug / parity; slows the kernel down)
+ *   workspace: unused by the current kernels (dgq_linear_workspace_bytes
+ *             returns 0); pass NULL / 0.
+ */
+int dgq_linear(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes,
+               const uint8_t *row_class, int64_t rows, float *y,
+               int32_t *acc_dump, void *workspace, size_t workspace_bytes,
+               void *stream);
+
+size_t dgq_linear_workspace_bytes(const dgq_groups_t *g, const dgq_weight_t *w,
+                                  int64_t rows);
+
+/*
+ * Cross-attention with log2-quantized probabilities (Section 3.3,
+ * attention-aware quantization; log quantizer of Section 3.1).
+ *   L[b,h,i,j] = (q[b,i,h,:] . k[b,j,h,:]) / sqrt(d) + key_bias[j]
+ *   A = softmax_j(L) over all nk keys, fp32
+ *   scale_out[b] = s_b = max over h, i and j >= 1 of A      (prompt-specific scale)
+ *   code[b,h,i,j] = clamp(rne(-log2(A / s_b)), 0, 2^attn_bits - 1),  j >= 1;
+ *                   a probability that rounds to zero in fp32 gets 2^attn_bits - 1
+ *   out[b,i,h,:] = A[..,0] * v[b,0,h,:] + s_b * sum_{j>=1} 2^(-code) * v[b,j,h,:]
+ * Column 0 (the <start> token) bypasses the quantizer; no renormalisation.
+ *   q, out: fp32 [B, N, H, d];  k, v: fp32 [B, nk, H, d];  key_bias: fp32 [nk] or NULL
+ *   scale_out: fp32 [B] (written);  codes_dump: NULL or uint8 [B, H, N, nk-1]
+ *   workspace: device scratch of at least dgq_xattn_workspace_bytes(...) bytes,
+ *              16-byte aligned; contents are overwritten.
+ * Limits: 2 <= nk <= 128, 1 <= d <= 256, attn_bits in {4, 8}.
+ * Two kernels run back to back on `stream` (all probabilities must be known
+ * before any of them can be coded).
+ */
+int dgq_xattn_logq(const float *q, const float *k, const float *v,
+                   const float *key_bias, int32_t B, int32_t N, int32_t H,
+                   int32_t d, int32_t nk, int32_t attn_bits, float *out,
+                   float *scale_out, uint8_t *codes_dump, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+size_t dgq_xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d,
+                                 int32_t nk);
+
+/* Host string describing the last error on this thread ("" if none). */
+const char *dgq_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int dgq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGQ_H */

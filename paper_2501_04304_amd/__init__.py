@@ -1,0 +1,260 @@
+"""Python binding of libdgq.so (the MI355X DGQ quantized-inference library).
+
+Argument marshalling only: every function below forwards torch device
+tensors' pointers and sizes to the C entry point of the same name
+(include/dgq.h).  There is no CPU fallback: if the HIP library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdgq.so")
+
+DGQ_K_GRANULE = 64
+
+_lib = None
+
+
+class DgqError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("dgq error %d: %s" % (code, msg))
+        self.code = code
+
+
+class GroupsInfo(C.Structure):
+    _fields_ = [("channels", C.c_int32), ("act_bits", C.c_int32), ("group_size", C.c_int32),
+                ("n_pixel_classes", C.c_int32), ("n_groups", C.c_int32), ("k_padded", C.c_int32),
+                ("n_outlier_channels", C.c_int32), ("n_regular_groups", C.c_int32),
+                ("dstar", C.c_int32), ("code_offset", C.c_int32), ("n_class1_rows", C.c_int32),
+                ("tau_pix", C.c_float), ("d_channel", C.c_double), ("d_pixel", C.c_double)]
+
+
+def lib():
+    """Load libdgq.so; fail loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libdgq.so is not built: run `python -m paper_2501_04304_amd.build` "
+                "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        L.dgq_calibrate_groups.argtypes = [vp, i64, i32, i32, i32, i32, vp, C.POINTER(vp)]
+        L.dgq_groups_info.argtypes = [vp, C.POINTER(GroupsInfo)]
+        L.dgq_groups_tables.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.dgq_groups_free.argtypes = [vp]
+        L.dgq_groups_free.restype = None
+        L.dgq_pack_weight.argtypes = [vp, vp, vp, i32, i32, vp, C.POINTER(vp)]
+        L.dgq_weight_tables.argtypes = [vp, vp, vp]
+        L.dgq_weight_free.argtypes = [vp]
+        L.dgq_weight_free.restype = None
+        L.dgq_quantize_act.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.dgq_linear.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dgq_linear_workspace_bytes.argtypes = [vp, vp, i64]
+        L.dgq_linear_workspace_bytes.restype = sz
+        L.dgq_xattn_logq.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
+                                     vp, sz, vp]
+        L.dgq_xattn_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.dgq_xattn_workspace_bytes.restype = sz
+        L.dgq_last_error.restype = C.c_char_p
+        L.dgq_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise DgqError(rc, lib().dgq_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev(t, dtype, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dtype))
+    return t
+
+
+@dataclass
+class Groups:
+    """Owner of a dgq_groups_t handle."""
+    handle: int
+    info: GroupsInfo
+
+    def tables(self):
+        import numpy as np
+        ng, kp = self.info.n_groups, self.info.k_padded
+        perm = np.empty(kp, np.int32)
+        goff = np.empty(ng + 1, np.int32)
+        glen = np.empty(ng, np.int32)
+        s = np.empty((2, ng), np.float32)
+        z = np.empty((2, ng), np.float32)
+        _check(lib().dgq_groups_tables(self.handle, perm.ctypes.data, goff.ctypes.data,
+                                       glen.ctypes.data, s.ctypes.data, z.ctypes.data))
+        return dict(perm=perm, goff=goff, glen=glen, s=s, z=z)
+
+    def free(self):
+        if self.handle:
+            lib().dgq_groups_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+@dataclass
+class Weight:
+    """Owner of a dgq_weight_t handle."""
+    handle: int
+    groups: Groups
+    out_channels: int
+    w_bits: int
+
+    def tables(self):
+        import numpy as np
+        wq = np.empty((self.out_channels, self.groups.info.channels), np.int8)
+        sw = np.empty(self.out_channels, np.float32)
+        _check(lib().dgq_weight_tables(self.handle, wq.ctypes.data, sw.ctypes.data))
+        return dict(wq=wq, sw=sw)
+
+    def free(self):
+        if self.handle:
+            lib().dgq_weight_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def dgq_calibrate_groups(x_cal, act_bits: int, group_size: int, n_pixel_classes: int = 2,
+                         stream=None) -> Groups:
+    import torch
+    _dev(x_cal, torch.float32, "x_cal")
+    rows, ch = x_cal.shape
+    h = C.c_void_p()
+    _check(lib().dgq_calibrate_groups(_ptr(x_cal), rows, ch, act_bits, group_size,
+                                      n_pixel_classes, _stream(stream), C.byref(h)))
+    info = GroupsInfo()
+    _check(lib().dgq_groups_info(h, C.byref(info)))
+    return Groups(handle=h.value, info=info)
+
+
+def dgq_pack_weight(groups: Groups, w, bias, w_bits: int, stream=None) -> Weight:
+    import torch
+    _dev(w, torch.float32, "w")
+    if bias is not None:
+        _dev(bias, torch.float32, "bias")
+    O, ch = w.shape
+    if ch != groups.info.channels:
+        raise ValueError("w has %d input channels, the groups have %d" % (ch, groups.info.channels))
+    h = C.c_void_p()
+    _check(lib().dgq_pack_weight(groups.handle, _ptr(w), _ptr(bias), O, w_bits, _stream(stream),
+                                 C.byref(h)))
+    return Weight(handle=h.value, groups=groups, out_channels=O, w_bits=w_bits)
+
+
+def codes_shape(groups: Groups, rows: int):
+    kp = groups.info.k_padded
+    return (rows, kp if groups.info.act_bits == 8 else kp // 2)
+
+
+def dgq_quantize_act(groups: Groups, x, codes=None, row_class=None, stream=None):
+    """Returns (codes int8 [rows, K'] or packed [rows, K'/2], row_class uint8 [rows])."""
+    import torch
+    _dev(x, torch.float32, "x")
+    rows, ch = x.shape
+    if ch != groups.info.channels:
+        raise ValueError("x has %d channels, the groups have %d" % (ch, groups.info.channels))
+    if codes is None:
+        codes = torch.empty(codes_shape(groups, rows), dtype=torch.int8, device=x.device)
+    if row_class is None:
+        row_class = torch.empty(rows, dtype=torch.uint8, device=x.device)
+    _dev(codes, torch.int8, "codes")
+    _dev(row_class, torch.uint8, "row_class")
+    if tuple(codes.shape) != codes_shape(groups, rows) or row_class.numel() != rows:
+        raise ValueError("codes / row_class have the wrong shape")
+    _check(lib().dgq_quantize_act(groups.handle, _ptr(x), rows, _ptr(codes), _ptr(row_class),
+                                  _stream(stream)))
+    return codes, row_class
+
+
+def dgq_linear(groups: Groups, weight: Weight, codes, row_class, y=None, acc_dump=None,
+               stream=None):
+    """Returns y fp32 [rows, O]; acc_dump (optional) int32 [rows, O, NG] is filled in place."""
+    import torch
+    _dev(codes, torch.int8, "codes")
+    _dev(row_class, torch.uint8, "row_class")
+    rows = codes.shape[0]
+    if tuple(codes.shape) != codes_shape(groups, rows) or row_class.numel() != rows:
+        raise ValueError("codes / row_class have the wrong shape")
+    O = weight.out_channels
+    if y is None:
+        y = torch.empty((rows, O), dtype=torch.float32, device=codes.device)
+    _dev(y, torch.float32, "y")
+    if tuple(y.shape) != (rows, O):
+        raise ValueError("y has the wrong shape")
+    if acc_dump is not None:
+        _dev(acc_dump, torch.int32, "acc_dump")
+        if tuple(acc_dump.shape) != (rows, O, groups.info.n_groups):
+            raise ValueError("acc_dump has the wrong shape")
+    _check(lib().dgq_linear(groups.handle, weight.handle, _ptr(codes), _ptr(row_class), rows,
+                            _ptr(y), _ptr(acc_dump), None, 0, _stream(stream)))
+    return y
+
+
+def dgq_xattn_workspace_bytes(B, N, H, d, nk) -> int:
+    return int(lib().dgq_xattn_workspace_bytes(B, N, H, d, nk))
+
+
+def dgq_xattn_logq(q, k, v, key_bias, attn_bits: int, out=None, scale_out=None, codes_dump=None,
+                   workspace=None, stream=None):
+    """q [B,N,H,d], k/v [B,nk,H,d] -> (out [B,N,H,d], scale [B])."""
+    import torch
+    _dev(q, torch.float32, "q")
+    _dev(k, torch.float32, "k")
+    _dev(v, torch.float32, "v")
+    if key_bias is not None:
+        _dev(key_bias, torch.float32, "key_bias")
+    B, N, H, d = q.shape
+    nk = k.shape[1]
+    if tuple(k.shape) != (B, nk, H, d) or tuple(v.shape) != (B, nk, H, d):
+        raise ValueError("k / v have the wrong shape")
+    if key_bias is not None and key_bias.numel() != nk:
+        raise ValueError("key_bias has the wrong shape")
+    if out is None:
+        out = torch.empty_like(q)
+    if scale_out is None:
+        scale_out = torch.empty(B, dtype=torch.float32, device=q.device)
+    _dev(out, torch.float32, "out")
+    _dev(scale_out, torch.float32, "scale_out")
+    if codes_dump is not None:
+        _dev(codes_dump, torch.uint8, "codes_dump")
+        if tuple(codes_dump.shape) != (B, H, N, nk - 1):
+            raise ValueError("codes_dump has the wrong shape")
+    need = dgq_xattn_workspace_bytes(B, N, H, d, nk)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().dgq_xattn_logq(_ptr(q), _ptr(k), _ptr(v), _ptr(key_bias), B, N, H, d, nk,
+                                attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
+                                _ptr(workspace), wbytes, _stream(stream)))
+    return out, scale_out

@@ -1,0 +1,451 @@
+// Host side of the C ABI: argument checks, the calibration driver (range
+// reductions on the GPU, exact 1-D clustering and table construction on the
+// host), handle lifetime, and dispatch to the kernels.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <numeric>
+
+#include "dgq_internal.h"
+
+namespace dgq {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string &msg) { g_last_error = msg; }
+
+int hip_fail(hipError_t e, const char *what) {
+    set_error(std::string(what) + ": " + hipGetErrorString(e));
+    return DGQ_EHIP;
+}
+
+namespace {
+
+int fail(int code, const std::string &msg) {
+    set_error(msg);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct DevBuf {  // scoped device allocation for the blocking (offline) calls
+    void *p = nullptr;
+    ~DevBuf() {
+        if (p) (void)hipFree(p);
+    }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+    template <class T>
+    T *as() const { return static_cast<T *>(p); }
+};
+
+// Result of the exact two-cluster split of a 1-D sample (Section 3.3 groups
+// vectors "based on their range using K-means"; in one dimension the optimum
+// is a cut of the sorted sample, so it can be found exactly).
+struct Split {
+    int64_t n_lower = 0;         // size of the lower cluster (n if no split exists)
+    float tau = INFINITY;        // value > tau  <=>  upper cluster
+    std::vector<int64_t> order;  // indices sorted by (value, index)
+};
+
+// Every cut between two distinct neighbouring values is scored by the
+// within-cluster sum of squares computed from running sums of v and v^2 in
+// double, taken in sorted order; the first minimum wins.  The threshold is the
+// midpoint of the two cluster means, rounded to fp32 and clamped between the
+// two values it separates.  The order of the floating-point operations is part
+// of the definition: tau must be reproducible bit for bit.
+Split split_two_clusters(const std::vector<float> &v) {
+    Split sp;
+    const int64_t n = (int64_t)v.size();
+    sp.order.resize(n);
+    std::iota(sp.order.begin(), sp.order.end(), (int64_t)0);
+    std::sort(sp.order.begin(), sp.order.end(), [&](int64_t a, int64_t b) {
+        return v[a] < v[b] || (v[a] == v[b] && a < b);
+    });
+    sp.n_lower = n;
+    if (n < 2 || !(v[sp.order.front()] < v[sp.order.back()])) return sp;
+
+    double total = 0.0, total_sq = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const double x = v[sp.order[i]];
+        total = total + x;
+        total_sq = total_sq + x * x;
+    }
+    double run = 0.0, run_sq = 0.0, best_cost = 0.0, best_run = 0.0;
+    int64_t cut = -1;
+    for (int64_t left = 1; left < n; ++left) {
+        const double x = v[sp.order[left - 1]];
+        run = run + x;
+        run_sq = run_sq + x * x;
+        if (!(v[sp.order[left - 1]] < v[sp.order[left]])) continue;
+        const double rest = total - run, rest_sq = total_sq - run_sq;
+        const double cost_lo = run_sq - (run * run) / (double)left;
+        const double cost_hi = rest_sq - (rest * rest) / (double)(n - left);
+        const double cost = cost_lo + cost_hi;
+        if (cut < 0 || cost < best_cost) {
+            best_cost = cost;
+            best_run = run;
+            cut = left;
+        }
+    }
+    const double mean_lo = best_run / (double)cut;
+    const double mean_hi = (total - best_run) / (double)(n - cut);
+    float tau = (float)(0.5 * (mean_lo + mean_hi));
+    const float below = v[sp.order[cut - 1]];
+    const float above = std::nextafterf(v[sp.order[cut]], -INFINITY);
+    tau = std::max(tau, below);
+    tau = std::min(tau, above);
+    sp.tau = tau;
+    sp.n_lower = cut;
+    return sp;
+}
+
+// D_d of Section 3.3 from the per-vector maxima and minima along one dimension.
+double variability(const std::vector<float> &vmax, const std::vector<float> &vmin) {
+    const auto mx = std::minmax_element(vmax.begin(), vmax.end());
+    const auto mn = std::minmax_element(vmin.begin(), vmin.end());
+    return ((double)*mx.second - (double)*mx.first) + ((double)*mn.second - (double)*mn.first);
+}
+
+template <class T>
+int upload(T **dst, const std::vector<T> &src) {
+    DGQ_HIP(hipMalloc(reinterpret_cast<void **>(dst), std::max<size_t>(src.size() * sizeof(T), 16)));
+    if (!src.empty())
+        DGQ_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+    return DGQ_OK;
+}
+
+void release(Groups *g) {
+    if (!g) return;
+    (void)hipFree(g->d_perm);
+    (void)hipFree(g->d_chunk_z);
+    (void)hipFree(g->d_chunk_inv);
+    (void)hipFree(g->d_s);
+    (void)hipFree(g->d_zoff);
+    (void)hipFree(g->d_gchunk);
+    delete g;
+}
+
+void release(Weight *w) {
+    if (!w) return;
+    (void)hipFree(w->d_wq);
+    (void)hipFree(w->d_sw);
+    (void)hipFree(w->d_zb);
+    delete w;
+}
+
+}  // namespace
+}  // namespace dgq
+
+using namespace dgq;
+
+extern "C" {
+
+int dgq_version(void) { return 100; }
+
+const char *dgq_last_error(void) { return g_last_error.c_str(); }
+
+int dgq_calibrate_groups(const float *x_cal, int64_t rows, int32_t channels, int32_t act_bits,
+                         int32_t group_size, int32_t n_pixel_classes, void *stream,
+                         dgq_groups_t **out) {
+    if (!x_cal || !out) return fail(DGQ_EINVAL, "dgq_calibrate_groups: null pointer");
+    *out = nullptr;
+    if (rows < 1 || channels < 1) return fail(DGQ_EINVAL, "dgq_calibrate_groups: empty tensor");
+    if (act_bits != 4 && act_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_calibrate_groups: act_bits must be 4 or 8");
+    if (group_size < kGranule || group_size % kGranule)
+        return fail(DGQ_EINVAL, "dgq_calibrate_groups: group_size must be a positive multiple of 64");
+    if (n_pixel_classes != 1 && n_pixel_classes != 2)
+        return fail(DGQ_EINVAL, "dgq_calibrate_groups: n_pixel_classes must be 1 or 2");
+    if (!aligned16(x_cal)) return fail(DGQ_EALIGN, "dgq_calibrate_groups: x_cal not 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t C = channels;
+
+    // 1. per-pixel range -> pixel classes
+    DevBuf d_rmx, d_rmn;
+    DGQ_HIP(d_rmx.alloc(sizeof(float) * rows));
+    DGQ_HIP(d_rmn.alloc(sizeof(float) * rows));
+    DGQ_HIP(launch_row_minmax(x_cal, rows, C, d_rmx.as<float>(), d_rmn.as<float>(), st));
+    std::vector<float> rmx(rows), rmn(rows), width(rows);
+    DGQ_HIP(hipMemcpyAsync(rmx.data(), d_rmx.p, sizeof(float) * rows, hipMemcpyDeviceToHost, st));
+    DGQ_HIP(hipMemcpyAsync(rmn.data(), d_rmn.p, sizeof(float) * rows, hipMemcpyDeviceToHost, st));
+    DGQ_HIP(hipStreamSynchronize(st));
+    for (int64_t r = 0; r < rows; ++r) width[r] = rmx[r] - rmn[r];
+    float tau = INFINITY;
+    if (n_pixel_classes == 2) tau = split_two_clusters(width).tau;
+    int64_t n_cls[2] = {0, 0};
+    for (int64_t r = 0; r < rows; ++r) ++n_cls[width[r] > tau ? 1 : 0];
+
+    // 2. per-channel range, separately for the two pixel classes
+    const int32_t slabs = (int32_t)std::min<int64_t>(rows, 256);
+    DevBuf d_part;
+    DGQ_HIP(d_part.alloc(sizeof(float) * (size_t)slabs * 4 * C));
+    DGQ_HIP(launch_col_minmax_by_class(x_cal, rows, C, d_rmx.as<float>(), d_rmn.as<float>(), tau,
+                                       slabs, d_part.as<float>(), st));
+    std::vector<float> part((size_t)slabs * 4 * C);
+    DGQ_HIP(hipMemcpyAsync(part.data(), d_part.p, sizeof(float) * part.size(),
+                           hipMemcpyDeviceToHost, st));
+    DGQ_HIP(hipStreamSynchronize(st));
+    std::vector<float> cmx[2], cmn[2];
+    for (int p = 0; p < 2; ++p) {
+        cmx[p].assign(C, -INFINITY);
+        cmn[p].assign(C, INFINITY);
+    }
+    for (int32_t sl = 0; sl < slabs; ++sl) {
+        const float *pp = part.data() + (size_t)sl * 4 * C;
+        for (int p = 0; p < 2; ++p)
+            for (int32_t c = 0; c < C; ++c) {
+                cmx[p][c] = std::max(cmx[p][c], pp[(2 * p) * C + c]);
+                cmn[p][c] = std::min(cmn[p][c], pp[(2 * p + 1) * C + c]);
+            }
+    }
+
+    // 3. D_d over the whole tensor and the dimension it would select
+    std::vector<float> all_mx(C), all_mn(C);
+    for (int32_t c = 0; c < C; ++c) {
+        all_mx[c] = std::max(cmx[0][c], cmx[1][c]);
+        all_mn[c] = std::min(cmn[0][c], cmn[1][c]);
+    }
+    const double d_channel = variability(all_mx, all_mn);
+    const double d_pixel = variability(rmx, rmn);
+
+    // 4. channel groups: outlier cluster by range over class-0 pixels, then blocks of G
+    std::vector<float> cw(C);
+    for (int32_t c = 0; c < C; ++c) cw[c] = cmx[0][c] - cmn[0][c];
+    const Split cs = split_two_clusters(cw);
+    Groups *g = new (std::nothrow) Groups();
+    if (!g) return fail(DGQ_EINVAL, "dgq_calibrate_groups: out of host memory");
+    int32_t n_regular_groups = 0;
+    g->goff.push_back(0);
+    auto cut_cluster = [&](int64_t begin, int64_t end) {
+        int32_t made = 0;
+        for (int64_t at = begin; at < end; at += group_size) {
+            const int32_t len = (int32_t)std::min<int64_t>(group_size, end - at);
+            const int32_t padded = (len + kGranule - 1) / kGranule * kGranule;
+            for (int32_t j = 0; j < padded; ++j)
+                g->perm.push_back(j < len ? (int32_t)cs.order[at + j] : -1);
+            g->glen.push_back(len);
+            g->goff.push_back((int32_t)g->perm.size());
+            ++made;
+        }
+        return made;
+    };
+    n_regular_groups = cut_cluster(0, cs.n_lower);
+    cut_cluster(cs.n_lower, C);
+    const int32_t NG = (int32_t)g->glen.size();
+    const int32_t Kp = (int32_t)g->perm.size();
+
+    // 5. cell parameters: s = (max - min) / 2^b, z = min
+    const float levels = (float)(1 << act_bits);
+    g->s.assign(2 * NG, 1.0f);
+    g->z.assign(2 * NG, 0.0f);
+    g->inv_s.assign(2 * NG, 1.0f);
+    for (int p = 0; p < 2; ++p)
+        for (int32_t k = 0; k < NG; ++k) {
+            float sc, zp;
+            if (n_cls[p] == 0) {
+                sc = g->s[k];
+                zp = g->z[k];
+            } else {
+                float mx = -INFINITY, mn = INFINITY;
+                for (int32_t j = 0; j < g->glen[k]; ++j) {
+                    const int32_t c = g->perm[g->goff[k] + j];
+                    mx = std::max(mx, cmx[p][c]);
+                    mn = std::min(mn, cmn[p][c]);
+                }
+                sc = mx > mn ? (mx - mn) / levels : 1.0f;
+                zp = mn;
+            }
+            g->s[p * NG + k] = sc;
+            g->z[p * NG + k] = zp;
+            g->inv_s[p * NG + k] = 1.0f / sc;
+        }
+
+    dgq_groups_info_t &in = g->info;
+    in.channels = C;
+    in.act_bits = act_bits;
+    in.group_size = group_size;
+    in.n_pixel_classes = n_pixel_classes;
+    in.n_groups = NG;
+    in.k_padded = Kp;
+    in.n_outlier_channels = (int32_t)(C - cs.n_lower);
+    in.n_regular_groups = n_regular_groups;
+    in.dstar = d_pixel > d_channel ? 1 : 0;
+    in.code_offset = act_bits == 8 ? 128 : 0;
+    in.n_class1_rows = (int32_t)n_cls[1];
+    in.tau_pix = tau;
+    in.d_channel = d_channel;
+    in.d_pixel = d_pixel;
+    g->n_chunks = Kp / kGranule;
+    (void)hipGetDevice(&g->device);
+
+    // 6. device tables
+    std::vector<float> chunk_z(2 * (size_t)g->n_chunks), chunk_inv(2 * (size_t)g->n_chunks);
+    std::vector<int32_t> gchunk(NG + 1);
+    for (int32_t k = 0; k <= NG; ++k) gchunk[k] = g->goff[k] / kGranule;
+    for (int p = 0; p < 2; ++p)
+        for (int32_t k = 0; k < NG; ++k)
+            for (int32_t ch = gchunk[k]; ch < gchunk[k + 1]; ++ch) {
+                chunk_z[(size_t)p * g->n_chunks + ch] = g->z[p * NG + k];
+                chunk_inv[(size_t)p * g->n_chunks + ch] = g->inv_s[p * NG + k];
+            }
+    int rc = upload(&g->d_perm, g->perm);
+    if (rc == DGQ_OK) rc = upload(&g->d_chunk_z, chunk_z);
+    if (rc == DGQ_OK) rc = upload(&g->d_chunk_inv, chunk_inv);
+    if (rc == DGQ_OK) rc = upload(&g->d_s, g->s);
+    if (rc == DGQ_OK) rc = upload(&g->d_zoff, g->z);
+    if (rc == DGQ_OK) rc = upload(&g->d_gchunk, gchunk);
+    if (rc != DGQ_OK) {
+        release(g);
+        return rc;
+    }
+    *out = reinterpret_cast<dgq_groups_t *>(g);
+    return DGQ_OK;
+}
+
+int dgq_groups_info(const dgq_groups_t *h, dgq_groups_info_t *info) {
+    if (!h || !info) return fail(DGQ_EINVAL, "dgq_groups_info: null pointer");
+    *info = reinterpret_cast<const Groups *>(h)->info;
+    return DGQ_OK;
+}
+
+int dgq_groups_tables(const dgq_groups_t *h, int32_t *perm, int32_t *goff, int32_t *glen, float *s,
+                      float *z) {
+    if (!h) return fail(DGQ_EINVAL, "dgq_groups_tables: null handle");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    if (perm) std::memcpy(perm, g->perm.data(), g->perm.size() * sizeof(int32_t));
+    if (goff) std::memcpy(goff, g->goff.data(), g->goff.size() * sizeof(int32_t));
+    if (glen) std::memcpy(glen, g->glen.data(), g->glen.size() * sizeof(int32_t));
+    if (s) std::memcpy(s, g->s.data(), g->s.size() * sizeof(float));
+    if (z) std::memcpy(z, g->z.data(), g->z.size() * sizeof(float));
+    return DGQ_OK;
+}
+
+void dgq_groups_free(dgq_groups_t *h) {
+    if (!h) return;
+    (void)hipDeviceSynchronize();
+    release(reinterpret_cast<Groups *>(h));
+}
+
+int dgq_pack_weight(const dgq_groups_t *h, const float *w, const float *bias, int32_t out_channels,
+                    int32_t w_bits, void *stream, dgq_weight_t **out) {
+    if (!h || !w || !out) return fail(DGQ_EINVAL, "dgq_pack_weight: null pointer");
+    *out = nullptr;
+    if (out_channels < 1) return fail(DGQ_EINVAL, "dgq_pack_weight: out_channels < 1");
+    if (w_bits != 4 && w_bits != 8) return fail(DGQ_EINVAL, "dgq_pack_weight: w_bits must be 4 or 8");
+    if (!aligned16(w) || (bias && !aligned16(bias)))
+        return fail(DGQ_EALIGN, "dgq_pack_weight: tensor not 16-byte aligned");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Weight *wt = new (std::nothrow) Weight();
+    if (!wt) return fail(DGQ_EINVAL, "dgq_pack_weight: out of host memory");
+    wt->groups = g;
+    wt->O = out_channels;
+    wt->O_pad = (out_channels + kTileO - 1) / kTileO * kTileO;
+    wt->C = g->info.channels;
+    wt->Kp = g->info.k_padded;
+    wt->w_bits = w_bits;
+    (void)hipGetDevice(&wt->device);
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&wt->d_wq), (size_t)wt->O_pad * wt->Kp);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&wt->d_sw), sizeof(float) * wt->O_pad);
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void **>(&wt->d_zb), sizeof(float) * 2 * wt->O_pad);
+    if (e == hipSuccess)
+        e = launch_pack_weight(w, bias, wt->O, wt->O_pad, wt->C, wt->Kp, g->info.n_groups, w_bits,
+                               g->info.code_offset, g->d_perm, g->d_gchunk, g->d_s, g->d_zoff,
+                               wt->d_wq, wt->d_sw, wt->d_zb, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+        release(wt);
+        return hip_fail(e, "dgq_pack_weight");
+    }
+    *out = reinterpret_cast<dgq_weight_t *>(wt);
+    return DGQ_OK;
+}
+
+int dgq_weight_tables(const dgq_weight_t *h, int8_t *wq, float *sw) {
+    if (!h) return fail(DGQ_EINVAL, "dgq_weight_tables: null handle");
+    const Weight *w = reinterpret_cast<const Weight *>(h);
+    if (sw) DGQ_HIP(hipMemcpy(sw, w->d_sw, sizeof(float) * w->O, hipMemcpyDeviceToHost));
+    if (wq) {
+        DevBuf tmp;
+        const size_t bytes = (size_t)w->O * w->C;
+        DGQ_HIP(tmp.alloc(bytes));
+        DGQ_HIP(hipMemset(tmp.p, 0, bytes));
+        DGQ_HIP(launch_unpack_weight(w->d_wq, w->O, w->C, w->Kp, w->groups->d_perm,
+                                     tmp.as<int8_t>(), nullptr));
+        DGQ_HIP(hipDeviceSynchronize());
+        DGQ_HIP(hipMemcpy(wq, tmp.p, bytes, hipMemcpyDeviceToHost));
+    }
+    return DGQ_OK;
+}
+
+void dgq_weight_free(dgq_weight_t *h) {
+    if (!h) return;
+    (void)hipDeviceSynchronize();
+    release(reinterpret_cast<Weight *>(h));
+}
+
+int dgq_quantize_act(const dgq_groups_t *h, const float *x, int64_t rows, int8_t *codes,
+                     uint8_t *row_class, void *stream) {
+    if (!h || !x || !codes || !row_class) return fail(DGQ_EINVAL, "dgq_quantize_act: null pointer");
+    if (rows < 1) return fail(DGQ_EINVAL, "dgq_quantize_act: rows < 1");
+    if (!aligned16(x) || !aligned16(codes))
+        return fail(DGQ_EALIGN, "dgq_quantize_act: tensor not 16-byte aligned");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    if ((size_t)g->info.channels * 16 > 160 * 1024)
+        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act: more than 10240 channels");
+    DGQ_HIP(launch_quantize_act(*g, x, rows, codes, row_class, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+size_t dgq_linear_workspace_bytes(const dgq_groups_t *, const dgq_weight_t *, int64_t) { return 0; }
+
+int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *codes,
+               const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump, void *workspace,
+               size_t workspace_bytes, void *stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!h || !hw || !codes || !row_class || !y) return fail(DGQ_EINVAL, "dgq_linear: null pointer");
+    if (rows < 1) return fail(DGQ_EINVAL, "dgq_linear: rows < 1");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    const Weight *w = reinterpret_cast<const Weight *>(hw);
+    if (w->groups != g)
+        return fail(DGQ_ESHAPE, "dgq_linear: weight was packed for a different group handle");
+    if (!aligned16(codes) || !aligned16(y) || (acc_dump && !aligned16(acc_dump)))
+        return fail(DGQ_EALIGN, "dgq_linear: tensor not 16-byte aligned");
+    if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear: too many output tiles");
+    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump,
+                          static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+size_t dgq_xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk) {
+    return xattn_workspace_bytes(B, N, H, d, nk);
+}
+
+int dgq_xattn_logq(const float *q, const float *k, const float *v, const float *key_bias, int32_t B,
+                   int32_t N, int32_t H, int32_t d, int32_t nk, int32_t attn_bits, float *out,
+                   float *scale_out, uint8_t *codes_dump, void *workspace, size_t workspace_bytes,
+                   void *stream) {
+    if (!q || !k || !v || !out || !scale_out) return fail(DGQ_EINVAL, "dgq_xattn_logq: null pointer");
+    if (B < 1 || N < 1 || H < 1) return fail(DGQ_EINVAL, "dgq_xattn_logq: empty tensor");
+    if (attn_bits != 4 && attn_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq: attn_bits must be 4 or 8");
+    if (nk < 2 || nk > 128 || d < 1 || d > 256)
+        return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq: needs 2 <= nk <= 128 and 1 <= d <= 256");
+    if (B > 65535 || H > 65535) return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq: B or H above 65535");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) ||
+        (key_bias && !aligned16(key_bias)))
+        return fail(DGQ_EALIGN, "dgq_xattn_logq: tensor not 16-byte aligned");
+    const size_t need = xattn_workspace_bytes(B, N, H, d, nk);
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace)))
+        return fail(DGQ_EWORKSPACE, "dgq_xattn_logq: workspace missing, too small or misaligned");
+    DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
+                         workspace, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the host API and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "dgq.h"
+
+namespace dgq {
+
+constexpr int kGranule = DGQ_K_GRANULE;  // positions per K chunk
+constexpr int kTileO = 128;              // GEMM output-channel tile; weights are padded to it
+
+// One (layer, timestep) entry of the quantization tables.
+struct Groups {
+    dgq_groups_info_t info{};
+    int32_t n_chunks = 0;  // K' / kGranule
+    // host copies
+    std::vector<int32_t> perm, goff, glen;
+    std::vector<float> s, z, inv_s;  // [2][NG]
+    // device tables
+    int32_t *d_perm = nullptr;     // [K'] original channel or -1
+    float *d_chunk_z = nullptr;    // [2][n_chunks]  offset of the chunk's group
+    float *d_chunk_inv = nullptr;  // [2][n_chunks]  1/s of the chunk's group
+    float *d_s = nullptr;          // [2][NG]
+    float *d_zoff = nullptr;       // [2][NG]  z + code_offset * s (double -> fp32 not used; see pack)
+    int32_t *d_gchunk = nullptr;   // [NG+1] first chunk of each group
+    int device = 0;
+};
+
+struct Weight {
+    const Groups *groups = nullptr;
+    int32_t O = 0, O_pad = 0, C = 0, Kp = 0, w_bits = 8;
+    int8_t *d_wq = nullptr;  // [O_pad][K'] permuted + padded rows
+    float *d_sw = nullptr;   // [O_pad]
+    float *d_zb = nullptr;   // [2][O_pad]
+    int device = 0;
+};
+
+void set_error(const std::string &msg);
+int hip_fail(hipError_t e, const char *what);
+
+#define DGQ_HIP(call)                                          \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return ::dgq::hip_fail(e_, #call); \
+    } while (0)
+
+// ---- kernel launchers (each returns a hipError_t from the launch) ----------
+
+// Per-row max and min of x [rows, C].
+hipError_t launch_row_minmax(const float *x, int64_t rows, int32_t C, float *rmx,
+                             float *rmn, hipStream_t st);
+
+// Per-class channel max/min partials: part [slabs][4][C] = (max0, min0, max1, min1),
+// class of row r = [rmx[r] - rmn[r] > tau].
+hipError_t launch_col_minmax_by_class(const float *x, int64_t rows, int32_t C,
+                                      const float *rmx, const float *rmn, float tau,
+                                      int32_t slabs, float *part, hipStream_t st);
+
+// Per-output-channel weight quantization into the K' layout plus the zero-point term.
+hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int32_t O_pad,
+                              int32_t C, int32_t Kp, int32_t NG, int32_t w_bits,
+                              int32_t code_offset, const int32_t *perm,
+                              const int32_t *gchunk, const float *s, const float *z,
+                              int8_t *wq, float *sw, float *zb, hipStream_t st);
+
+// Inverse of the K' layout: wq_out [O][C] original order.
+hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t Kp,
+                                const int32_t *perm, int8_t *wq_out, hipStream_t st);
+
+hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
+                               uint8_t *row_class, hipStream_t st);
+
+hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
+                         const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
+                         hipStream_t st);
+
+hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
+                        int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
+                        float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
+                        hipStream_t st);
+
+size_t xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk);
+
+}  // namespace dgq

@@ -1,0 +1,76 @@
+"""The C-ABI library loads and exports every symbol include/dgq.h declares;
+argument errors are reported without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2501_04304_amd as dgq
+    if not os.path.exists(dgq.LIB_PATH):
+        from paper_2501_04304_amd import build
+        build.build()
+    return dgq.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dgq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dgq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_entry_points():
+    syms = declared_symbols()
+    for s in ("dgq_calibrate_groups", "dgq_quantize_act", "dgq_linear", "dgq_xattn_logq"):
+        assert s in syms
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for s in declared_symbols():
+        assert hasattr(lib, s), s
+
+
+def test_version_and_error_string(lib):
+    assert lib.dgq_version() >= 100
+    assert isinstance(lib.dgq_last_error(), bytes)
+
+
+def test_argument_errors_without_gpu(lib):
+    # null pointers are rejected before any HIP call
+    assert lib.dgq_quantize_act(None, None, 4, None, None, None) == -1
+    assert b"null" in lib.dgq_last_error()
+    assert lib.dgq_linear(None, None, None, None, 4, None, None, None, 0, None) == -1
+    h = C.c_void_p()
+    assert lib.dgq_calibrate_groups(None, 4, 64, 8, 64, 2, None, C.byref(h)) == -1
+    buf = (C.c_float * 64)()
+    p = C.cast(buf, C.c_void_p)
+    assert lib.dgq_calibrate_groups(p, 1, 64, 5, 64, 2, None, C.byref(h)) == -1  # act_bits
+    assert lib.dgq_calibrate_groups(p, 1, 64, 8, 96, 2, None, C.byref(h)) == -1  # group size
+    assert lib.dgq_calibrate_groups(p, 1, 64, 8, 64, 3, None, C.byref(h)) == -1  # classes
+    assert lib.dgq_calibrate_groups(p, 0, 64, 8, 64, 2, None, C.byref(h)) == -1  # empty
+    assert lib.dgq_xattn_logq(p, p, p, None, 1, 1, 1, 8, 77, 5, p, p, None, None, 0, None) == -1
+    assert lib.dgq_xattn_logq(p, p, p, None, 1, 1, 1, 8, 1, 8, p, p, None, None, 0, None) == -4
+    assert lib.dgq_xattn_logq(p, p, p, None, 1, 1, 1, 300, 77, 8, p, p, None, None, 0, None) == -4
+    assert lib.dgq_xattn_logq(p, p, p, None, 0, 1, 1, 8, 77, 8, p, p, None, None, 0, None) == -1
+
+
+def test_binding_names_match_the_abi():
+    import paper_2501_04304_amd as dgq
+    for s in ("dgq_calibrate_groups", "dgq_pack_weight", "dgq_quantize_act", "dgq_linear",
+              "dgq_xattn_logq", "dgq_xattn_workspace_bytes"):
+        assert callable(getattr(dgq, s))
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2501_04304_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "dgq_oracle" not in text, f

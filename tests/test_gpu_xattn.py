@@ -1,0 +1,145 @@
+"""GPU parity of the log2-quantized cross-attention against the CPU oracle.
+
+Codes are compared bit-exactly on margin-guarded inputs (oracle/guard.py: no
+rounding decision within 2^-13 log2 units of a boundary); on raw inputs every
+element whose oracle margin is at least that large must still match and the
+few others may differ by one step.  The prompt scale is an fp32 output
+(relative 1e-6), the product is held to 1e-4 * max|ref|."""
+import numpy as np
+import pytest
+
+import dgq_inputs as di
+from support import assert_close_fp32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgq():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2501_04304_amd as m
+    m.lib()
+    return m
+
+
+def _dev(a):
+    import torch
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _gpu(dgq, c, bits, use_bias=True):
+    import torch
+    B, N, H, d = c["Q"].shape
+    nk = c["K"].shape[1]
+    codes = torch.full((B, H, N, nk - 1), 0xEE, dtype=torch.uint8, device="cuda")
+    out, s = dgq.dgq_xattn_logq(_dev(c["Q"]), _dev(c["K"]), _dev(c["V"]),
+                                _dev(c["key_bias"]) if use_bias else None, bits,
+                                codes_dump=codes)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), s.cpu().numpy(), codes.cpu().numpy()
+
+
+def _compare(dgq, oracle, c, bits, exact=True, use_bias=True):
+    from oracle.guard import DELTA
+    ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"] if use_bias else None, bits)
+    out, s, codes = _gpu(dgq, c, bits, use_bias)
+    assert np.all(np.abs(s - ref["s"]) <= 1e-6 * ref["s"])
+    safe = ref["margin"] >= DELTA
+    assert np.array_equal(codes[safe], ref["codes"][safe])
+    if exact:
+        assert safe.all(), "guarded inputs must have no marginal element"
+        assert np.array_equal(codes, ref["codes"])
+        assert_close_fp32(out, ref["out"], "out")
+    else:
+        diff = np.abs(codes.astype(int) - ref["codes"].astype(int))
+        assert diff.max() <= 1
+        assert (~safe).mean() < 1e-3
+    # codes without the dump buffer give the same product
+    import torch
+    out2, s2 = dgq.dgq_xattn_logq(_dev(c["Q"]), _dev(c["K"]), _dev(c["V"]),
+                                  _dev(c["key_bias"]) if use_bias else None, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(out2.cpu().numpy(), out) and np.array_equal(s2.cpu().numpy(), s)
+
+
+SHAPES = [
+    # B, N, H, d, nk
+    (2, 300, 3, 40, 77),   # ragged query tile
+    (1, 64, 2, 64, 77),
+    (2, 70, 2, 37, 77),    # head dim not a multiple of 4
+    (1, 33, 1, 160, 77),
+    (1, 257, 2, 8, 10),    # few keys
+    (1, 40, 2, 40, 100),   # more than 80 keys
+    (3, 1, 1, 16, 2),      # one query, one quantized key
+]
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("B,N,H,d,nk", SHAPES)
+def test_guarded_shapes(dgq, oracle, B, N, H, d, nk, bits):
+    from oracle.guard import guarded_attention_case
+    c, _ = guarded_attention_case(700 + d + nk, B, N, H, d, nk=nk, bits_list=(bits,))
+    _compare(dgq, oracle, c, bits, exact=True)
+
+
+def test_without_key_bias(dgq, oracle):
+    from oracle.guard import guarded_attention_case
+    c, _ = guarded_attention_case(11, 2, 96, 2, 40, bits_list=(8,))
+    c = dict(c)
+    c["key_bias"] = np.zeros_like(c["key_bias"])
+    # the guard ran with the boost; re-guard on the unboosted logits via the raw-input rule
+    _compare(dgq, oracle, c, 8, exact=False, use_bias=False)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_raw_inputs_only_marginal_elements_may_differ(dgq, oracle, bits):
+    c = di.attention_case(12, 2, 512, 4, 40)
+    _compare(dgq, oracle, c, bits, exact=False)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_config3_full(dgq, oracle, bits):
+    """64x64 latent: batch 2, 8 heads, 4096 queries x 77 keys, head dim 40."""
+    from oracle.guard import guarded_attention_case
+    name, B, N, H, d, nk, d_ctx = di.config3()["attention"][0]
+    c, n_redrawn = guarded_attention_case(3000, B, N, H, d, nk=nk, d_ctx=d_ctx, bits_list=(4, 8))
+    assert n_redrawn < 0.1 * B * N * H
+    _compare(dgq, oracle, c, bits, exact=True)
+
+
+def test_config5_shape_sampled(dgq, oracle):
+    """SDXL-scale launch shape (16 prompts, 10 heads, d = 64); the oracle checks
+    two whole prompts, which is what a per-prompt scale allows."""
+    import torch
+    name, B, N, H, d, nk, d_ctx = di.config5()["attention"][0]
+    c = di.attention_case(5000, B, N, H, d, nk=nk, d_ctx=d_ctx)
+    from oracle.guard import DELTA
+    out, s, codes = _gpu(dgq, c, 8)
+    for b in (0, B - 1):
+        sub = {k: (v[b:b + 1] if k != "key_bias" else v) for k, v in c.items()}
+        ref = oracle.xattn(sub["Q"], sub["K"], sub["V"], sub["key_bias"], 8)
+        assert abs(s[b] - ref["s"][0]) <= 1e-6 * ref["s"][0]
+        safe = ref["margin"][0] >= DELTA
+        assert np.array_equal(codes[b][safe], ref["codes"][0][safe])
+        assert np.abs(codes[b].astype(int) - ref["codes"][0].astype(int)).max() <= 1
+        # rows without a marginal element must match to the fp32 tolerance
+        good = np.transpose(safe.all(-1), (1, 0))  # [N, H]
+        err = np.abs(out[b] - ref["out"][0])[good]
+        assert err.max() <= 1e-4 * np.abs(ref["out"][0]).max()
+    torch.cuda.synchronize()
+
+
+def test_scale_buffer_is_reset_between_calls(dgq, oracle):
+    """The prompt maximum is accumulated with atomics; a second call with smaller
+    probabilities must not see the first call's maximum."""
+    import torch
+    c1 = di.attention_case(21, 1, 64, 2, 40, start_boost=0.0)
+    c2 = di.attention_case(22, 1, 64, 2, 40, start_boost=12.0)
+    s_buf = torch.empty(1, dtype=torch.float32, device="cuda")
+    for c in (c1, c2):
+        out, s = dgq.dgq_xattn_logq(_dev(c["Q"]), _dev(c["K"]), _dev(c["V"]), _dev(c["key_bias"]),
+                                    8, scale_out=s_buf)
+        torch.cuda.synchronize()
+        ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8)
+        assert abs(s.item() - ref["s"][0]) <= 1e-6 * ref["s"][0]
