@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the DGQ quantized-inference hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input of
+the chosen workload: for every (activation bits, weight bits) mode, every linear
+layer runs dgq_quantize_act + dgq_linear; every cross-attention runs
+dgq_xattn_logq at each code width.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config5|config2+3]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
+METRIC = "dgq_linear int8 TOPS (% MFMA peak) + xattn_logq GB/s (% HBM), 1 MI355X"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config5", choices=["config5", "config2+3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-batch", type=int, default=2,
+                    help="batch elements of fresh data used for (untimed) calibration")
+    return ap.parse_args()
+
+
+def workload(name):
+    import dgq_inputs as di
+    if name == "config5":
+        c = di.config5()
+        desc = ("config5: SDXL-scale sweep, 1024x1024, batch 8x2; linears [65536x640] and "
+                "[16384x1280] (q,k,v,out, text k/v from 2048, ff.in, ff.out), G=128, A8W8 and "
+                "A4W8; cross-attention 16x10 heads x 4096 queries x 77 keys, d=64, 4- and 8-bit codes")
+        return c, desc
+    c2, c3 = di.config2(), di.config3()
+    c = dict(seed=c2["seed"], linears=c2["linears"], modes=c2["modes"],
+             attention=c3["attention"], attn_bits=c3["attn_bits"])
+    desc = ("config2+3: 64x64 latent of SD-v1.4, batch 2; linears [8192x320] (q,k,v,out, ff.in, "
+            "ff.out), G=64, A8W8 and A4W8; cross-attention 2x8 heads x 4096 x 77, d=40")
+    return c, desc
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused); "
+              "the one-GPU figure is the whole-job figure." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import dgq_inputs as di
+    import paper_2501_04304_amd as dgq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dgq.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg, desc = workload(args.workload)
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---------------- set-up (untimed): inputs, calibration, weights, outputs -------------
+    t_setup = time.time()
+    layers = []
+    for li, (name, M, B, N, C, O, G) in enumerate(cfg["linears"]):
+        seed = di.layer_seed(cfg["seed"], li)
+        run = di.linear_case(seed, B, N, C, O)
+        cal = di.linear_case(seed, min(B, args.calib_batch), N, C, O, calib=True, with_weight=False)
+        x = up(run["X"])
+        w = up(run["W"])
+        xc = up(cal["X"])
+        ent = dict(name=name, M=M, C=C, O=O, G=G, x=x, modes={})
+        for (ab, wb) in cfg["modes"]:
+            g = dgq.dgq_calibrate_groups(xc, ab, G, 2)
+            wt = dgq.dgq_pack_weight(g, w, None, wb)
+            codes = torch.empty(dgq.codes_shape(g, M), dtype=torch.int8, device=dev)
+            cls = torch.empty(M, dtype=torch.uint8, device=dev)
+            ent["modes"][(ab, wb)] = dict(g=g, wt=wt, codes=codes, cls=cls, Kp=g.info.k_padded)
+        ent["y"] = torch.empty((M, O), dtype=torch.float32, device=dev)
+        del w, xc
+        layers.append(ent)
+    attns = []
+    for ai, (name, B, N, H, d, nk, d_ctx) in enumerate(cfg["attention"]):
+        c = di.attention_case(cfg["seed"] + 500 + ai, B, N, H, d, nk=nk, d_ctx=d_ctx)
+        attns.append(dict(name=name, B=B, N=N, H=H, d=d, nk=nk, q=up(c["Q"]), k=up(c["K"]),
+                          v=up(c["V"]), kb=up(c["key_bias"]),
+                          out=torch.empty((B, N, H, d), dtype=torch.float32, device=dev),
+                          s=torch.empty(B, dtype=torch.float32, device=dev)))
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    # ---------------- the step, with HIP events around every call ------------------------
+    stream = torch.cuda.current_stream()
+    calls = []  # (kind, key, algorithmic units)
+
+    def plan():
+        for (ab, wb) in cfg["modes"]:
+            for ent in layers:
+                m = ent["modes"][(ab, wb)]
+                qbytes = ent["M"] * ent["C"] * 4 + ent["M"] * m["Kp"] * (1 if ab == 8 else 0.5) + ent["M"]
+                calls.append(("quantize_a%d" % ab, (ent, m), qbytes))
+                calls.append(("linear_a%d" % ab, (ent, m), 2.0 * ent["M"] * ent["C"] * ent["O"]))
+        for bits in cfg["attn_bits"]:
+            for a in attns:
+                abytes = 2.0 * a["B"] * a["N"] * a["H"] * a["d"] * 4  # Q read once + Out written
+                calls.append(("xattn_b%d" % bits, (a, bits), abytes))
+    plan()
+
+    def run_call(kind, key):
+        if kind.startswith("quantize"):
+            ent, m = key
+            dgq.dgq_quantize_act(m["g"], ent["x"], codes=m["codes"], row_class=m["cls"])
+        elif kind.startswith("linear"):
+            ent, m = key
+            dgq.dgq_linear(m["g"], m["wt"], m["codes"], m["cls"], y=ent["y"])
+        else:
+            a, bits = key
+            dgq.dgq_xattn_logq(a["q"], a["k"], a["v"], a["kb"], bits, out=a["out"], scale_out=a["s"])
+
+    def step(events=None):
+        for ci, (kind, key, _) in enumerate(calls):
+            if events is not None:
+                events[ci][0].record(stream)
+            run_call(kind, key)
+            if events is not None:
+                events[ci][1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in calls] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ---------------- per-kernel figures ----------------------------------------------------
+    agg = {}
+    for k in range(args.steps):
+        for ci, (kind, key, units) in enumerate(calls):
+            a = agg.setdefault(kind, dict(ms=0.0, units=0.0, launches=0))
+            a["ms"] += ev[k][ci][0].elapsed_time(ev[k][ci][1])
+            a["units"] += units
+            a["launches"] += 1
+    kernels = {}
+    for kind, a in sorted(agg.items()):
+        sec = a["ms"] * 1e-3
+        if kind.startswith("linear"):
+            ach, peak, unit, bound = a["units"] / sec / 1e12, PEAK_INT8_TOPS, "TOP/s", "mfma"
+        else:
+            ach, peak, unit, bound = a["units"] / sec / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+        kernels[kind] = dict(bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
+                             frac=round(ach / peak, 4),
+                             avg_call_us=round(a["ms"] * 1e3 / a["launches"], 2),
+                             calls_per_step=a["launches"] // args.steps)
+    total_ops = sum(u for (kind, _, u) in calls if kind.startswith("linear"))
+    value = total_ops / (ms_per_step * 1e-3) / 1e12
+    dom = kernels["linear_a8"]
+    roofline = dict(kernel="k_linear<8,false> (dgq_linear, 8-bit activation codes)",
+                    bound="mfma", achieved=dom["achieved"], peak=PEAK_INT8_TOPS, unit="TOP/s",
+                    frac=dom["frac"], traffic=None, avg_launch_us=dom["avg_call_us"],
+                    launches_per_step=dom["calls_per_step"])
+
+    # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        t_ops = 0.0
+        t_sec = 0.0
+        frac = 128
+        for ent in layers:
+            if ent["M"] < 4096:
+                continue
+            rows = max(8, ent["M"] // frac)
+            xs = ent["x"][:rows].cpu().numpy()
+            li = [e["name"] for e in layers].index(ent["name"])
+            seed = di.layer_seed(cfg["seed"], li)
+            wnp = di.linear_case(seed, 1, 2, ent["C"], ent["O"])["W"]
+            og = oracle.calibrate(xs, 8, ent["G"], 2)
+            t1 = time.perf_counter()
+            oq = oracle.quantize_act(og, xs)
+            owq, osw = oracle.quantize_weight(wnp, 8)
+            t_w = time.perf_counter()
+            oracle.linear(og, oq["q"], oq["cls"], owq, osw, None)
+            t2 = time.perf_counter()
+            # weight quantization is offline on both sides: not counted
+            t_sec += (t2 - t1) - (t_w - t1) + 0.0
+            t_ops += 2.0 * rows * ent["C"] * ent["O"]
+        cpu = dict(value=round(t_ops / t_sec / 1e12, 6), unit="TOPS", cores=1, kind="oracle",
+                   sample=("first 1/%d of the rows of every large linear layer, A8W8, quantize + "
+                           "contraction, single thread; %.1f s of CPU work" % (frac, t_sec)))
+
+    line = dict(metric=METRIC, value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps,
+                warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=True,
+                scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
+                config=dict(workload=desc, linear_ops_per_step=total_ops,
+                            calls_per_step=len(calls), setup_s=round(t_setup, 1)),
+                roofline=roofline, kernels=kernels, cpu_baseline=cpu)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
