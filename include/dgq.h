@@ -151,8 +151,10 @@ void dgq_weight_free(dgq_weight_t *w);
  *     stored code = q - code_offset;  padding positions store 0.
  * Subtraction and multiplication are separate fp32 operations (no FMA).
  *   codes: act_bits 8 -> int8 [rows, K'];
- *          act_bits 4 -> [rows, K'/2] bytes, position 2i in the low nibble and
- *          2i+1 in the high nibble of byte i, each nibble the unsigned q.
+ *          act_bits 4 -> [rows, K'/2] bytes; positions are packed in blocks of 8
+ *          into 4 bytes: byte i of block t holds position 8t+i in its low nibble
+ *          and position 8t+i+4 in its high nibble, each nibble the unsigned q
+ *          (two mask operations then give 4+4 codes in position order).
  *   row_class: uint8 [rows].
  */
 int dgq_quantize_act(const dgq_groups_t *g, const float *x, int64_t rows,

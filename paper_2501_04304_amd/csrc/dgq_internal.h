@@ -12,7 +12,7 @@
 namespace dgq {
 
 constexpr int kGranule = DGQ_K_GRANULE;  // positions per K chunk
-constexpr int kTileO = 128;              // GEMM output-channel tile; weights are padded to it
+constexpr int kTileO = 256;              // weights are padded to a multiple of every GEMM tile width
 
 // One (layer, timestep) entry of the quantization tables.
 struct Groups {

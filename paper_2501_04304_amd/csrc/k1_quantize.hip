@@ -116,7 +116,8 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                 for (int k = 0; k < 8; ++k) {
                     uint32_t qv = 0;
                     if (cc[k] >= 0) qv = (uint32_t)quant1(xs[cc[k]], z, is, qmax);
-                    word |= qv << (4 * k);
+                    // byte i of the dword holds position i (low nibble) and i + 4 (high)
+                    word |= qv << (k < 4 ? 8 * k : 8 * (k - 4) + 4);
                 }
                 out[j8] = word;
             }

@@ -8,16 +8,34 @@
 // group-wise (s_k, z_k) of Section 3.3, moved behind the integer dot product.
 //
 // Work decomposition
-//   workgroup = 256 threads = 4 wavefronts, output tile 128 rows x 128 channels
-//   wavefront = 64 x 64 sub-tile = 2 x 2 blocks of v_mfma_i32_32x32x32_i8
-//   K loop    = 64-position chunks (the K granule), double-buffered in LDS;
-//               a group is a whole number of chunks, so each group ends on a
-//               chunk boundary where its int32 block is folded into fp32.
+//   workgroup = WR x WO wavefronts; wavefront = BR x BO blocks of
+//               v_mfma_i32_32x32x32_i8 (default 2 x 2 waves of 2 x 2 blocks:
+//               a 128 x 128 output tile)
+//   K loop    = 64-position chunks (the K granule).  Chunks travel from global
+//               memory straight into LDS (global_load_lds_dwordx4, no staging
+//               registers) through a ring of stages, one barrier per chunk,
+//               and the loop is software-pipelined over half chunks so LDS
+//               reads overlap the matrix cores.  A group is a whole number of
+//               chunks, so each group ends on a chunk boundary where its int32
+//               block is folded into fp32 (convert + one FMA with a scalar scale
+//               per output); the next group's first MFMA starts from C = 0.
+//   classes   = a wavefront whose rows all share one pixel class p (almost all
+//               wavefronts: outlier pixels are rare) takes s[p, g] from a scalar
+//               register; a wavefront with mixed rows selects the scale per
+//               accumulator register through lane masks prepared before the
+//               loop.  The two cases are separate instantiations of the whole
+//               loop + epilogue, so the common one carries no class logic.
+// LDS rows are 64 B (8-bit codes, weights) or 32 B (packed 4-bit codes); the
+// 16-byte slots of a row are XOR-swizzled with row bits so that the 16-byte
+// fragment reads of 32 consecutive rows spread over all banks.  The swizzle
+// costs nothing: every lane of a direct-to-LDS load picks its own global
+// address.
 // Activation rows are the MFMA's M index (spread over accumulator registers)
 // and output channels its N index (lane % 32), so a store instruction writes
-// 128 contiguous bytes per row, and sw / zb are per-lane constants.  Rows of the
-// outlier pixel class are rare: a wavefront whose 64 rows are all class 0 takes
-// the scale from a scalar register; otherwise it selects per register.
+// 128 contiguous bytes per row, and sw / zb are per-lane constants.
+#include <cstdlib>
+#include <type_traits>
+
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -25,34 +43,68 @@ namespace dgq {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kTR = 128;           // rows per workgroup tile
-constexpr int kTO = kTileO;        // output channels per workgroup tile
-constexpr int kLdsStride = 80;     // 64 payload bytes + 16 pad: conflict-free 16-byte reads
-constexpr int kTileBytes = 128 * kLdsStride;
-constexpr int kSuperRows = 8;      // r-tiles per L2 super-tile
+constexpr int kStageBudget = 160 * 1024;  // LDS bytes per CU
+constexpr int kSuperRows = 8;             // r-tiles per L2 super-tile
 
-// Spread the unsigned nibbles of one dword (positions 0..7, position 2i in the
-// low nibble of byte i) into two dwords of bytes in position order.
-__device__ inline void unpack8(uint32_t w, uint32_t &p0123, uint32_t &p4567) {
-    const uint32_t lo = w & 0x0f0f0f0fu;         // positions 0,2,4,6
-    const uint32_t hi = (w >> 4) & 0x0f0f0f0fu;  // positions 1,3,5,7
-    p0123 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-    p4567 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+#define DGQ_LDS_DMA16(gptr, lptr)                                                          \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr), \
+                                     (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = {simm[15:14], simm[3:0]}).
+#define DGQ_WAIT_VMCNT(N) \
+    __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
+// Wait until at most min(later, L) chunks of LOADS loads each are still pending.
+template <int L, int LOADS>
+__device__ inline void wait_chunks_pending(int32_t later) {
+    if constexpr (L <= 0) {
+        DGQ_WAIT_VMCNT(0);
+    } else {
+        if (later >= L)
+            DGQ_WAIT_VMCNT(L * LOADS);
+        else
+            wait_chunks_pending<L - 1, LOADS>(later);
+    }
 }
 
-template <int ABITS, bool DUMP>
-__global__ __launch_bounds__(256, 2) void k_linear(
+// slot swizzle of a 64-byte row (4 slots): injective over rows {m, m+4, m+8, m+12}
+// and over rows {m, m+2, m+4, m+6}
+__device__ inline int swz64(int row) { return ((row >> 2) & 1) | ((((row >> 1) ^ (row >> 3)) & 1) << 1); }
+// slot swizzle of a 32-byte row (2 slots)
+__device__ inline int swz32(int row) { return (row >> 3) & 1; }
+
+// Tile shape: WR x WO wavefronts, each BR x BO blocks of 32 x 32 outputs.
+template <int ABITS_, int WR_, int WO_, int BR_, int BO_, int STAGES_, int OCC_>
+struct Cfg {
+    static constexpr int ABITS = ABITS_, WR = WR_, WO = WO_, BR = BR_, BO = BO_, STAGES = STAGES_;
+    static constexpr int OCC = OCC_;  // wavefronts per SIMD the register budget is sized for
+    static constexpr int NW = WR * WO, THREADS = 64 * NW;
+    static constexpr int TR = WR * BR * 32, TO = WO * BO * 32;
+    static constexpr int AROW = ABITS == 8 ? 64 : 32;  // bytes per code row per chunk
+    static constexpr int ABYTES = TR * AROW, BBYTES = TO * 64;
+    static constexpr int STAGE_BYTES = ABYTES + BBYTES;
+    static constexpr int AINSTR = ABYTES / 1024, BINSTR = BBYTES / 1024;  // 1 KB per DMA instruction
+    static constexpr int LOADS = (AINSTR + BINSTR) / NW;                 // per wave per chunk
+    static_assert((AINSTR + BINSTR) % NW == 0, "DMA instructions must divide evenly over the waves");
+    static_assert(STAGES >= 3 && STAGES * STAGE_BYTES <= kStageBudget, "LDS ring does not fit");
+    static_assert((STAGES - 2) * LOADS < 64, "vmcnt is a 6-bit counter");
+};
+
+template <class CF, bool DUMP>
+__global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int8_t *__restrict__ codes, const uint8_t *__restrict__ row_class,
     const int8_t *__restrict__ wq, const float *__restrict__ sw, const float *__restrict__ zb,
     const float *__restrict__ s_tab, const int32_t *__restrict__ gchunk, int64_t rows, int32_t O,
     int32_t O_pad, int32_t Kp, int32_t NG, int32_t tiles_r, int32_t tiles_o, int32_t per_xcd,
     float *__restrict__ y, int32_t *__restrict__ acc_dump) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * 2 * kTileBytes];
+    constexpr int ABITS = CF::ABITS, BR = CF::BR, BO = CF::BO, STAGES = CF::STAGES;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
-    // ---- XCD-aware tile mapping: workgroup w runs on XCD w % 8; give every XCD a
-    // contiguous range of tile indices and walk it in 8-row-tile super-columns so
+    // ---- tile and class of this workgroup.  Workgroup w runs on XCD w % 8: give every
+    // XCD a contiguous range of tile indices and walk it in 8-row-tile super-columns so
     // that the tiles resident on one XCD share code rows and weight rows in its L2.
     const int32_t T = tiles_r * tiles_o;
     const int32_t t = (int32_t)(blockIdx.x & 7) * per_xcd + (int32_t)(blockIdx.x >> 3);
@@ -65,219 +117,363 @@ __global__ __launch_bounds__(256, 2) void k_linear(
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int wr = wave >> 1, wo = wave & 1;
+    const int wr = wave / CF::WO, wo = wave % CF::WO;
     const int m32 = lane & 31, kh = lane >> 5;
-    const int64_t r0 = (int64_t)tile_r * kTR;
-    const int32_t o0 = tile_o * kTO;
+    const int64_t r0 = (int64_t)tile_r * CF::TR;
+    const int32_t o0 = tile_o * CF::TO;
     const int32_t n_chunks = Kp >> 6;
 
-    // ---- global -> register staging ------------------------------------------------
-    // weights: 128 rows x 64 B per chunk = 512 x 16 B, two per thread
-    // codes:   8 bit: same; 4 bit: 128 rows x 32 B = 256 x 16 B, one per thread
-    const int8_t *wsrc[2];
-    int wdst[2];
+    // ---- pixel classes of the rows this lane holds: bit i of cls1[a] / past[a] says
+    // whether the row in accumulator register i of row-block a is of class 1 / lies past
+    // the end of the tensor.
+    uint32_t cls1[BR], past[BR];
+    bool any1 = false, all1 = true, any_past = false;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int slot = tid + 256 * i;
-        const int row = slot >> 2, kq = slot & 3;
-        wsrc[i] = wq + (int64_t)(o0 + row) * Kp + kq * 16;
-        wdst[i] = kTileBytes + row * kLdsStride + kq * 16;
-    }
-    const int8_t *csrc[2];
-    int cdst[2];
-    if (ABITS == 8) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int slot = tid + 256 * i;
-            const int row = slot >> 2, kq = slot & 3;
-            int64_t r = r0 + row;
-            r = r < rows ? r : rows - 1;  // clamp: rows past the end are never stored
-            csrc[i] = codes + r * Kp + kq * 16;
-            cdst[i] = row * kLdsStride + kq * 16;
-        }
-    } else {
-        const int row = tid >> 1, half = tid & 1;
-        int64_t r = r0 + row;
-        r = r < rows ? r : rows - 1;
-        csrc[0] = codes + r * (Kp >> 1) + half * 16;
-        cdst[0] = row * kLdsStride + half * 32;
-        csrc[1] = csrc[0];
-        cdst[1] = cdst[0];
-    }
-
-    v4i stage_c[2], stage_w[2];
-    auto load_chunk = [&](int32_t ch) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            stage_w[i] = *reinterpret_cast<const v4i *>(wsrc[i] + (int64_t)ch * 64);
-        if (ABITS == 8) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                stage_c[i] = *reinterpret_cast<const v4i *>(csrc[i] + (int64_t)ch * 64);
-        } else {
-            stage_c[0] = *reinterpret_cast<const v4i *>(csrc[0] + (int64_t)ch * 32);
-        }
-    };
-    auto store_chunk = [&](int buf) {
-        uint8_t *base = lds + buf * 2 * kTileBytes;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) *reinterpret_cast<v4i *>(base + wdst[i]) = stage_w[i];
-        if (ABITS == 8) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) *reinterpret_cast<v4i *>(base + cdst[i]) = stage_c[i];
-        } else {
-            v4i a, b;
-            uint32_t x0, x1;
-            unpack8((uint32_t)stage_c[0].x, x0, x1); a.x = (int)x0; a.y = (int)x1;
-            unpack8((uint32_t)stage_c[0].y, x0, x1); a.z = (int)x0; a.w = (int)x1;
-            unpack8((uint32_t)stage_c[0].z, x0, x1); b.x = (int)x0; b.y = (int)x1;
-            unpack8((uint32_t)stage_c[0].w, x0, x1); b.z = (int)x0; b.w = (int)x1;
-            *reinterpret_cast<v4i *>(base + cdst[0]) = a;
-            *reinterpret_cast<v4i *>(base + cdst[0] + 16) = b;
-        }
-    };
-
-    // ---- pixel classes of this wavefront's 64 rows ---------------------------------
-    uint32_t lane_cls = 0;  // bit (br*16 + i): class of the row held in register i of block br
-    bool any_cls1;
-    {
-        int64_t r = r0 + wr * 64 + lane;
-        const int c = (r < rows) ? (int)row_class[r] : 0;
-        const uint64_t mask = __ballot(c != 0);
-        any_cls1 = mask != 0;
-        if (any_cls1) {
-#pragma unroll
-            for (int br = 0; br < 2; ++br)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int m = br * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                    lane_cls |= (uint32_t)((mask >> m) & 1) << (br * 16 + i);
-                }
-        }
-    }
-
-    float facc[2][2][16];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) facc[a][b][i] = 0.0f;
-
-    load_chunk(0);
-    store_chunk(0);
-    __syncthreads();
-
-    const int a_off = (wr * 64 + m32) * kLdsStride + kh * 16;
-    const int b_off = kTileBytes + (wo * 64 + m32) * kLdsStride + kh * 16;
-
-    int32_t ch = 0;
-    for (int32_t g = 0; g < NG; ++g) {
-        v16i acc[2][2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0;
-        const int32_t ch_end = gchunk[g + 1];
-        for (; ch < ch_end; ++ch) {
-            const bool more = ch + 1 < n_chunks;
-            if (more) load_chunk(ch + 1);
-            const uint8_t *base = lds + (ch & 1) * 2 * kTileBytes;
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                v4i af[2], bf[2];
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-                    af[a] = *reinterpret_cast<const v4i *>(base + a_off + a * 32 * kLdsStride + ks * 32);
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    bf[b] = *reinterpret_cast<const v4i *>(base + b_off + b * 32 * kLdsStride + ks * 32);
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-#pragma unroll
-                    for (int b = 0; b < 2; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
-            }
-            if (more) store_chunk((ch + 1) & 1);
-            __syncthreads();
-        }
-        // ---- fold this group's int32 block into the fp32 sum with its scale ---------
-        const float s0 = s_tab[g], s1 = s_tab[NG + g];
-        if (!any_cls1) {
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        facc[a][b][i] = fmaf((float)acc[a][b][i], s0, facc[a][b][i]);
-        } else {
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float sg = ((lane_cls >> (a * 16 + i)) & 1) ? s1 : s0;
-                        facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
-                    }
-        }
-        if (DUMP) {
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const int32_t o = o0 + wo * 64 + b * 32 + m32;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int64_t r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                        if (r < rows && o < O) acc_dump[(r * O + o) * NG + g] = acc[a][b][i];
-                    }
-                }
-        }
-    }
-
-    // ---- epilogue: y = sw[o] * sum + zb[class][o] ------------------------------------
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int32_t o = o0 + wo * 64 + b * 32 + m32;
-        const float swo = sw[o];  // o < O_pad always
-        const float zb0 = zb[o], zb1 = zb[O_pad + o];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < BR; ++a) {
+        const int64_t r = r0 + (wr * BR + a) * 32 + m32;
+        const bool in = r < rows;
+        const bool c1 = in && row_class[r] != 0;
+        const uint64_t m1 = __ballot(c1 && kh == 0);   // bit m: row m of the block is class 1
+        const uint64_t mp = __ballot(!in && kh == 0);  // bit m: row m is past the end
+        any1 = any1 || m1 != 0;
+        all1 = all1 && ((m1 | mp) & 0xffffffffull) == 0xffffffffull;
+        any_past = any_past || mp != 0;
+        cls1[a] = 0;
+        past[a] = 0;
+        if (m1 != 0 || mp != 0) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int64_t r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                const float zz = ((lane_cls >> (a * 16 + i)) & 1) ? zb1 : zb0;
-                if (r < rows && o < O) y[r * O + o] = fmaf(swo, facc[a][b][i], zz);
+                const int m = 8 * (i >> 2) + 4 * kh + (i & 3);
+                cls1[a] |= (uint32_t)((m1 >> m) & 1) << i;
+                past[a] |= (uint32_t)((mp >> m) & 1) << i;
             }
+        }
     }
+    const bool mixed = any1 && !all1;  // wave-uniform
+
+    // ---- direct-to-LDS load plan: one instruction moves 64 lanes x 16 B = 1 KB into
+    // consecutive LDS bytes (lane j lands in slot j of that kilobyte).  Instruction i of
+    // a chunk covers 16 code rows (32 for 4-bit codes) or 16 weight rows; the
+    // instructions are dealt round-robin to the waves.
+    const int8_t *src[CF::LOADS];
+    int dst[CF::LOADS];
+    int src_step[CF::LOADS];
+#pragma unroll
+    for (int j = 0; j < CF::LOADS; ++j) {
+        const int i = wave + CF::NW * j;
+        if (i < CF::AINSTR) {
+            int row, off;
+            if (ABITS == 8) {
+                row = i * 16 + (lane >> 2);
+                off = ((lane & 3) ^ swz64(row)) * 16;
+            } else {
+                row = i * 32 + (lane >> 1);
+                off = ((lane & 1) ^ swz32(row)) * 16;
+            }
+            int64_t r = r0 + row;
+            r = r < rows ? r : rows - 1;  // clamp: rows past the end are never stored
+            src[j] = codes + r * (int64_t)(ABITS == 8 ? Kp : (Kp >> 1)) + off;
+            dst[j] = i * 1024;
+            src_step[j] = CF::AROW;
+        } else {
+            const int ib = i - CF::AINSTR;
+            const int row = ib * 16 + (lane >> 2);
+            src[j] = wq + (int64_t)(o0 + row) * Kp + ((lane & 3) ^ swz64(row)) * 16;
+            dst[j] = CF::ABYTES + ib * 1024;
+            src_step[j] = 64;
+        }
+    }
+    auto issue_chunk = [&](int32_t ch) {
+        uint8_t *base = lds + (ch % STAGES) * CF::STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < CF::LOADS; ++j)
+            DGQ_LDS_DMA16(src[j] + (int64_t)ch * src_step[j], base + dst[j]);
+    };
+
+    // ---- fragment read offsets (per lane, per k-step) ---------------------------------
+    int a_off[2], b_off[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int rowa = wr * BR * 32 + m32, rowb = wo * BO * 32 + m32;
+        if (ABITS == 8)
+            a_off[ks] = rowa * 64 + (((ks * 2 + kh) ^ swz64(rowa)) * 16);
+        else
+            a_off[ks] = rowa * 32 + ((ks ^ swz32(rowa)) * 16) + kh * 8;
+        b_off[ks] = CF::ABYTES + rowb * 64 + (((ks * 2 + kh) ^ swz64(rowb)) * 16);
+    }
+    // 16 bytes of K per lane for each row-block / channel-block
+    auto load_frags = [&](const uint8_t *base, int ks, v4i (&af)[BR], v4i (&bf)[BO]) {
+#pragma unroll
+        for (int a = 0; a < BR; ++a) {
+            if (ABITS == 8) {
+                af[a] = *reinterpret_cast<const v4i *>(base + a_off[ks] + a * 32 * 64);
+            } else {
+                // 16 unsigned nibbles; byte i of a dword holds positions i and i+4
+                const v2i q = *reinterpret_cast<const v2i *>(base + a_off[ks] + a * 32 * 32);
+                af[a].x = q.x & 0x0f0f0f0f;
+                af[a].y = (int)(((uint32_t)q.x >> 4) & 0x0f0f0f0fu);
+                af[a].z = q.y & 0x0f0f0f0f;
+                af[a].w = (int)(((uint32_t)q.y >> 4) & 0x0f0f0f0fu);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < BO; ++b)
+            bf[b] = *reinterpret_cast<const v4i *>(base + b_off[ks] + b * 32 * 64);
+    };
+
+    // Make the compiler wait for a fragment set HERE (before the next set's reads are
+    // issued), so that each LDS wait only covers reads issued one MFMA batch earlier.
+    auto touch_frags = [&](v4i (&af)[BR], v4i (&bf)[BO]) {
+#pragma unroll
+        for (int a = 0; a < BR; ++a) asm volatile("" : "+v"(af[a]));
+#pragma unroll
+        for (int b = 0; b < BO; ++b) asm volatile("" : "+v"(bf[b]));
+    };
+
+    v16i acc[BR][BO];
+    float facc[BR][BO][16];
+#pragma unroll
+    for (int a = 0; a < BR; ++a)
+#pragma unroll
+        for (int b = 0; b < BO; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                facc[a][b][i] = 0.0f;
+                acc[a][b][i] = 0;
+            }
+    // fresh: the group's first k-step starts from C = 0 (no register clearing)
+    auto mfma_all = [&](const v4i (&af)[BR], const v4i (&bf)[BO], bool fresh) {
+        if (fresh) {
+            const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int a = 0; a < BR; ++a)
+#pragma unroll
+                for (int b = 0; b < BO; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[a], bf[b], zero, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int a = 0; a < BR; ++a)
+#pragma unroll
+                for (int b = 0; b < BO; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+    };
+
+    // ---- group tables in LDS (behind the ring): last chunk of each group and the two
+    // scale rows.  Reading them with LDS instructions keeps scalar memory loads out of
+    // the main loop, so its LDS waits can be partial (LDS returns in order).
+    int32_t *tab_end = reinterpret_cast<int32_t *>(lds + STAGES * CF::STAGE_BYTES);
+    float *tab_s = reinterpret_cast<float *>(tab_end + NG);
+    for (int32_t i = tid; i < NG; i += CF::THREADS) {
+        tab_end[i] = gchunk[i + 1];
+        tab_s[i] = s_tab[i];
+        tab_s[NG + i] = s_tab[NG + i];
+    }
+    __syncthreads();
+
+    // ---- prologue: fill the ring, wait for chunk 0 -------------------------------------
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st)
+        if (st < n_chunks) issue_chunk(st);
+    asm volatile("" ::: "memory");
+    wait_chunks_pending<STAGES - 2, CF::LOADS>(n_chunks - 1);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    // The loop and the epilogue, instantiated for uniform-class and mixed-class waves.
+    auto run = [&](auto mixed_tag) {
+        constexpr bool MIXED = decltype(mixed_tag)::value;
+        const int32_t p = (!MIXED && any1) ? 1 : 0;  // the wave's class when it is uniform
+        v4i af0[BR], bf0[BO], af1[BR], bf1[BO];
+        load_frags(lds, 0, af0, bf0);
+        const float *s_p = tab_s + p * NG;
+        int32_t g = 0;
+        int32_t g_end = __builtin_amdgcn_readfirstlane(tab_end[0]);
+        bool fresh = true;
+
+        // ---- main loop, software-pipelined over half chunks: while the matrix cores
+        // work on one k-step the LDS reads of the next one are in flight.  The barrier
+        // that publishes chunk ch+1 (and retires the stage chunk ch-1 used) sits between
+        // the two k-steps of chunk ch.
+        for (int32_t ch = 0; ch < n_chunks; ++ch) {
+            const uint8_t *base = lds + (ch % STAGES) * CF::STAGE_BYTES;
+            touch_frags(af0, bf0);
+            load_frags(base, 1, af1, bf1);
+            mfma_all(af0, bf0, fresh);
+            fresh = false;
+            touch_frags(af1, bf1);
+            if (ch + 1 < n_chunks) {
+                asm volatile("" ::: "memory");
+                if (DUMP)
+                    DGQ_WAIT_VMCNT(0);
+                else
+                    wait_chunks_pending<STAGES - 3, CF::LOADS>(n_chunks - 2 - ch);
+#ifndef DGQ_DBG_NO_BARRIER
+                __builtin_amdgcn_s_barrier();
+#endif
+                asm volatile("" ::: "memory");
+#ifndef DGQ_DBG_NO_DMA
+                if (ch + STAGES - 1 < n_chunks) issue_chunk(ch + STAGES - 1);
+#endif
+                load_frags(lds + ((ch + 1) % STAGES) * CF::STAGE_BYTES, 0, af0, bf0);
+            }
+            mfma_all(af1, bf1, false);
+
+#ifdef DGQ_DBG_NO_FOLD
+            if (ch + 1 == n_chunks) {
+#else
+            if (ch + 1 == g_end) {
+#endif
+                // ---- fold this group's int32 block into the fp32 sum with its scale ---
+                if (!MIXED) {
+                    const float sg = s_p[g];
+#pragma unroll
+                    for (int a = 0; a < BR; ++a)
+#pragma unroll
+                        for (int b = 0; b < BO; ++b)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i)
+                                facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
+                } else {
+                    const float s0 = tab_s[g], s1 = tab_s[NG + g];
+#pragma unroll
+                    for (int a = 0; a < BR; ++a)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float sg = ((cls1[a] >> i) & 1) ? s1 : s0;
+#pragma unroll
+                            for (int b = 0; b < BO; ++b)
+                                facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
+                        }
+                }
+                if (DUMP) {
+#pragma unroll
+                    for (int a = 0; a < BR; ++a)
+#pragma unroll
+                        for (int b = 0; b < BO; ++b) {
+                            const int32_t o = o0 + (wo * BO + b) * 32 + m32;
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const int64_t r =
+                                    r0 + (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                                if (r < rows && o < O) acc_dump[(r * O + o) * NG + g] = acc[a][b][i];
+                            }
+                        }
+                }
+                fresh = true;
+                ++g;
+                g_end = g < NG ? __builtin_amdgcn_readfirstlane(tab_end[g]) : 0x7fffffff;
+            }
+        }
+
+        // ---- epilogue: y = sw[o] * sum + zb[class][o] ---------------------------------
+        // Wide path (O a multiple of 4): the tile goes through LDS (over the drained
+        // ring) so that every lane stores 16 contiguous bytes and every row of the
+        // tile leaves as one contiguous run.  LDS layout: row-major [TR][TO] floats with
+        // the 32-float halves of each 64-float span swapped on rows with bit 2 set, which
+        // spreads the two row groups of one register over all banks.
+        const bool wide = (O & 3) == 0;
+        float *tile = reinterpret_cast<float *>(lds);
+        if (wide) __syncthreads();  // every wave is done with the last stage
+#pragma unroll
+        for (int b = 0; b < BO; ++b) {
+            const int ol = (wo * BO + b) * 32 + m32;  // column inside the tile
+            const int32_t o = o0 + ol;
+            const float swo = sw[o];  // o < O_pad always
+            const float zb0 = zb[o], zb1 = zb[O_pad + o];
+#pragma unroll
+            for (int a = 0; a < BR; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                    float zz;
+                    if (MIXED)
+                        zz = ((cls1[a] >> i) & 1) ? zb1 : zb0;
+                    else
+                        zz = p ? zb1 : zb0;
+                    const float v = fmaf(swo, facc[a][b][i], zz);
+                    if (wide) {
+                        tile[rl * CF::TO + (ol ^ ((rl & 4) << 3))] = v;
+                    } else if (o < O && (!any_past || !((past[a] >> i) & 1))) {
+                        y[(r0 + rl) * O + o] = v;
+                    }
+                }
+        }
+        if (wide) {
+            __syncthreads();
+            constexpr int kVecPerRow = CF::TO / 4;
+            constexpr int kRowsPerPass = CF::THREADS / kVecPerRow;
+            const int c4 = (tid % kVecPerRow) * 4;
+            const bool col_ok = o0 + c4 < O;
+#pragma unroll 4
+            for (int rl = tid / kVecPerRow; rl < CF::TR; rl += kRowsPerPass) {
+                const int64_t r = r0 + rl;
+                const float4 v = *reinterpret_cast<const float4 *>(tile + rl * CF::TO + (c4 ^ ((rl & 4) << 3)));
+                if (col_ok && r < rows) *reinterpret_cast<float4 *>(y + r * O + o0 + c4) = v;
+            }
+        }
+    };
+    if (mixed)
+        run(std::true_type{});
+    else
+        run(std::false_type{});
+}
+
+template <class CF, bool DUMP>
+hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
+                      const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
+                      hipStream_t st) {
+    const int32_t tiles_r = (int32_t)((rows + CF::TR - 1) / CF::TR);
+    const int32_t tiles_o = (w.O + CF::TO - 1) / CF::TO;  // O_pad is a multiple of every TO
+    const int64_t T = (int64_t)tiles_r * tiles_o;
+    const int32_t per_xcd = (int32_t)((T + 7) / 8);
+    const dim3 grid((unsigned)(per_xcd * 8));
+    size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES + 12 * (size_t)g.info.n_groups;
+    if (lds < (size_t)CF::TR * CF::TO * 4) lds = (size_t)CF::TR * CF::TO * 4;  // epilogue tile
+    auto kern = k_linear<CF, DUMP>;
+    static bool attr_done = false;  // per instantiation
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kStageBudget);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    if (lds > (size_t)kStageBudget) return hipErrorInvalidValue;  // too many groups for the table
+    hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
+                       w.d_zb, g.d_s, g.d_gchunk, rows, w.O, w.O_pad, w.Kp, g.info.n_groups,
+                       tiles_r, tiles_o, per_xcd, y, acc_dump);
+    return hipGetLastError();
 }
 
 }  // namespace
 
+static int g_force_cfg = -1;  // tuning hook: environment variable DGQ_LINEAR_CFG selects a tile shape
+
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
                          hipStream_t st) {
-    const int32_t tiles_r = (int32_t)((rows + kTR - 1) / kTR);
-    const int32_t tiles_o = w.O_pad / kTO;
-    const int64_t T = (int64_t)tiles_r * tiles_o;
-    const int32_t per_xcd = (int32_t)((T + 7) / 8);
-    const dim3 grid((unsigned)(per_xcd * 8));
-    using Kern = void (*)(const int8_t *, const uint8_t *, const int8_t *, const float *,
-                          const float *, const float *, const int32_t *, int64_t, int32_t, int32_t,
-                          int32_t, int32_t, int32_t, int32_t, int32_t, float *, int32_t *);
-    Kern kern;
-    if (g.info.act_bits == 8)
-        kern = acc_dump ? k_linear<8, true> : k_linear<8, false>;
-    else
-        kern = acc_dump ? k_linear<4, true> : k_linear<4, false>;
-    hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, codes, row_class, w.d_wq, w.d_sw, w.d_zb,
-                       g.d_s, g.d_gchunk, rows, w.O, w.O_pad, w.Kp, g.info.n_groups, tiles_r,
-                       tiles_o, per_xcd, y, acc_dump);
-    return hipGetLastError();
+    static bool env_read = false;
+    if (!env_read) {
+        if (const char *e = getenv("DGQ_LINEAR_CFG")) g_force_cfg = atoi(e);
+        env_read = true;
+    }
+    const bool a8 = g.info.act_bits == 8;
+    if (acc_dump) {
+        return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
+                  : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
+    }
+    int cfg = g_force_cfg >= 0 ? g_force_cfg : 0;
+#define DGQ_CASE(ID, ...)                                                                          \
+    case ID:                                                                                       \
+        return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st) \
+                  : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
+    switch (cfg) {
+        DGQ_CASE(1, 4, 2, 2, 2, 6, 2);  // 256 x 128, 8 waves of 64 x 64, one workgroup per CU
+        default:
+            DGQ_CASE(0, 2, 2, 2, 2, 4, 2);  // 128 x 128, 4 waves of 64 x 64, two workgroups per CU
+    }
+#undef DGQ_CASE
 }
 
 }  // namespace dgq

@@ -27,11 +27,11 @@ def codes_to_q(codes_np, act_bits, kp):
     """Stored containers -> the unsigned codes q [rows, K'] the paper defines."""
     if act_bits == 8:
         return (codes_np.astype(np.int16) + 128).astype(np.uint8)
-    b = codes_np.view(np.uint8)
-    q = np.empty((b.shape[0], kp), np.uint8)
-    q[:, 0::2] = b & 0x0F
-    q[:, 1::2] = b >> 4
-    return q
+    b = codes_np.view(np.uint8).reshape(codes_np.shape[0], kp // 8, 4)
+    q = np.empty((b.shape[0], kp // 8, 8), np.uint8)
+    q[:, :, 0:4] = b & 0x0F   # byte i of a block: position i in the low nibble,
+    q[:, :, 4:8] = b >> 4     # position i + 4 in the high nibble
+    return q.reshape(b.shape[0], kp)
 
 
 def assert_close_fp32(got, ref, what=""):
