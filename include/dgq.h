@@ -150,15 +150,25 @@ void dgq_weight_free(dgq_weight_t *w);
  *     q = clamp(rne((x[r,c] - z[p,g]) * (1/s[p,g])), 0, 2^b - 1)
  *     stored code = q - code_offset;  padding positions store 0.
  * Subtraction and multiplication are separate fp32 operations (no FMA).
- *   codes: act_bits 8 -> int8 [rows, K'];
- *          act_bits 4 -> [rows, K'/2] bytes; positions are packed in blocks of 8
- *          into 4 bytes: byte i of block t holds position 8t+i in its low nibble
- *          and position 8t+i+4 in its high nibble, each nibble the unsigned q
- *          (two mask operations then give 4+4 codes in position order).
+ *   codes: dgq_codes_bytes(g, rows) bytes, written in the block-tiled layout
+ *          dgq_linear reads with 1 KiB direct-to-LDS loads.  A block is 1 KiB and
+ *          holds one 64-position chunk of R consecutive rows (R = 16 at 8 bit,
+ *          R = 32 at 4 bit); blocks are ordered [row block][chunk].  Inside a block,
+ *          row t occupies bytes [t*B, (t+1)*B), B = 64 (8 bit) or 32 (4 bit), and its
+ *          16-byte slots are XOR-permuted: slot k is stored at slot
+ *              k ^ ( bit2(t) | ((bit1(t) ^ bit3(t)) << 1) )          (8 bit, 4 slots)
+ *              k ^ bit3(t)                                           (4 bit, 2 slots)
+ *          8 bit: one int8 per position.  4 bit: positions are packed in groups of 8
+ *          into 4 bytes, byte i holding position i in its low nibble and position
+ *          i+4 in its high nibble, each nibble the unsigned q.
+ *          Rows of the last row block past `rows` are not written.
  *   row_class: uint8 [rows].
  */
 int dgq_quantize_act(const dgq_groups_t *g, const float *x, int64_t rows,
                      int8_t *codes, uint8_t *row_class, void *stream);
+
+/* Size in bytes of the code buffer for `rows` rows (rows rounded up to a block). */
+size_t dgq_codes_bytes(const dgq_groups_t *g, int64_t rows);
 
 /*
  * Quantized linear layer: grouped integer contraction and dequantization.

@@ -54,6 +54,8 @@ def lib():
         L.dgq_weight_free.restype = None
         L.dgq_quantize_act.argtypes = [vp, vp, i64, vp, vp, vp]
         L.dgq_linear.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dgq_codes_bytes.argtypes = [vp, i64]
+        L.dgq_codes_bytes.restype = sz
         L.dgq_linear_workspace_bytes.argtypes = [vp, vp, i64]
         L.dgq_linear_workspace_bytes.restype = sz
         L.dgq_xattn_logq.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
@@ -173,12 +175,14 @@ def dgq_pack_weight(groups: Groups, w, bias, w_bits: int, stream=None) -> Weight
 
 
 def codes_shape(groups: Groups, rows: int):
-    kp = groups.info.k_padded
-    return (rows, kp if groups.info.act_bits == 8 else kp // 2)
+    """Shape of the block-tiled code buffer: [row blocks, chunks, 1024 bytes]."""
+    n_chunks = groups.info.k_padded // DGQ_K_GRANULE
+    nbytes = int(lib().dgq_codes_bytes(groups.handle, rows))
+    return (nbytes // (n_chunks * 1024), n_chunks, 1024)
 
 
 def dgq_quantize_act(groups: Groups, x, codes=None, row_class=None, stream=None):
-    """Returns (codes int8 [rows, K'] or packed [rows, K'/2], row_class uint8 [rows])."""
+    """Returns (codes int8 [row blocks, chunks, 1024] block-tiled, row_class uint8 [rows])."""
     import torch
     _dev(x, torch.float32, "x")
     rows, ch = x.shape
@@ -203,8 +207,8 @@ def dgq_linear(groups: Groups, weight: Weight, codes, row_class, y=None, acc_dum
     import torch
     _dev(codes, torch.int8, "codes")
     _dev(row_class, torch.uint8, "row_class")
-    rows = codes.shape[0]
-    if tuple(codes.shape) != codes_shape(groups, rows) or row_class.numel() != rows:
+    rows = row_class.numel()
+    if tuple(codes.shape) != codes_shape(groups, rows):
         raise ValueError("codes / row_class have the wrong shape")
     O = weight.out_channels
     if y is None:

@@ -400,6 +400,13 @@ int dgq_quantize_act(const dgq_groups_t *h, const float *x, int64_t rows, int8_t
     return DGQ_OK;
 }
 
+size_t dgq_codes_bytes(const dgq_groups_t *h, int64_t rows) {
+    if (!h || rows < 1) return 0;
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    const int64_t block_rows = g->info.act_bits == 8 ? 16 : 32;
+    return (size_t)((rows + block_rows - 1) / block_rows) * (size_t)g->n_chunks * 1024;
+}
+
 size_t dgq_linear_workspace_bytes(const dgq_groups_t *, const dgq_weight_t *, int64_t) { return 0; }
 
 int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *codes,

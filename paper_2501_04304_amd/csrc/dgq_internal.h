@@ -14,6 +14,27 @@ namespace dgq {
 constexpr int kGranule = DGQ_K_GRANULE;  // positions per K chunk
 constexpr int kTileO = 256;              // weights are padded to a multiple of every GEMM tile width
 
+// ---- block-tiled operand layout shared by the quantizer, the weight packer and the
+// GEMM.  A block is 1 KiB = one 64-position chunk of 16 rows (64 B per row: int8
+// codes and weights) or of 32 rows (32 B per row: packed 4-bit codes); blocks are
+// ordered [row block][chunk].  The 16-byte slots of a row are XOR-permuted so that the
+// GEMM's 16-byte LDS fragment reads of 32 consecutive rows touch all banks; since a
+// block is copied verbatim into LDS the permutation lives in the global layout.
+__host__ __device__ inline int swz64(int row) {  // 4 slots
+    return ((row >> 2) & 1) | ((((row >> 1) ^ (row >> 3)) & 1) << 1);
+}
+__host__ __device__ inline int swz32(int row) { return (row >> 3) & 1; }  // 2 slots
+// byte offset of 16-byte slot kq of (row, chunk) in a 64-B-per-row tensor
+__host__ __device__ inline int64_t tiled64_offset(int64_t row, int32_t chunk, int32_t n_chunks, int kq) {
+    const int t = (int)(row & 15);
+    return (((row >> 4) * n_chunks + chunk) << 10) + t * 64 + ((kq ^ swz64(t)) << 4);
+}
+// byte offset of 16-byte slot h of (row, chunk) in a 32-B-per-row tensor
+__host__ __device__ inline int64_t tiled32_offset(int64_t row, int32_t chunk, int32_t n_chunks, int h) {
+    const int t = (int)(row & 31);
+    return (((row >> 5) * n_chunks + chunk) << 10) + t * 32 + ((h ^ swz32(t)) << 4);
+}
+
 // One (layer, timestep) entry of the quantization tables.
 struct Groups {
     dgq_groups_info_t info{};
@@ -34,7 +55,7 @@ struct Groups {
 struct Weight {
     const Groups *groups = nullptr;
     int32_t O = 0, O_pad = 0, C = 0, Kp = 0, w_bits = 8;
-    int8_t *d_wq = nullptr;  // [O_pad][K'] permuted + padded rows
+    int8_t *d_wq = nullptr;  // [O_pad x K'] permuted + padded rows, block-tiled (64 B per row)
     float *d_sw = nullptr;   // [O_pad]
     float *d_zb = nullptr;   // [2][O_pad]
     int device = 0;

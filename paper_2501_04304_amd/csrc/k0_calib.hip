@@ -92,9 +92,12 @@ __global__ __launch_bounds__(256) void k_pack_weight(
     const int32_t o = blockIdx.x;
     const int tid = threadIdx.x;
     const int32_t n_chunks = Kp / kGranule;
-    int8_t *row = wq + (int64_t)o * Kp;
+    // position j of row o in the block-tiled layout
+    auto at = [&](int32_t j) -> int8_t & {
+        return wq[tiled64_offset(o, j >> 6, n_chunks, (j >> 4) & 3) + (j & 15)];
+    };
     if (o >= O) {  // padding rows: all-zero weights
-        for (int32_t j = tid; j < Kp; j += 256) row[j] = 0;
+        for (int32_t j = tid; j < Kp; j += 256) at(j) = 0;
         if (tid == 0) {
             sw[o] = 0.0f;
             zb[o] = 0.0f;
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(
             v = (int32_t)qf;
             atomicAdd(&gsum[chunk2grp[j / kGranule]], v);
         }
-        row[j] = (int8_t)v;
+        at(j) = (int8_t)v;
     }
     __syncthreads();
     if (tid < 2) {
@@ -143,7 +146,6 @@ __global__ __launch_bounds__(256) void k_pack_weight(
         zb[p * O_pad + o] = (float)v;
         if (p == 0) sw[o] = sc;
     }
-    (void)n_chunks;
 }
 
 __global__ __launch_bounds__(256) void k_unpack_weight(const int8_t *__restrict__ wq, int32_t O,
@@ -153,7 +155,8 @@ __global__ __launch_bounds__(256) void k_unpack_weight(const int8_t *__restrict_
     const int32_t o = blockIdx.x;
     for (int32_t j = threadIdx.x; j < Kp; j += 256) {
         const int32_t c = perm[j];
-        if (c >= 0) out[(int64_t)o * C + c] = wq[(int64_t)o * Kp + j];
+        if (c >= 0)
+            out[(int64_t)o * C + c] = wq[tiled64_offset(o, j >> 6, Kp >> 6, (j >> 4) & 3) + (j & 15)];
     }
 }
 

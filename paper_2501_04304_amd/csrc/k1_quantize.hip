@@ -7,8 +7,8 @@
 // (1 B at 8 bit, 0.5 B at 4 bit), plus one class byte per row.  One wavefront
 // owns a row: it streams the row with 16-byte loads into its LDS slice while
 // reducing max/min with wave shuffles, decides the pixel class, then gathers
-// the row from LDS in the permuted K' order so that the codes leave as fully
-// coalesced dword stores.
+// the row from LDS in the permuted K' order and writes the codes as dwords into
+// the block-tiled layout the GEMM loads (64 contiguous bytes per row and chunk).
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -87,7 +87,6 @@ __global__ __launch_bounds__(256) void k_quantize_act(
         __builtin_amdgcn_wave_barrier();
 
         if (BITS == 8) {
-            uint32_t *out = reinterpret_cast<uint32_t *>(codes + r * Kp);
             const int4 *perm4 = reinterpret_cast<const int4 *>(perm);
             for (int32_t j4 = lane; j4 < (Kp >> 2); j4 += kWave) {
                 const int32_t ch = j4 >> 4;  // 16 dwords per 64-position chunk
@@ -101,10 +100,11 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                     if (cc[k] >= 0) code = (int32_t)quant1(xs[cc[k]], z, is, qmax) - kOff;
                     word |= ((uint32_t)code & 0xffu) << (8 * k);
                 }
-                out[j4] = word;
+                // dword (j4 & 15) of chunk ch: slot (j4 >> 2) & 3, dword j4 & 3 of the slot
+                *reinterpret_cast<uint32_t *>(codes + tiled64_offset(r, ch, n_chunks, (j4 >> 2) & 3) +
+                                              (j4 & 3) * 4) = word;
             }
         } else {
-            uint32_t *out = reinterpret_cast<uint32_t *>(codes + r * (Kp >> 1));
             const int4 *perm4 = reinterpret_cast<const int4 *>(perm);
             for (int32_t j8 = lane; j8 < (Kp >> 3); j8 += kWave) {
                 const int32_t ch = j8 >> 3;  // 8 dwords per 64-position chunk
@@ -119,7 +119,8 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                     // byte i of the dword holds position i (low nibble) and i + 4 (high)
                     word |= qv << (k < 4 ? 8 * k : 8 * (k - 4) + 4);
                 }
-                out[j8] = word;
+                *reinterpret_cast<uint32_t *>(codes + tiled32_offset(r, ch, n_chunks, (j8 >> 2) & 1) +
+                                              (j8 & 3) * 4) = word;
             }
         }
         // the next row overwrites xs

@@ -25,11 +25,13 @@
 //               accumulator register through lane masks prepared before the
 //               loop.  The two cases are separate instantiations of the whole
 //               loop + epilogue, so the common one carries no class logic.
-// LDS rows are 64 B (8-bit codes, weights) or 32 B (packed 4-bit codes); the
-// 16-byte slots of a row are XOR-swizzled with row bits so that the 16-byte
-// fragment reads of 32 consecutive rows spread over all banks.  The swizzle
-// costs nothing: every lane of a direct-to-LDS load picks its own global
-// address.
+// Codes and weights are stored block-tiled in global memory (1 KiB = one chunk
+// of 16 rows, or of 32 rows of packed 4-bit codes), so that one direct-to-LDS
+// instruction copies 1 KiB of contiguous memory: loads that gather 64-byte row
+// pieces cost about twice as much in the address path.  LDS rows are 64 B
+// (8-bit codes, weights) or 32 B (packed 4-bit codes); the 16-byte slots of a
+// row are XOR-swizzled with row bits (already in global memory) so that the
+// 16-byte fragment reads of 32 consecutive rows spread over all banks.
 // Activation rows are the MFMA's M index (spread over accumulator registers)
 // and output channels its N index (lane % 32), so a store instruction writes
 // 128 contiguous bytes per row, and sw / zb are per-lane constants.
@@ -69,12 +71,6 @@ __device__ inline void wait_chunks_pending(int32_t later) {
             wait_chunks_pending<L - 1, LOADS>(later);
     }
 }
-
-// slot swizzle of a 64-byte row (4 slots): injective over rows {m, m+4, m+8, m+12}
-// and over rows {m, m+2, m+4, m+6}
-__device__ inline int swz64(int row) { return ((row >> 2) & 1) | ((((row >> 1) ^ (row >> 3)) & 1) << 1); }
-// slot swizzle of a 32-byte row (2 slots)
-__device__ inline int swz32(int row) { return (row >> 3) & 1; }
 
 // Tile shape: WR x WO wavefronts, each BR x BO blocks of 32 x 32 outputs.
 template <int ABITS_, int WR_, int WO_, int BR_, int BO_, int STAGES_, int OCC_>
@@ -151,43 +147,32 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     }
     const bool mixed = any1 && !all1;  // wave-uniform
 
-    // ---- direct-to-LDS load plan: one instruction moves 64 lanes x 16 B = 1 KB into
-    // consecutive LDS bytes (lane j lands in slot j of that kilobyte).  Instruction i of
-    // a chunk covers 16 code rows (32 for 4-bit codes) or 16 weight rows; the
-    // instructions are dealt round-robin to the waves.
+    // ---- direct-to-LDS load plan: the operands are stored block-tiled, one block =
+    // 1 KiB = one chunk of 16 rows (32 rows of packed 4-bit codes), already in the
+    // slot-swizzled order LDS wants.  One instruction copies one block (lane j moves
+    // bytes [16j, 16j+16)); the blocks of a chunk are dealt round-robin to the waves.
+    constexpr int kARows = ABITS == 8 ? 16 : 32;  // rows per code block
+    const int64_t n_ablocks = (rows + kARows - 1) / kARows;
     const int8_t *src[CF::LOADS];
     int dst[CF::LOADS];
-    int src_step[CF::LOADS];
 #pragma unroll
     for (int j = 0; j < CF::LOADS; ++j) {
         const int i = wave + CF::NW * j;
         if (i < CF::AINSTR) {
-            int row, off;
-            if (ABITS == 8) {
-                row = i * 16 + (lane >> 2);
-                off = ((lane & 3) ^ swz64(row)) * 16;
-            } else {
-                row = i * 32 + (lane >> 1);
-                off = ((lane & 1) ^ swz32(row)) * 16;
-            }
-            int64_t r = r0 + row;
-            r = r < rows ? r : rows - 1;  // clamp: rows past the end are never stored
-            src[j] = codes + r * (int64_t)(ABITS == 8 ? Kp : (Kp >> 1)) + off;
+            int64_t blk = r0 / kARows + i;
+            blk = blk < n_ablocks ? blk : n_ablocks - 1;  // clamp: rows past the end are never stored
+            src[j] = codes + ((blk * n_chunks) << 10) + lane * 16;
             dst[j] = i * 1024;
-            src_step[j] = CF::AROW;
         } else {
             const int ib = i - CF::AINSTR;
-            const int row = ib * 16 + (lane >> 2);
-            src[j] = wq + (int64_t)(o0 + row) * Kp + ((lane & 3) ^ swz64(row)) * 16;
+            src[j] = wq + (((int64_t)(o0 / 16 + ib) * n_chunks) << 10) + lane * 16;
             dst[j] = CF::ABYTES + ib * 1024;
-            src_step[j] = 64;
         }
     }
     auto issue_chunk = [&](int32_t ch) {
         uint8_t *base = lds + (ch % STAGES) * CF::STAGE_BYTES;
 #pragma unroll
-        for (int j = 0; j < CF::LOADS; ++j)
-            DGQ_LDS_DMA16(src[j] + (int64_t)ch * src_step[j], base + dst[j]);
+        for (int j = 0; j < CF::LOADS; ++j) DGQ_LDS_DMA16(src[j] + ((int64_t)ch << 10), base + dst[j]);
     };
 
     // ---- fragment read offsets (per lane, per k-step) ---------------------------------
@@ -470,6 +455,7 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                   : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
     switch (cfg) {
         DGQ_CASE(1, 4, 2, 2, 2, 6, 2);  // 256 x 128, 8 waves of 64 x 64, one workgroup per CU
+        DGQ_CASE(2, 2, 2, 2, 2, 3, 2);  // 128 x 128, 3 stages
         default:
             DGQ_CASE(0, 2, 2, 2, 2, 4, 2);  // 128 x 128, 4 waves of 64 x 64, two workgroups per CU
     }

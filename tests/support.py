@@ -23,15 +23,36 @@ def gpu_groups_vs_oracle(gg, og):
     assert np.array_equal(t["z"].view(np.uint32), og.z.view(np.uint32))
 
 
-def codes_to_q(codes_np, act_bits, kp):
-    """Stored containers -> the unsigned codes q [rows, K'] the paper defines."""
+def _swz64(t):
+    return ((t >> 2) & 1) | ((((t >> 1) ^ (t >> 3)) & 1) << 1)
+
+
+def codes_to_q(codes_np, act_bits, kp, rows):
+    """Block-tiled containers -> the unsigned codes q [rows, K'] the paper defines.
+
+    Layout (include/dgq.h): blocks of 1 KiB ordered [row block][chunk]; a block is one
+    64-position chunk of 16 rows x 64 B (8 bit) or 32 rows x 32 B (4 bit); the 16-byte
+    slots of row t are XOR-permuted."""
+    n_chunks = kp // 64
+    b = codes_np.view(np.uint8).reshape(-1, n_chunks, 1024)
     if act_bits == 8:
-        return (codes_np.astype(np.int16) + 128).astype(np.uint8)
-    b = codes_np.view(np.uint8).reshape(codes_np.shape[0], kp // 8, 4)
-    q = np.empty((b.shape[0], kp // 8, 8), np.uint8)
-    q[:, :, 0:4] = b & 0x0F   # byte i of a block: position i in the low nibble,
-    q[:, :, 4:8] = b >> 4     # position i + 4 in the high nibble
-    return q.reshape(b.shape[0], kp)
+        blk = b.reshape(-1, n_chunks, 16, 4, 16)          # [rb, ch, t, stored slot, byte]
+        out = np.empty_like(blk)
+        for t in range(16):
+            for k in range(4):
+                out[:, :, t, k] = blk[:, :, t, k ^ _swz64(t)]
+        q = out.transpose(0, 2, 1, 3, 4).reshape(-1, kp)   # [rb*16, ch*64]
+        return (q[:rows].astype(np.int8).astype(np.int16) + 128).astype(np.uint8)
+    blk = b.reshape(-1, n_chunks, 32, 2, 16)
+    out = np.empty_like(blk)
+    for t in range(32):
+        for h in range(2):
+            out[:, :, t, h] = blk[:, :, t, h ^ ((t >> 3) & 1)]
+    packed = out.transpose(0, 2, 1, 3, 4).reshape(-1, kp // 8, 4)[:rows]  # groups of 8 positions
+    q = np.empty((packed.shape[0], kp // 8, 8), np.uint8)
+    q[:, :, 0:4] = packed & 0x0F   # byte i: position i in the low nibble,
+    q[:, :, 4:8] = packed >> 4     # position i + 4 in the high nibble
+    return q.reshape(packed.shape[0], kp)
 
 
 def assert_close_fp32(got, ref, what=""):

@@ -37,7 +37,7 @@ def _run_layer(dgq, oracle, run, cal, act_bits, w_bits, G, P=2, bias=None, sampl
     codes, cls = dgq.dgq_quantize_act(gg, _dev(X))
     torch.cuda.synchronize()
     oq = oracle.quantize_act(og, X)
-    q_gpu = codes_to_q(codes.cpu().numpy(), act_bits, og.Kp)
+    q_gpu = codes_to_q(codes.cpu().numpy(), act_bits, og.Kp, rows)
     real = og.perm >= 0
     assert np.array_equal(cls.cpu().numpy(), oq["cls"])
     assert np.array_equal(q_gpu[:, real], oq["q"][:, real])
@@ -67,8 +67,7 @@ def _run_layer(dgq, oracle, run, cal, act_bits, w_bits, G, P=2, bias=None, sampl
             assert np.array_equal(y2.cpu().numpy(), y_np)  # the dump path gives the same y
         else:
             # re-run the sampled rows alone with the accumulator dump
-            sub_codes = codes[torch.from_numpy(sel).cuda()].contiguous()
-            sub_cls = cls[torch.from_numpy(sel).cuda()].contiguous()
+            sub_codes, sub_cls = dgq.dgq_quantize_act(gg, _dev(X[sel]))
             dump = torch.full((len(sel), O, og.NG), -7, dtype=torch.int32, device="cuda")
             y2 = dgq.dgq_linear(gg, wt, sub_codes, sub_cls, acc_dump=dump)
             torch.cuda.synchronize()
