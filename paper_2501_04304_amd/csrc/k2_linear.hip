@@ -49,7 +49,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kStageBudget = 160 * 1024;  // LDS bytes per CU
-constexpr int kSuperRows = 8;             // r-tiles per L2 super-tile
 
 #define DGQ_LDS_DMA16(gptr, lptr)                                                          \
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr), \
@@ -83,8 +82,9 @@ struct Cfg {
     static constexpr int ABYTES = TR * AROW, BBYTES = TO * 64;
     static constexpr int STAGE_BYTES = ABYTES + BBYTES;
     static constexpr int AINSTR = ABYTES / 1024, BINSTR = BBYTES / 1024;  // 1 KB per DMA instruction
-    static constexpr int LOADS = (AINSTR + BINSTR) / NW;                 // per wave per chunk
-    static_assert((AINSTR + BINSTR) % NW == 0, "DMA instructions must divide evenly over the waves");
+    // loads per wave per chunk; when the blocks do not divide evenly the last block is
+    // copied by more than one wave (same bytes to the same place)
+    static constexpr int LOADS = (AINSTR + BINSTR + NW - 1) / NW;
     static_assert(STAGES >= 3 && STAGES * STAGE_BYTES <= kStageBudget, "LDS ring does not fit");
     static_assert((STAGES - 2) * LOADS < 64, "vmcnt is a 6-bit counter");
 };
@@ -95,19 +95,19 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int8_t *__restrict__ wq, const float *__restrict__ sw, const float *__restrict__ zb,
     const float *__restrict__ s_tab, const int32_t *__restrict__ gchunk, int64_t rows, int32_t O,
     int32_t O_pad, int32_t Kp, int32_t NG, int32_t tiles_r, int32_t tiles_o, int32_t per_xcd,
-    float *__restrict__ y, int32_t *__restrict__ acc_dump) {
+    int32_t super_rows, float *__restrict__ y, int32_t *__restrict__ acc_dump) {
     constexpr int ABITS = CF::ABITS, BR = CF::BR, BO = CF::BO, STAGES = CF::STAGES;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     // ---- tile and class of this workgroup.  Workgroup w runs on XCD w % 8: give every
-    // XCD a contiguous range of tile indices and walk it in 8-row-tile super-columns so
+    // XCD a contiguous range of tile indices and walk it in super-columns of `super_rows` row tiles so
     // that the tiles resident on one XCD share code rows and weight rows in its L2.
     const int32_t T = tiles_r * tiles_o;
     const int32_t t = (int32_t)(blockIdx.x & 7) * per_xcd + (int32_t)(blockIdx.x >> 3);
     if (t >= T) return;
-    const int32_t in_super = kSuperRows * tiles_o;
-    const int32_t first_r = (t / in_super) * kSuperRows;
-    const int32_t gsz = tiles_r - first_r < kSuperRows ? tiles_r - first_r : kSuperRows;
+    const int32_t in_super = super_rows * tiles_o;
+    const int32_t first_r = (t / in_super) * super_rows;
+    const int32_t gsz = tiles_r - first_r < super_rows ? tiles_r - first_r : super_rows;
     const int32_t tile_r = first_r + (t % in_super) % gsz;
     const int32_t tile_o = (t % in_super) / gsz;
 
@@ -119,33 +119,32 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int32_t o0 = tile_o * CF::TO;
     const int32_t n_chunks = Kp >> 6;
 
-    // ---- pixel classes of the rows this lane holds: bit i of cls1[a] / past[a] says
-    // whether the row in accumulator register i of row-block a is of class 1 / lies past
-    // the end of the tensor.
-    uint32_t cls1[BR], past[BR];
-    bool any1 = false, all1 = true, any_past = false;
+    // ---- start-up order: (1) issue the small global loads (row classes, group table
+    // entries), (2) issue the first chunks' direct-to-LDS loads, (3) only then consume
+    // the small loads, so their latency overlaps the first chunks'.
+    bool row_in[BR];
+    uint8_t row_c1[BR];
 #pragma unroll
     for (int a = 0; a < BR; ++a) {
         const int64_t r = r0 + (wr * BR + a) * 32 + m32;
-        const bool in = r < rows;
-        const bool c1 = in && row_class[r] != 0;
-        const uint64_t m1 = __ballot(c1 && kh == 0);   // bit m: row m of the block is class 1
-        const uint64_t mp = __ballot(!in && kh == 0);  // bit m: row m is past the end
-        any1 = any1 || m1 != 0;
-        all1 = all1 && ((m1 | mp) & 0xffffffffull) == 0xffffffffull;
-        any_past = any_past || mp != 0;
-        cls1[a] = 0;
-        past[a] = 0;
-        if (m1 != 0 || mp != 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = 8 * (i >> 2) + 4 * kh + (i & 3);
-                cls1[a] |= (uint32_t)((m1 >> m) & 1) << i;
-                past[a] |= (uint32_t)((mp >> m) & 1) << i;
-            }
-        }
+        row_in[a] = r < rows;
+        row_c1[a] = row_in[a] ? row_class[r] : (uint8_t)0;
     }
-    const bool mixed = any1 && !all1;  // wave-uniform
+    float col_sw[BO], col_zb0[BO], col_zb1[BO];  // per-lane output-channel constants
+#pragma unroll
+    for (int b = 0; b < BO; ++b) {
+        const int32_t o = o0 + (wo * BO + b) * 32 + m32;  // o < O_pad always
+        col_sw[b] = sw[o];
+        col_zb0[b] = zb[o];
+        col_zb1[b] = zb[O_pad + o];
+    }
+    int32_t t_end = 0;
+    float t_s0 = 0.0f, t_s1 = 0.0f;
+    if (tid < NG) {
+        t_end = gchunk[tid + 1];
+        t_s0 = s_tab[tid];
+        t_s1 = s_tab[NG + tid];
+    }
 
     // ---- direct-to-LDS load plan: the operands are stored block-tiled, one block =
     // 1 KiB = one chunk of 16 rows (32 rows of packed 4-bit codes), already in the
@@ -157,7 +156,8 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     int dst[CF::LOADS];
 #pragma unroll
     for (int j = 0; j < CF::LOADS; ++j) {
-        const int i = wave + CF::NW * j;
+        int i = wave + CF::NW * j;
+        i = i < CF::AINSTR + CF::BINSTR ? i : CF::AINSTR + CF::BINSTR - 1;
         if (i < CF::AINSTR) {
             int64_t blk = r0 / kARows + i;
             blk = blk < n_ablocks ? blk : n_ablocks - 1;  // clamp: rows past the end are never stored
@@ -244,26 +244,132 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         }
     };
 
+    // ---- prologue: fill the ring ---------------------------------------------------------
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st)
+        if (st < n_chunks) issue_chunk(st);
+
     // ---- group tables in LDS (behind the ring): last chunk of each group and the two
     // scale rows.  Reading them with LDS instructions keeps scalar memory loads out of
     // the main loop, so its LDS waits can be partial (LDS returns in order).
     int32_t *tab_end = reinterpret_cast<int32_t *>(lds + STAGES * CF::STAGE_BYTES);
     float *tab_s = reinterpret_cast<float *>(tab_end + NG);
-    for (int32_t i = tid; i < NG; i += CF::THREADS) {
+    if (tid < NG) {
+        tab_end[tid] = t_end;
+        tab_s[tid] = t_s0;
+        tab_s[NG + tid] = t_s1;
+    }
+    for (int32_t i = tid + CF::THREADS; i < NG; i += CF::THREADS) {  // more groups than threads
         tab_end[i] = gchunk[i + 1];
         tab_s[i] = s_tab[i];
         tab_s[NG + i] = s_tab[NG + i];
     }
-    __syncthreads();
 
-    // ---- prologue: fill the ring, wait for chunk 0 -------------------------------------
+    // ---- pixel classes of the rows this lane holds: bit i of cls1[a] / past[a] says
+    // whether the row in accumulator register i of row-block a is of class 1 / lies past
+    // the end of the tensor.
+    uint32_t cls1[BR], past[BR];
+    bool any1 = false, all1 = true, any_past = false;
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st)
-        if (st < n_chunks) issue_chunk(st);
+    for (int a = 0; a < BR; ++a) {
+        const bool in = row_in[a];
+        const bool c1 = in && row_c1[a] != 0;
+        const uint64_t m1 = __ballot(c1 && kh == 0);   // bit m: row m of the block is class 1
+        const uint64_t mp = __ballot(!in && kh == 0);  // bit m: row m is past the end
+        any1 = any1 || m1 != 0;
+        all1 = all1 && ((m1 | mp) & 0xffffffffull) == 0xffffffffull;
+        any_past = any_past || mp != 0;
+        cls1[a] = 0;
+        past[a] = 0;
+        if (m1 != 0 || mp != 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = 8 * (i >> 2) + 4 * kh + (i & 3);
+                cls1[a] |= (uint32_t)((m1 >> m) & 1) << i;
+                past[a] |= (uint32_t)((mp >> m) & 1) << i;
+            }
+        }
+    }
+    const bool mixed = any1 && !all1;  // wave-uniform
+
+
+    // ---- wait for chunk 0 and for everyone's table entries ---------------------------------
     asm volatile("" ::: "memory");
-    wait_chunks_pending<STAGES - 2, CF::LOADS>(n_chunks - 1);
+    if (NG > CF::THREADS)
+        DGQ_WAIT_VMCNT(0);
+    else
+        wait_chunks_pending<STAGES - 2, CF::LOADS>(n_chunks - 1);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the table writes have landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+
+    auto epilogue = [&](auto mixed_tag, const int32_t p) {
+        constexpr bool MIXED = decltype(mixed_tag)::value;
+        // ---- epilogue: y = sw[o] * sum + zb[class][o] ---------------------------------
+        // Wide path (O a multiple of 4): the tile goes through LDS (over the drained
+        // ring) so that every lane stores 16 contiguous bytes and every row of the
+        // tile leaves as one contiguous run.  LDS layout: row-major [TR][TO] floats with
+        // the 32-float halves of each 64-float span swapped on rows with bit 2 set, which
+        // spreads the two row groups of one register over all banks.
+        const bool wide = (O & 3) == 0;
+        float *tile = reinterpret_cast<float *>(lds);
+        // final values in place: facc <- sw * facc + zb[class]
+#pragma unroll
+        for (int b = 0; b < BO; ++b) {
+            const float swo = col_sw[b];
+            const float zb0 = col_zb0[b], zb1 = col_zb1[b];
+#pragma unroll
+            for (int a = 0; a < BR; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float zz;
+                    if (MIXED)
+                        zz = ((cls1[a] >> i) & 1) ? zb1 : zb0;
+                    else
+                        zz = p ? zb1 : zb0;
+                    facc[a][b][i] = fmaf(swo, facc[a][b][i], zz);
+                }
+        }
+        if (wide) {
+            __syncthreads();  // every wave is done with the last stage
+#pragma unroll
+            for (int b = 0; b < BO; ++b) {
+                const int ol = (wo * BO + b) * 32 + m32;  // column inside the tile
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                        tile[rl * CF::TO + (ol ^ ((rl & 4) << 3))] = facc[a][b][i];
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < BO; ++b) {
+                const int32_t o = o0 + (wo * BO + b) * 32 + m32;
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                        if (o < O && !((past[a] >> i) & 1)) y[(r0 + rl) * O + o] = facc[a][b][i];
+                    }
+            }
+        }
+        if (wide) {
+            __syncthreads();
+            constexpr int kVecPerRow = CF::TO / 4;
+            constexpr int kRowsPerPass = CF::THREADS / kVecPerRow;
+            const int c4 = (tid % kVecPerRow) * 4;
+            const bool col_ok = o0 + c4 < O;
+#pragma unroll 4
+            for (int rl = tid / kVecPerRow; rl < CF::TR; rl += kRowsPerPass) {
+                const int64_t r = r0 + rl;
+                const float4 v = *reinterpret_cast<const float4 *>(tile + rl * CF::TO + (c4 ^ ((rl & 4) << 3)));
+                if (col_ok && r < rows) *reinterpret_cast<float4 *>(y + r * O + o0 + c4) = v;
+            }
+        }
+    };
 
     // The loop and the epilogue, instantiated for uniform-class and mixed-class waves.
     auto run = [&](auto mixed_tag) {
@@ -293,22 +399,14 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                     DGQ_WAIT_VMCNT(0);
                 else
                     wait_chunks_pending<STAGES - 3, CF::LOADS>(n_chunks - 2 - ch);
-#ifndef DGQ_DBG_NO_BARRIER
                 __builtin_amdgcn_s_barrier();
-#endif
                 asm volatile("" ::: "memory");
-#ifndef DGQ_DBG_NO_DMA
                 if (ch + STAGES - 1 < n_chunks) issue_chunk(ch + STAGES - 1);
-#endif
                 load_frags(lds + ((ch + 1) % STAGES) * CF::STAGE_BYTES, 0, af0, bf0);
             }
             mfma_all(af1, bf1, false);
 
-#ifdef DGQ_DBG_NO_FOLD
-            if (ch + 1 == n_chunks) {
-#else
             if (ch + 1 == g_end) {
-#endif
                 // ---- fold this group's int32 block into the fp32 sum with its scale ---
                 if (!MIXED) {
                     const float sg = s_p[g];
@@ -351,53 +449,9 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             }
         }
 
-        // ---- epilogue: y = sw[o] * sum + zb[class][o] ---------------------------------
-        // Wide path (O a multiple of 4): the tile goes through LDS (over the drained
-        // ring) so that every lane stores 16 contiguous bytes and every row of the
-        // tile leaves as one contiguous run.  LDS layout: row-major [TR][TO] floats with
-        // the 32-float halves of each 64-float span swapped on rows with bit 2 set, which
-        // spreads the two row groups of one register over all banks.
-        const bool wide = (O & 3) == 0;
-        float *tile = reinterpret_cast<float *>(lds);
-        if (wide) __syncthreads();  // every wave is done with the last stage
-#pragma unroll
-        for (int b = 0; b < BO; ++b) {
-            const int ol = (wo * BO + b) * 32 + m32;  // column inside the tile
-            const int32_t o = o0 + ol;
-            const float swo = sw[o];  // o < O_pad always
-            const float zb0 = zb[o], zb1 = zb[O_pad + o];
-#pragma unroll
-            for (int a = 0; a < BR; ++a)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                    float zz;
-                    if (MIXED)
-                        zz = ((cls1[a] >> i) & 1) ? zb1 : zb0;
-                    else
-                        zz = p ? zb1 : zb0;
-                    const float v = fmaf(swo, facc[a][b][i], zz);
-                    if (wide) {
-                        tile[rl * CF::TO + (ol ^ ((rl & 4) << 3))] = v;
-                    } else if (o < O && (!any_past || !((past[a] >> i) & 1))) {
-                        y[(r0 + rl) * O + o] = v;
-                    }
-                }
-        }
-        if (wide) {
-            __syncthreads();
-            constexpr int kVecPerRow = CF::TO / 4;
-            constexpr int kRowsPerPass = CF::THREADS / kVecPerRow;
-            const int c4 = (tid % kVecPerRow) * 4;
-            const bool col_ok = o0 + c4 < O;
-#pragma unroll 4
-            for (int rl = tid / kVecPerRow; rl < CF::TR; rl += kRowsPerPass) {
-                const int64_t r = r0 + rl;
-                const float4 v = *reinterpret_cast<const float4 *>(tile + rl * CF::TO + (c4 ^ ((rl & 4) << 3)));
-                if (col_ok && r < rows) *reinterpret_cast<float4 *>(y + r * O + o0 + c4) = v;
-            }
-        }
+        epilogue(mixed_tag, p);
     };
+
     if (mixed)
         run(std::true_type{});
     else
@@ -425,9 +479,16 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
         attr_done = true;
     }
     if (lds > (size_t)kStageBudget) return hipErrorInvalidValue;  // too many groups for the table
+    // Row tiles per super-column: the workgroups resident on one XCD (32 CUs) should
+    // cover whole output rows, so that each row leaves as one long contiguous run,
+    // while still sharing code rows and weight rows in that XCD's L2.
+    const int32_t resident = 32 * (CF::THREADS == 256 ? (CF::OCC >= 4 ? 4 : 2) : 1);
+    int32_t super_rows = (resident + tiles_o - 1) / tiles_o;
+    super_rows = super_rows < 1 ? 1 : (super_rows > 8 ? 8 : super_rows);
+    if (const char *e = getenv("DGQ_SUPER_ROWS")) super_rows = atoi(e) > 0 ? atoi(e) : super_rows;
     hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
                        w.d_zb, g.d_s, g.d_gchunk, rows, w.O, w.O_pad, w.Kp, g.info.n_groups,
-                       tiles_r, tiles_o, per_xcd, y, acc_dump);
+                       tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump);
     return hipGetLastError();
 }
 
@@ -448,14 +509,17 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
                   : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
     }
-    int cfg = g_force_cfg >= 0 ? g_force_cfg : 0;
+    // short contractions are bound by the output write and by per-tile start-up: use
+    // small tiles and four resident workgroups per CU so that the phases overlap
+    int cfg = w.Kp <= 1536 ? 2 : 0;
+    if (g_force_cfg >= 0) cfg = g_force_cfg;
 #define DGQ_CASE(ID, ...)                                                                          \
     case ID:                                                                                       \
         return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st) \
                   : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
     switch (cfg) {
         DGQ_CASE(1, 4, 2, 2, 2, 6, 2);  // 256 x 128, 8 waves of 64 x 64, one workgroup per CU
-        DGQ_CASE(2, 2, 2, 2, 2, 3, 2);  // 128 x 128, 3 stages
+        DGQ_CASE(2, 2, 2, 1, 2, 3, 4);  // 64 x 128, 4 waves of 32 x 64, four workgroups per CU
         default:
             DGQ_CASE(0, 2, 2, 2, 2, 4, 2);  // 128 x 128, 4 waves of 64 x 64, two workgroups per CU
     }
