@@ -4,11 +4,18 @@
 // Section 3.3:  q = clamp(rne((x - z[p,g]) * inv_s[p,g]), 0, 2^b - 1).
 //
 // HBM-bound: every fp32 input is read once (4 B) and one code is written
-// (1 B at 8 bit, 0.5 B at 4 bit), plus one class byte per row.  One wavefront
-// owns a row: it streams the row with 16-byte loads into its LDS slice while
-// reducing max/min with wave shuffles, decides the pixel class, then gathers
-// the row from LDS in the permuted K' order and writes the codes as dwords into
-// the block-tiled layout the GEMM loads (64 contiguous bytes per row and chunk).
+// (1 B at 8 bit, 0.5 B at 4 bit), plus one class byte per row.
+//
+// One wavefront owns a row.  The row arrives in registers with 16-byte loads
+// (issued one row ahead, so the next row is in flight while the current one is
+// processed), is reduced to max/min with wave shuffles, and is parked in the
+// wave's LDS slice.  After the class decision every lane takes 4 (8-bit) or 8
+// (4-bit) consecutive OUTPUT positions, gathers the inputs from LDS through the
+// channel permutation, and writes one dword into the block-tiled code layout the
+// GEMM loads (64 contiguous bytes per row and chunk; the four waves of a
+// workgroup own four consecutive rows each of a 16-row block, so a 1 KiB block
+// is completed by one workgroup).  The permutation (16-bit) and the per-chunk
+// (z, 1/s) pairs sit in LDS, loaded once per workgroup.
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -17,6 +24,7 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;
+constexpr int kRowsPerWave = 4;  // consecutive rows of a 16-row block per wave
 
 __device__ inline float wave_max(float v) {
 #pragma unroll
@@ -42,91 +50,225 @@ __device__ inline float quant1(float x, float z, float inv_s, float qmax) {
     return fminf(fmaxf(rintf(u), 0.0f), qmax);
 }
 
-template <int BITS, bool VEC4>
+// LDS: [perm16: Kp u16, padded to 16 B][cz: 2 * n_chunks float2][rows: 4 * C floats]
+__host__ __device__ inline size_t lds_perm_bytes(int32_t Kp) { return ((size_t)Kp * 2 + 15) & ~(size_t)15; }
+
+// NV: float4 registers per lane that hold one row (C <= NV * 256).
+template <int BITS, int NV>
 __global__ __launch_bounds__(256) void k_quantize_act(
+    const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
+    const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
+    const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
+    uint8_t *__restrict__ row_class) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    uint16_t *perm16 = reinterpret_cast<uint16_t *>(lds_raw);
+    float2 *cz = reinterpret_cast<float2 *>(lds_raw + lds_perm_bytes(Kp));
+    float *rowbuf = reinterpret_cast<float *>(cz + 2 * n_chunks);
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    float *xs = rowbuf + (size_t)wave * C;  // this wave's copy of the row
+    constexpr float qmax = (float)((1 << BITS) - 1);
+    constexpr int kOff = BITS == 8 ? 128 : 0;
+    const int32_t c4n = C >> 2;  // float4 per row
+
+    for (int32_t j = tid; j < Kp; j += 256) {
+        const int32_t c = perm[j];
+        perm16[j] = c >= 0 ? (uint16_t)c : (uint16_t)0xffff;
+    }
+    for (int32_t i = tid; i < 2 * n_chunks; i += 256) cz[i] = make_float2(chunk_z[i], chunk_inv[i]);
+    __syncthreads();
+
+    // rows: block b of 16 rows -> workgroup, wave w takes rows 16b + 4w .. 16b + 4w + 3
+    const int64_t n_blocks = (rows + 15) >> 4;
+    auto row_of = [&](int64_t it) -> int64_t {  // it-th row of this wave's sequence
+        const int64_t blk = (int64_t)blockIdx.x + (it / kRowsPerWave) * gridDim.x;
+        return blk < n_blocks ? (blk << 4) + wave * kRowsPerWave + (it % kRowsPerWave) : rows;
+    };
+    // Branch-free loads: a lane index past the end of the row (and a row index past the
+    // end of the tensor) is clamped to the last valid one, which re-reads a value that is
+    // already part of the row, so max/min and the LDS copy are unaffected.
+    float4 v[NV];
+    int32_t cidx[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int32_t c = lane + k * kWave;
+        cidx[k] = c < c4n ? c : c4n - 1;
+    }
+    auto fetch = [&](int64_t r) {
+        const int64_t re = r < rows ? r : rows - 1;
+        const float4 *x4 = reinterpret_cast<const float4 *>(x + re * C);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) v[k] = x4[cidx[k]];
+    };
+
+    int64_t it = 0;
+    int64_t r = row_of(0);
+    fetch(r);
+    while (true) {
+        // the sequence ends at the first block index past the end; rows inside the last
+        // block but past `rows` are skipped
+        const int64_t blk = (int64_t)blockIdx.x + (it / kRowsPerWave) * gridDim.x;
+        if (blk >= n_blocks) break;
+        const int64_t r_next = row_of(it + 1);
+        if (r < rows) {
+            float mx = -INFINITY, mn = INFINITY;
+            float4 *s4 = reinterpret_cast<float4 *>(xs);
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                s4[cidx[k]] = v[k];
+                mx = fmaxf(fmaxf(fmaxf(v[k].x, v[k].y), fmaxf(v[k].z, v[k].w)), mx);
+                mn = fminf(fminf(fminf(v[k].x, v[k].y), fminf(v[k].z, v[k].w)), mn);
+            }
+            fetch(r_next);  // in flight while this row is quantized
+            mx = wave_max(mx);
+            mn = wave_min(mn);
+            const int p = __fsub_rn(mx, mn) > tau ? 1 : 0;
+            if (lane == 0) row_class[r] = (uint8_t)p;
+            const float2 *czp = cz + p * n_chunks;
+            // The LDS slice is private to this wave and a wave's LDS operations complete
+            // in issue order, so a compiler-level fence is all that is needed.
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+
+            // Output dword d of the row covers positions 4d..4d+3 (8 bit) or 8d..8d+7
+            // (4 bit).  Lane l handles dwords l, l + 64, ...; in the tiled layout that is a
+            // fixed place inside a 64-byte (32-byte) row segment and a chunk index that
+            // advances by 4 (8 bit) or 8 (4 bit) per step.  Four steps are processed
+            // together so that their LDS round trips overlap.
+            constexpr int kPer = BITS == 8 ? 4 : 8;          // positions per dword
+            constexpr int kDwPerChunk = 64 / kPer;            // 16 or 8
+            constexpr int kChunkStep = kWave / kDwPerChunk;   // chunks per step: 4 or 8
+            const int32_t n_dw = Kp / kPer;
+            const int64_t lane_off =
+                (BITS == 8 ? tiled64_offset(r, lane / kDwPerChunk, n_chunks, (lane >> 2) & 3)
+                           : tiled32_offset(r, lane / kDwPerChunk, n_chunks, (lane >> 2) & 1)) +
+                (lane & 3) * 4;
+            int8_t *out_lane = codes + lane_off;
+            for (int32_t d0 = lane; d0 < n_dw; d0 += 4 * kWave) {
+                uint32_t idx[4][kPer];
+                float2 zi[4];
+                bool live[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int32_t d = d0 + t * kWave;
+                    live[t] = d < n_dw;
+                    const int32_t dc = live[t] ? d : n_dw - 1;  // clamp: reads stay in range
+                    zi[t] = czp[dc / kDwPerChunk];
+                    const ushort4 c0 = *reinterpret_cast<const ushort4 *>(perm16 + kPer * dc);
+                    idx[t][0] = c0.x; idx[t][1] = c0.y; idx[t][2] = c0.z; idx[t][3] = c0.w;
+                    if (BITS == 4) {
+                        const ushort4 c1 = *reinterpret_cast<const ushort4 *>(perm16 + kPer * dc + 4);
+                        idx[t][4] = c1.x; idx[t][5] = c1.y; idx[t][6] = c1.z; idx[t][7] = c1.w;
+                    }
+                }
+                float xv[4][kPer];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int k = 0; k < kPer; ++k) {
+                        const uint32_t c = idx[t][k] < (uint32_t)C ? idx[t][k] : 0u;  // padding reads channel 0
+                        xv[t][k] = xs[c];
+                    }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    uint32_t lo = 0, hi = 0;
+#pragma unroll
+                    for (int k = 0; k < kPer; ++k) {
+                        float qf = quant1(xv[t][k], zi[t].x, zi[t].y, qmax);
+                        if (idx[t][k] == 0xffffu) qf = (float)kOff;  // padding: stored container 0
+                        // exact small integer -> byte k of the word
+                        if (k < 4)
+                            lo = __builtin_amdgcn_cvt_pk_u8_f32(qf, k, lo);
+                        else
+                            hi = __builtin_amdgcn_cvt_pk_u8_f32(qf, k - 4, hi);
+                    }
+                    // 8 bit: stored code = q - 128 = q ^ 0x80 per byte.  4 bit: byte i holds
+                    // position i (low nibble) and position i + 4 (high nibble).
+                    const uint32_t word = BITS == 8 ? (lo ^ 0x80808080u) : (lo | (hi << 4));
+                    if (live[t])
+                        *reinterpret_cast<uint32_t *>(out_lane + ((int64_t)(d0 - lane) / kWave + t) *
+                                                                     (kChunkStep * 1024)) = word;
+                }
+            }
+            // the next row overwrites xs
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        } else {
+            fetch(r_next);
+        }
+        r = r_next;
+        ++it;
+    }
+}
+
+// Fallback for channel counts that are not a multiple of 4 (no 16-byte loads):
+// scalar loads straight into LDS, tables read from global memory.
+template <int BITS>
+__global__ __launch_bounds__(256) void k_quantize_act_any(
     const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
     const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
     uint8_t *__restrict__ row_class) {
     extern __shared__ float lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    float *xs = lds + (size_t)wave * C;  // this wave's copy of the row
+    float *xs = lds + (size_t)wave * C;
     constexpr float qmax = (float)((1 << BITS) - 1);
     constexpr int kOff = BITS == 8 ? 128 : 0;
+    constexpr int kPer = BITS == 8 ? 4 : 8;  // positions per output dword
 
     for (int64_t r = (int64_t)blockIdx.x * kWavesPerBlock + wave; r < rows;
          r += (int64_t)gridDim.x * kWavesPerBlock) {
         const float *xr = x + r * C;
         float mx = -INFINITY, mn = INFINITY;
-        if (VEC4) {
-            const float4 *x4 = reinterpret_cast<const float4 *>(xr);
-            float4 *s4 = reinterpret_cast<float4 *>(xs);
-            for (int32_t c = lane; c < (C >> 2); c += kWave) {
-                const float4 v = x4[c];
-                s4[c] = v;
-                mx = fmaxf(fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)), mx);
-                mn = fminf(fminf(fminf(v.x, v.y), fminf(v.z, v.w)), mn);
-            }
-        } else {
-            for (int32_t c = lane; c < C; c += kWave) {
-                const float v = xr[c];
-                xs[c] = v;
-                mx = fmaxf(v, mx);
-                mn = fminf(v, mn);
-            }
+        for (int32_t c = lane; c < C; c += kWave) {
+            const float v = xr[c];
+            xs[c] = v;
+            mx = fmaxf(v, mx);
+            mn = fminf(v, mn);
         }
         mx = wave_max(mx);
         mn = wave_min(mn);
         const int p = __fsub_rn(mx, mn) > tau ? 1 : 0;
         if (lane == 0) row_class[r] = (uint8_t)p;
-        const float *zt = chunk_z + p * n_chunks;
-        const float *it = chunk_inv + p * n_chunks;
-        // The LDS slice is private to this wave and a wave's LDS operations
-        // complete in issue order, so a compiler-level fence is all that is needed.
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-
-        if (BITS == 8) {
-            const int4 *perm4 = reinterpret_cast<const int4 *>(perm);
-            for (int32_t j4 = lane; j4 < (Kp >> 2); j4 += kWave) {
-                const int32_t ch = j4 >> 4;  // 16 dwords per 64-position chunk
-                const float z = zt[ch], is = it[ch];
-                const int4 c = perm4[j4];
-                uint32_t word = 0;
-                const int32_t cc[4] = {c.x, c.y, c.z, c.w};
+        for (int32_t jd = lane; jd < Kp / kPer; jd += kWave) {
+            const int32_t ch = (jd * kPer) >> 6;
+            const float z = chunk_z[p * n_chunks + ch], is = chunk_inv[p * n_chunks + ch];
+            uint32_t word = 0;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    int32_t code = 0;
-                    if (cc[k] >= 0) code = (int32_t)quant1(xs[cc[k]], z, is, qmax) - kOff;
-                    word |= ((uint32_t)code & 0xffu) << (8 * k);
+            for (int k = 0; k < kPer; ++k) {
+                const int32_t c = perm[jd * kPer + k];
+                uint32_t qv = 0;
+                if (c >= 0) {
+                    const int32_t q = (int32_t)quant1(xs[c], z, is, qmax) - kOff;
+                    qv = BITS == 8 ? ((uint32_t)q & 0xffu) : (uint32_t)q;
                 }
-                // dword (j4 & 15) of chunk ch: slot (j4 >> 2) & 3, dword j4 & 3 of the slot
-                *reinterpret_cast<uint32_t *>(codes + tiled64_offset(r, ch, n_chunks, (j4 >> 2) & 3) +
-                                              (j4 & 3) * 4) = word;
+                word |= BITS == 8 ? qv << (8 * k) : qv << (k < 4 ? 8 * k : 8 * (k - 4) + 4);
             }
-        } else {
-            const int4 *perm4 = reinterpret_cast<const int4 *>(perm);
-            for (int32_t j8 = lane; j8 < (Kp >> 3); j8 += kWave) {
-                const int32_t ch = j8 >> 3;  // 8 dwords per 64-position chunk
-                const float z = zt[ch], is = it[ch];
-                const int4 c0 = perm4[2 * j8], c1 = perm4[2 * j8 + 1];
-                const int32_t cc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-                uint32_t word = 0;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    uint32_t qv = 0;
-                    if (cc[k] >= 0) qv = (uint32_t)quant1(xs[cc[k]], z, is, qmax);
-                    // byte i of the dword holds position i (low nibble) and i + 4 (high)
-                    word |= qv << (k < 4 ? 8 * k : 8 * (k - 4) + 4);
-                }
-                *reinterpret_cast<uint32_t *>(codes + tiled32_offset(r, ch, n_chunks, (j8 >> 2) & 1) +
-                                              (j8 & 3) * 4) = word;
-            }
+            const int64_t off = BITS == 8 ? tiled64_offset(r, ch, n_chunks, (jd >> 2) & 3)
+                                          : tiled32_offset(r, ch, n_chunks, (jd >> 2) & 1);
+            *reinterpret_cast<uint32_t *>(codes + off + (jd & 3) * 4) = word;
         }
-        // the next row overwrites xs
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const int32_t *,
+                      const float *, const float *, float, int8_t *, uint8_t *);
+
+// NV = float4 loads per lane per row; exact for the usual channel counts (320 .. 5120).
+template <int BITS>
+Kern pick_vec(int32_t C) {
+    const int nv = (C + 255) / 256;
+    if (nv <= 2) return k_quantize_act<BITS, 2>;
+    if (nv <= 3) return k_quantize_act<BITS, 3>;
+    if (nv <= 5) return k_quantize_act<BITS, 5>;
+    if (nv <= 8) return k_quantize_act<BITS, 8>;
+    if (nv <= 10) return k_quantize_act<BITS, 10>;
+    if (nv <= 20) return k_quantize_act<BITS, 20>;
+    return k_quantize_act<BITS, 40>;
 }
 
 }  // namespace
@@ -134,18 +276,27 @@ __global__ __launch_bounds__(256) void k_quantize_act(
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
                                uint8_t *row_class, hipStream_t st) {
     const int32_t C = g.info.channels, Kp = g.info.k_padded;
-    const size_t lds = sizeof(float) * (size_t)C * kWavesPerBlock;
-    int64_t blocks = (rows + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t cap = 256 * 8;  // a few resident blocks per CU; rows are strided over them
-    if (blocks > cap) blocks = cap;
-    const bool vec4 = (C % 4) == 0;
-    using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const int32_t *,
-                          const float *, const float *, float, int8_t *, uint8_t *);
+    const bool vec4 = (C % 4) == 0 && C < 65535;
     Kern kern;
-    if (g.info.act_bits == 8)
-        kern = vec4 ? k_quantize_act<8, true> : k_quantize_act<8, false>;
-    else
-        kern = vec4 ? k_quantize_act<4, true> : k_quantize_act<4, false>;
+    size_t lds;
+    int64_t blocks;
+    if (vec4) {
+        kern = g.info.act_bits == 8 ? pick_vec<8>(C) : pick_vec<4>(C);
+        lds = lds_perm_bytes(Kp) + sizeof(float) * 4 * (size_t)g.n_chunks +
+              sizeof(float) * (size_t)C * kWavesPerBlock;
+        blocks = (rows + 15) / 16;
+        // resident workgroups per CU by LDS; every workgroup walks several 16-row blocks
+        int per_cu = (int)((160 * 1024) / lds);
+        per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+        const int64_t cap = 256 * (int64_t)per_cu;
+        if (blocks > cap) blocks = cap;
+    } else {
+        kern = g.info.act_bits == 8 ? k_quantize_act_any<8> : k_quantize_act_any<4>;
+        lds = sizeof(float) * (size_t)C * kWavesPerBlock;
+        blocks = (rows + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (blocks > 2048) blocks = 2048;
+    }
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
