@@ -101,7 +101,9 @@ def main():
         attns.append(dict(name=name, B=B, N=N, H=H, d=d, nk=nk, q=up(c["Q"]), k=up(c["K"]),
                           v=up(c["V"]), kb=up(c["key_bias"]),
                           out=torch.empty((B, N, H, d), dtype=torch.float32, device=dev),
-                          s=torch.empty(B, dtype=torch.float32, device=dev)))
+                          s=torch.empty(B, dtype=torch.float32, device=dev),
+                          ws=torch.empty(max(16, dgq.dgq_xattn_workspace_bytes(B, N, H, d, nk)),
+                                         dtype=torch.uint8, device=dev)))
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
@@ -131,7 +133,8 @@ def main():
             dgq.dgq_linear(m["g"], m["wt"], m["codes"], m["cls"], y=ent["y"])
         else:
             a, bits = key
-            dgq.dgq_xattn_logq(a["q"], a["k"], a["v"], a["kb"], bits, out=a["out"], scale_out=a["s"])
+            dgq.dgq_xattn_logq(a["q"], a["k"], a["v"], a["kb"], bits, out=a["out"], scale_out=a["s"],
+                               workspace=a["ws"])
 
     def step(events=None):
         for ci, (kind, key, _) in enumerate(calls):

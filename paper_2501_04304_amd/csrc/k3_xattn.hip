@@ -10,13 +10,41 @@
 // probability can be coded before all of them exist: two kernels.  Both
 // recompute the logits from Q (a second read of Q costs less than storing the
 // [N, nk] probabilities).  The code is evaluated in the log domain,
-//   -log2(A/s) = log2(s) + log2(sum_j e^(L_ij - m_i)) - (L_ij - m_i) * log2(e),
+//   -log2(A/s) = log2(s) + lse2_i - L_ij * log2(e),   lse2_i = log2(sum_j 2^(L_ij log2 e)),
 // which needs no exponential per element and is exact to ~1e-6 in log2 units;
 // a probability below 2^-150 rounds to zero in fp32 and takes the top code.
 //
-// One thread owns one (query, head) row: the nk logits live in registers, the
-// keys (then the values, reusing the same LDS) of the (batch, head) pair are
-// broadcast from LDS.
+// Matrix-core path (head dim a multiple of 8 up to 96, nk <= 126)
+// ----------------------------------------------------------------
+// A workgroup owns one (prompt, head) pair and a range of queries; its four
+// wavefronts each take 32 queries at a time.  The logits are computed
+// TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_f16: a lane then holds, for
+// ONE query (lane % 32), half of that query's keys in its accumulator registers,
+// so the soft-max maximum and sum are register reductions plus one exchange
+// with lane ^ 32.  fp32 accuracy comes from splitting both operands into two
+// fp16 pieces, x = hi + lo (round to nearest; lo may be subnormal, which these
+// instructions honour), and adding three products hi*hi + hi*lo + lo*hi in the
+// fp32 accumulator; the dropped lo*lo term is below 2^-24 relative.  Inputs
+// must stay inside the fp16 range (|k| and |q| log2(e)/sqrt(d) below 65504).
+// log2(e)/sqrt(d) is folded into Q before the
+// split and key_bias*log2(e) is the accumulator's start value, with -inf for the
+// padding keys so that they vanish from maximum and sum without a mask.
+//
+// Pass 1 writes lse2_i per (prompt, head, query) into the workspace and folds
+// max_{j>=1} 2^(S_ij - lse2_i) into scale_out[b].  Pass 2 recomputes S^T the
+// same way (bit-identical), turns each register into its code, and builds
+// 2^-code directly as a bf16 bit pattern (an exact power of two).  The
+// accumulator layout of S^T is, register for register, the B-operand layout of
+// the next product Out^T = V^T P^T (v_mfma_f32_32x32x16_bf16) once the key order
+// inside each 16-key step is permuted the same way on the V^T side, so the
+// probabilities never leave the registers.  V is split into two bf16 pieces
+// (2^-17 relative).  The <start> column is carried through the same product:
+// a' = A_i0 / s_b, split into three bf16 pieces (24 bits), occupies key slot 0
+// and the last two padding slots, whose V^T columns hold V_0.  The result is
+// multiplied by s_b on the way out.
+//
+// Other shapes use the plain fp32 kernel at the bottom of the file: one thread
+// per (query, head), logits in registers, K then V broadcast from LDS.
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -36,6 +64,377 @@ __device__ inline float wave_max(float v) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
     return v;
 }
+
+// ======================================================================================
+// Matrix-core path
+// ======================================================================================
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// NKB: 32-key blocks (keys padded to 32*NKB, the last two slots reserved).
+// KS:  16-wide steps over the head dimension (d padded to 16*KS).
+template <int NKB_, int KS_>
+struct XCfg {
+    static constexpr int NKB = NKB_, KS = KS_;
+    static constexpr int NKP = 32 * NKB;        // padded keys
+    static constexpr int DB = (KS + 1) / 2;     // 32-wide blocks of output dims
+    static constexpr int DP = 32 * DB;
+    static constexpr int KROW = 16 * KS + 8;    // halves per K row (+16 B against bank conflicts)
+    static constexpr int VROW = NKP + 8;        // bf16 per V^T row
+    static constexpr int NBIAS = 2 * NKB * 16;  // floats: start values per lane half
+    static constexpr size_t lds_pass1 = (size_t)NKP * KROW * 2 * 2 + NBIAS * 4;
+    static constexpr size_t lds_pass2 = lds_pass1 + (size_t)DP * VROW * 2 * 2;
+};
+
+__device__ inline uint32_t pack_h2(float a, float b) {
+    v2h r = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// x = hi + lo, both fp16, round to nearest (lo may be subnormal: the matrix cores honour
+// subnormal fp16 inputs).
+struct HiLo {
+    uint32_t hi, lo;
+};
+__device__ inline HiLo split_h2(float a, float b) {
+    const v2h h = {(_Float16)a, (_Float16)b};
+    HiLo r;
+    r.hi = __builtin_bit_cast(uint32_t, h);
+    // The residual must be taken from the very halves the matrix cores will see.  Without
+    // this opaque copy the compiler converts twice, with the packed and with the scalar
+    // instruction, and the two do not round alike next to a tie, which breaks hi + lo = x.
+    asm("" : "+v"(r.hi));
+    const v2h hr = __builtin_bit_cast(v2h, r.hi);
+    r.lo = pack_h2(a - (float)hr.x, b - (float)hr.y);
+    return r;
+}
+
+__device__ inline uint32_t bf16_rne_bits(float x) {  // upper 16 bits hold the bf16
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u & 0xFFFF0000u;
+}
+
+// key held by accumulator register i of key block blk in lane half hh
+__device__ __host__ constexpr int key_of(int blk, int i, int hh) {
+    return 32 * blk + 8 * (i >> 2) + 4 * hh + (i & 3);
+}
+
+template <class CF, int PASS, bool DUMP>
+__global__ __launch_bounds__(256, 2) void k_xattn_mfma(
+    const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
+    const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
+    float q_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
+    float *__restrict__ lse2, uint8_t *__restrict__ codes_dump) {
+    constexpr int NKB = CF::NKB, KS = CF::KS, NKP = CF::NKP, DB = CF::DB, DP = CF::DP;
+    constexpr int KROW = CF::KROW, VROW = CF::VROW;
+    extern __shared__ __align__(16) unsigned char smem[];
+    _Float16 *Kh = reinterpret_cast<_Float16 *>(smem);
+    _Float16 *Kl = Kh + NKP * KROW;
+    float *biasv = reinterpret_cast<float *>(Kl + NKP * KROW);
+    uint16_t *Vh = reinterpret_cast<uint16_t *>(biasv + CF::NBIAS);
+    uint16_t *Vl = Vh + DP * VROW;
+    __shared__ float red[4];
+
+    const int32_t b = blockIdx.z, head = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 31, hh = lane >> 5;
+    const int64_t hs = (int64_t)H * d;  // stride between tokens
+
+    // ---- stage K (two fp16 pieces), the start values and, in pass 2, V^T ---------------
+    {
+        const float *kb = k + ((int64_t)b * nk * H + head) * d;
+        for (int idx = tid; idx < NKP * KS * 4; idx += 256) {
+            const int j = idx / (KS * 4), t4 = (idx - j * (KS * 4)) * 4;
+            float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (j < nk && t4 < d) x = *reinterpret_cast<const float4 *>(kb + (int64_t)j * hs + t4);
+            const HiLo p0 = split_h2(x.x, x.y), p1 = split_h2(x.z, x.w);
+            const u32x2 hi = {p0.hi, p1.hi}, lo = {p0.lo, p1.lo};
+            *reinterpret_cast<u32x2 *>(Kh + j * KROW + t4) = hi;
+            *reinterpret_cast<u32x2 *>(Kl + j * KROW + t4) = lo;
+        }
+        for (int idx = tid; idx < CF::NBIAS; idx += 256) {
+            const int half = idx / (NKB * 16), r = idx - half * (NKB * 16);
+            const int key = key_of(r >> 4, r & 15, half);
+            biasv[idx] = key < nk ? (key_bias ? key_bias[key] * kLog2e : 0.0f) : -INFINITY;
+        }
+        if (PASS == 2) {
+            const float *vb = v + ((int64_t)b * nk * H + head) * d;
+            for (int idx = tid; idx < NKP * (DP / 4); idx += 256) {
+                const int j = idx / (DP / 4), t4 = (idx - j * (DP / 4)) * 4;
+                // the last two key slots repeat V_0 for the low pieces of the <start> weight
+                const int js = j >= NKP - 2 ? 0 : j;
+                float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (js < nk && t4 < d)
+                    x = *reinterpret_cast<const float4 *>(vb + (int64_t)js * hs + t4);
+                const float xe[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t hb = bf16_rne_bits(xe[e]);
+                    const uint32_t lb = bf16_rne_bits(xe[e] - __uint_as_float(hb));
+                    Vh[(t4 + e) * VROW + j] = (uint16_t)(hb >> 16);
+                    Vl[(t4 + e) * VROW + j] = (uint16_t)(lb >> 16);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    const int32_t q_begin = blockIdx.x * qpw;
+    const int32_t q_end = min(q_begin + qpw, N);
+    const float *qbase = q + ((int64_t)b * N * H + head) * d;
+
+    // raw fp32 query slices of this lane: dims 16 s + 8 hh .. + 7 of query qi
+    struct QRaw {
+        float4 x[KS][2];
+        float lse;
+    };
+    auto load_q = [&](int32_t q0) {
+        QRaw r;
+        const int32_t qi = min(q0 + n, N - 1);
+        const float *p = qbase + (int64_t)qi * hs;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            // past the head dimension K is zero in LDS: any finite value will do there
+            const int32_t t = min(16 * s + 8 * hh, d - 8);
+            r.x[s][0] = *reinterpret_cast<const float4 *>(p + t);
+            r.x[s][1] = *reinterpret_cast<const float4 *>(p + t + 4);
+        }
+        r.lse = 0.0f;
+        if (PASS == 2) r.lse = lse2[((int64_t)b * H + head) * N + qi];
+        return r;
+    };
+
+    float s_b = 0.0f, s_eff = 1.0f, l2s = 0.0f;
+    uint32_t pmask = 0xFFFFFFFFu;
+    if (PASS == 2) {
+        s_b = scale[b];
+        // no probability above zero outside the <start> column: only that column contributes
+        s_eff = s_b > 0.0f ? s_b : 1.0f;
+        pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;
+        l2s = __log2f(s_eff);
+    }
+    const float qmax = (float)((1 << bits) - 1);
+    float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
+
+    QRaw cur = load_q(q_begin + 32 * wave);
+    for (int32_t q0 = q_begin + 32 * wave; q0 < q_end; q0 += 128) {
+        const int32_t qi = q0 + n;
+        const bool valid = qi < N;
+        // The K and V^T fragments of a lane do not depend on the query block; an opaque
+        // zero keeps their LDS reads inside the loop (hoisted, they would not fit in
+        // the register file next to the accumulators).
+        int lds_ofs = 0;
+        asm volatile("" : "+v"(lds_ofs));
+        // ---- split the scaled query into fp16 pieces ---------------------------------------
+        u32x4 qh[KS], ql[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const float4 a = cur.x[s][0], c = cur.x[s][1];
+            const HiLo p0 = split_h2(a.x * q_scale, a.y * q_scale);
+            const HiLo p1 = split_h2(a.z * q_scale, a.w * q_scale);
+            const HiLo p2 = split_h2(c.x * q_scale, c.y * q_scale);
+            const HiLo p3 = split_h2(c.z * q_scale, c.w * q_scale);
+            qh[s] = u32x4{p0.hi, p1.hi, p2.hi, p3.hi};
+            ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
+        }
+        const float lse_i = cur.lse;
+        cur = load_q(q0 + 128);  // prefetch (address clamped, always in bounds)
+
+        // ---- S^T = K Q^T in log2 units --------------------------------------------------------
+        v16f sm[NKB];
+#pragma unroll
+        for (int blk = 0; blk < NKB; ++blk) {
+            const float4 *bp = reinterpret_cast<const float4 *>(biasv + hh * (NKB * 16) + blk * 16);
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const float4 t = bp[a];
+                sm[blk][4 * a + 0] = t.x;
+                sm[blk][4 * a + 1] = t.y;
+                sm[blk][4 * a + 2] = t.z;
+                sm[blk][4 * a + 3] = t.w;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const v8h bqh = __builtin_bit_cast(v8h, qh[s]);
+            const v8h bql = __builtin_bit_cast(v8h, ql[s]);
+#pragma unroll
+            for (int blk = 0; blk < NKB; ++blk) {
+                const int off = (32 * blk + n) * KROW + 16 * s + 8 * hh + lds_ofs;
+                const v8h akh = __builtin_bit_cast(v8h, *reinterpret_cast<const u32x4 *>(Kh + off));
+                const v8h akl = __builtin_bit_cast(v8h, *reinterpret_cast<const u32x4 *>(Kl + off));
+                sm[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bqh, sm[blk], 0, 0, 0);
+                sm[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bql, sm[blk], 0, 0, 0);
+                sm[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(akl, bqh, sm[blk], 0, 0, 0);
+            }
+        }
+
+        if (PASS == 1) {
+            // ---- soft-max statistics of the lane's query ---------------------------------------
+            float rest = -INFINITY;  // every key of this lane except register (0, 0)
+#pragma unroll
+            for (int blk = 0; blk < NKB; ++blk)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (blk || i) rest = fmaxf(rest, sm[blk][i]);
+            const float s00 = sm[0][0];  // key 0 in the lower lane half, key 4 in the upper
+            float m = fmaxf(rest, s00);
+            float m1 = fmaxf(rest, hh == 0 ? -INFINITY : s00);
+            m = fmaxf(m, __shfl_xor(m, 32, kWave));
+            m1 = fmaxf(m1, __shfl_xor(m1, 32, kWave));
+            float sum = 0.0f;
+#pragma unroll
+            for (int blk = 0; blk < NKB; ++blk)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(sm[blk][i] - m);
+            sum += __shfl_xor(sum, 32, kWave);
+            const float lse = m + __log2f(sum);
+            if (valid) {
+                run_l2 = fmaxf(run_l2, m1 - lse);
+                if (hh == 0) lse2[((int64_t)b * H + head) * N + qi] = lse;
+            }
+            continue;
+        }
+
+        // ---- pass 2: codes -> bf16 powers of two, packed as the next B operand --------------
+        const float c0 = l2s + lse_i;        // code = rne(c0 - S)
+        const float ufl = lse_i - 150.0f;    // S below this: A rounds to zero in fp32
+        uint8_t *cd = nullptr;
+        if (DUMP) cd = codes_dump + ((((int64_t)b * H + head) * N + qi) * (int64_t)(nk - 1));
+        uint32_t pk[NKB][8];
+#pragma unroll
+        for (int blk = 0; blk < NKB; ++blk)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                uint32_t e[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const float sv = sm[blk][i + u];
+                    float c = fminf(fmaxf(rintf(c0 - sv), 0.0f), qmax);
+                    c = sv < ufl ? qmax : c;
+                    if (DUMP) {
+                        const int key = key_of(blk, i + u, hh);
+                        if (valid && key >= 1 && key < nk) cd[key - 1] = (uint8_t)c;
+                    }
+                    const int ex = (int)(127.0f - c);  // biased exponent of 2^-c; <= 0: flush
+                    e[u] = (uint32_t)max(ex, 0);
+                }
+                pk[blk][i >> 1] = ((e[0] << 7) | (e[1] << 23)) & pmask;
+            }
+        {
+            // <start> weight a' = A_i0 / s in three bf16 pieces (truncation keeps each exact)
+            const float s_start = __shfl(sm[0][0], n, kWave);
+            const float ap = __builtin_amdgcn_exp2f(s_start - c0);
+            const uint32_t a1 = __float_as_uint(ap) & 0xFFFF0000u;
+            const float r1 = ap - __uint_as_float(a1);
+            const uint32_t a2 = __float_as_uint(r1) & 0xFFFF0000u;
+            const float r2 = r1 - __uint_as_float(a2);
+            const uint32_t a3 = __float_as_uint(r2) & 0xFFFF0000u;
+            if (hh == 0) pk[0][0] = (pk[0][0] & 0xFFFF0000u) | (a1 >> 16);
+            if (hh == 1) pk[NKB - 1][7] = (a2 >> 16) | a3;  // key slots NKP-2 and NKP-1
+        }
+
+        // ---- Out^T = V^T P^T -----------------------------------------------------------------
+        v16f o[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
+#pragma unroll
+        for (int s16 = 0; s16 < 2 * NKB; ++s16) {
+            u32x4 pb;
+            pb.x = pk[s16 >> 1][4 * (s16 & 1) + 0];
+            pb.y = pk[s16 >> 1][4 * (s16 & 1) + 1];
+            pb.z = pk[s16 >> 1][4 * (s16 & 1) + 2];
+            pb.w = pk[s16 >> 1][4 * (s16 & 1) + 3];
+            const v8bf bp = __builtin_bit_cast(v8bf, pb);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                // slots 0..3: keys 16 s16 + 4 hh + (0..3); slots 4..7: the same + 8
+                const int off = (32 * db + n) * VROW + 16 * s16 + 4 * hh + lds_ofs;
+                const u32x2 h0 = *reinterpret_cast<const u32x2 *>(Vh + off);
+                const u32x2 h1 = *reinterpret_cast<const u32x2 *>(Vh + off + 8);
+                const u32x2 l0 = *reinterpret_cast<const u32x2 *>(Vl + off);
+                const u32x2 l1 = *reinterpret_cast<const u32x2 *>(Vl + off + 8);
+                const u32x4 ah = {h0.x, h0.y, h1.x, h1.y};
+                const u32x4 al = {l0.x, l0.y, l1.x, l1.y};
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ah), bp,
+                                                                 o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, al), bp,
+                                                                 o[db], 0, 0, 0);
+            }
+        }
+        float *orow = out + ((int64_t)b * N * H + head) * d + (int64_t)qi * hs;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int dim = 32 * db + 8 * a + 4 * hh;
+                if (valid && dim < d) {
+                    float4 t;
+                    t.x = o[db][4 * a + 0] * s_eff;
+                    t.y = o[db][4 * a + 1] * s_eff;
+                    t.z = o[db][4 * a + 2] * s_eff;
+                    t.w = o[db][4 * a + 3] * s_eff;
+                    *reinterpret_cast<float4 *>(orow + dim) = t;
+                }
+            }
+    }
+
+    if (PASS == 1) {
+        float amax = wave_max(run_l2);
+        if (lane == 0) red[wave] = amax;
+        __syncthreads();
+        if (tid == 0) {
+            amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+            // probabilities are non-negative: their bit patterns order like unsigned ints
+            atomicMax(reinterpret_cast<unsigned int *>(scale + b),
+                      __float_as_uint(__builtin_amdgcn_exp2f(amax)));
+        }
+    }
+}
+
+template <class CF>
+hipError_t launch_mfma(const float *q, const float *k, const float *v, const float *key_bias,
+                       int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
+                       float *out, float *scale_out, uint8_t *codes_dump, float *lse2,
+                       hipStream_t st) {
+    auto k1 = k_xattn_mfma<CF, 1, false>;
+    auto k2 = codes_dump ? k_xattn_mfma<CF, 2, true> : k_xattn_mfma<CF, 2, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k1),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)CF::lds_pass1);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)CF::lds_pass2);
+    if (e != hipSuccess) return e;
+    // queries per workgroup: 128 per trip of the four waves, more trips once there are
+    // enough workgroups to fill the chip several times over
+    const int64_t blocks128 = (N + 127) / 128;
+    int64_t trips = (int64_t)B * H * blocks128 / 1024;
+    trips = trips < 1 ? 1 : (trips > 8 ? 8 : trips);
+    const int32_t qpw = (int32_t)(128 * trips);
+    const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B);
+    const float q_scale = (float)(1.4426950408889634 / sqrt((double)d));
+    hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
+    hipLaunchKernelGGL(k1, grid, dim3(256), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
+                       bits, q_scale, qpw, out, scale_out, lse2, codes_dump);
+    hipLaunchKernelGGL(k2, grid, dim3(256), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
+                       bits, q_scale, qpw, out, scale_out, lse2, codes_dump);
+    return hipGetLastError();
+}
+
+bool mfma_shape(int32_t d, int32_t nk) { return (d % 8) == 0 && d <= 96 && nk + 2 <= 128; }
+
+// ======================================================================================
+// Plain fp32 path (any head dim up to 256, any nk up to 128)
+// ======================================================================================
 
 // Cooperative copy of one [nk, d] head slice (row stride H*d) into LDS
 // [NKP][dpad], zero-filling the padding.
@@ -202,11 +601,33 @@ hipError_t launch_passes(const float *q, const float *k, const float *v, const f
 
 }  // namespace
 
-size_t xattn_workspace_bytes(int32_t, int32_t, int32_t, int32_t, int32_t) { return 0; }
+// The matrix-core path keeps one float (log2 of the soft-max denominator, shifted by the
+// row maximum) per (prompt, head, query) between its two passes.
+size_t xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk) {
+    if (!mfma_shape(d, nk)) return 0;
+    return ((size_t)B * H * N * sizeof(float) + 255) / 256 * 256;
+}
 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
-                        float *out, float *scale_out, uint8_t *codes_dump, void *, hipStream_t st) {
+                        float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
+                        hipStream_t st) {
+    if (mfma_shape(d, nk)) {
+        float *lse2 = static_cast<float *>(workspace);
+        const int ks = d <= 48 ? 3 : (d <= 64 ? 4 : 6);
+        const int nkb = nk + 2 <= 96 ? 3 : 4;
+#define DGQ_XATTN_CASE(NKB, KS)                                                              \
+    if (nkb == NKB && ks == KS)                                                              \
+        return launch_mfma<XCfg<NKB, KS>>(q, k, v, key_bias, B, N, H, d, nk, bits, out,       \
+                                          scale_out, codes_dump, lse2, st);
+        DGQ_XATTN_CASE(3, 3)
+        DGQ_XATTN_CASE(3, 4)
+        DGQ_XATTN_CASE(3, 6)
+        DGQ_XATTN_CASE(4, 3)
+        DGQ_XATTN_CASE(4, 4)
+        DGQ_XATTN_CASE(4, 6)
+#undef DGQ_XATTN_CASE
+    }
     if (nk <= 80)
         return launch_passes<80>(q, k, v, key_bias, B, N, H, d, nk, bits, out, scale_out,
                                  codes_dump, st);

@@ -3,8 +3,11 @@
 Codes are compared bit-exactly on margin-guarded inputs (oracle/guard.py: no
 rounding decision within 2^-13 log2 units of a boundary); on raw inputs every
 element whose oracle margin is at least that large must still match and the
-few others may differ by one step.  The prompt scale is an fp32 output
-(relative 1e-6), the product is held to 1e-4 * max|ref|."""
+few others may differ by one step.  The prompt scale is exp2 of an fp32 logit
+difference: logits reach 2^4..2^5 in log2 units, where one fp32 ulp is 2e-6 to
+4e-6, so a handful of roundings (input scaling, the accumulation, the log-sum)
+bound its relative error by S_RTOL = 1e-5.  The product is held to
+1e-4 * max|ref|."""
 import numpy as np
 import pytest
 
@@ -12,6 +15,8 @@ import dgq_inputs as di
 from support import assert_close_fp32
 
 pytestmark = pytest.mark.gpu
+
+S_RTOL = 1e-5
 
 
 @pytest.fixture(scope="module")
@@ -44,7 +49,7 @@ def _compare(dgq, oracle, c, bits, exact=True, use_bias=True):
     from oracle.guard import DELTA
     ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"] if use_bias else None, bits)
     out, s, codes = _gpu(dgq, c, bits, use_bias)
-    assert np.all(np.abs(s - ref["s"]) <= 1e-6 * ref["s"])
+    assert np.all(np.abs(s - ref["s"]) <= S_RTOL * ref["s"])
     safe = ref["margin"] >= DELTA
     assert np.array_equal(codes[safe], ref["codes"][safe])
     if exact:
@@ -119,7 +124,7 @@ def test_config5_shape_sampled(dgq, oracle):
     for b in (0, B - 1):
         sub = {k: (v[b:b + 1] if k != "key_bias" else v) for k, v in c.items()}
         ref = oracle.xattn(sub["Q"], sub["K"], sub["V"], sub["key_bias"], 8)
-        assert abs(s[b] - ref["s"][0]) <= 1e-6 * ref["s"][0]
+        assert abs(s[b] - ref["s"][0]) <= S_RTOL * ref["s"][0]
         safe = ref["margin"][0] >= DELTA
         assert np.array_equal(codes[b][safe], ref["codes"][0][safe])
         assert np.abs(codes[b].astype(int) - ref["codes"][0].astype(int)).max() <= 1
@@ -142,4 +147,4 @@ def test_scale_buffer_is_reset_between_calls(dgq, oracle):
                                     8, scale_out=s_buf)
         torch.cuda.synchronize()
         ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8)
-        assert abs(s.item() - ref["s"][0]) <= 1e-6 * ref["s"][0]
+        assert abs(s.item() - ref["s"][0]) <= S_RTOL * ref["s"][0]
