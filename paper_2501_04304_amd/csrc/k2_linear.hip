@@ -112,7 +112,10 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int32_t tile_o = (t % in_super) / gsz;
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    // the wave index is uniform: say so, and everything derived from it (block
+    // pointers, LDS stage addresses, the M0 values of the direct-to-LDS loads) is
+    // computed on the scalar unit instead of per lane
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wr = wave / CF::WO, wo = wave % CF::WO;
     const int m32 = lane & 31, kh = lane >> 5;
     const int64_t r0 = (int64_t)tile_r * CF::TR;
@@ -305,15 +308,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
 
     auto epilogue = [&](auto mixed_tag, const int32_t p) {
         constexpr bool MIXED = decltype(mixed_tag)::value;
-        // ---- epilogue: y = sw[o] * sum + zb[class][o] ---------------------------------
-        // Wide path (O a multiple of 4): the tile goes through LDS (over the drained
-        // ring) so that every lane stores 16 contiguous bytes and every row of the
-        // tile leaves as one contiguous run.  LDS layout: row-major [TR][TO] floats with
-        // the 32-float halves of each 64-float span swapped on rows with bit 2 set, which
-        // spreads the two row groups of one register over all banks.
-        const bool wide = (O & 3) == 0;
-        float *tile = reinterpret_cast<float *>(lds);
-        // final values in place: facc <- sw * facc + zb[class]
+        // ---- epilogue: y = sw[o] * sum + zb[class][o], in place -------------------------
 #pragma unroll
         for (int b = 0; b < BO; ++b) {
             const float swo = col_sw[b];
@@ -330,19 +325,30 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                     facc[a][b][i] = fmaf(swo, facc[a][b][i], zz);
                 }
         }
-        if (wide) {
-            __syncthreads();  // every wave is done with the last stage
+        // Register i of a block holds row 8 (i / 4) + 4 kh + i % 4 at column m32: one
+        // store instruction writes two 128-byte row pieces.  Interior tiles use a scalar
+        // row pointer plus one per-lane 32-bit offset, so the 16 * BR * BO stores need no
+        // vector address arithmetic; edge tiles predicate every element.
+        const bool interior = r0 + CF::TR <= rows && o0 + CF::TO <= O;
+        if (interior) {
+            const uint32_t lane_off = (uint32_t)(4 * kh * O + m32) * 4u;
+            char *tile_ptr = reinterpret_cast<char *>(y + r0 * O + o0);
 #pragma unroll
-            for (int b = 0; b < BO; ++b) {
-                const int ol = (wo * BO + b) * 32 + m32;  // column inside the tile
+            for (int a = 0; a < BR; ++a)
 #pragma unroll
-                for (int a = 0; a < BR; ++a)
+                for (int i = 0; i < 16; ++i) {
+                    const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + (i & 3);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                        tile[rl * CF::TO + (ol ^ ((rl & 4) << 3))] = facc[a][b][i];
+                    for (int b = 0; b < BO; ++b) {
+                        // scalar base + 32-bit lane offset, spelled out so that no vector
+                        // instruction is spent on the address
+                        char *rp = tile_ptr + ((int64_t)rl * O + (wo * BO + b) * 32) * 4;
+                        asm volatile("global_store_dword %0, %1, %2 nt"
+                                     :
+                                     : "v"(lane_off), "v"(facc[a][b][i]), "s"(rp)
+                                     : "memory");
                     }
-            }
+                }
         } else {
 #pragma unroll
             for (int b = 0; b < BO; ++b) {
@@ -354,19 +360,6 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                         const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
                         if (o < O && !((past[a] >> i) & 1)) y[(r0 + rl) * O + o] = facc[a][b][i];
                     }
-            }
-        }
-        if (wide) {
-            __syncthreads();
-            constexpr int kVecPerRow = CF::TO / 4;
-            constexpr int kRowsPerPass = CF::THREADS / kVecPerRow;
-            const int c4 = (tid % kVecPerRow) * 4;
-            const bool col_ok = o0 + c4 < O;
-#pragma unroll 4
-            for (int rl = tid / kVecPerRow; rl < CF::TR; rl += kRowsPerPass) {
-                const int64_t r = r0 + rl;
-                const float4 v = *reinterpret_cast<const float4 *>(tile + rl * CF::TO + (c4 ^ ((rl & 4) << 3)));
-                if (col_ok && r < rows) *reinterpret_cast<float4 *>(y + r * O + o0 + c4) = v;
             }
         }
     };
@@ -468,7 +461,6 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     const int32_t per_xcd = (int32_t)((T + 7) / 8);
     const dim3 grid((unsigned)(per_xcd * 8));
     size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES + 12 * (size_t)g.info.n_groups;
-    if (lds < (size_t)CF::TR * CF::TO * 4) lds = (size_t)CF::TR * CF::TO * 4;  // epilogue tile
     auto kern = k_linear<CF, DUMP>;
     static bool attr_done = false;  // per instantiation
     if (!attr_done) {
@@ -482,7 +474,8 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     // Row tiles per super-column: the workgroups resident on one XCD (32 CUs) should
     // cover whole output rows, so that each row leaves as one long contiguous run,
     // while still sharing code rows and weight rows in that XCD's L2.
-    const int32_t resident = 32 * (CF::THREADS == 256 ? (CF::OCC >= 4 ? 4 : 2) : 1);
+    constexpr int kWgPerCu = CF::OCC * 4 / CF::NW > 0 ? CF::OCC * 4 / CF::NW : 1;
+    const int32_t resident = 32 * kWgPerCu;
     int32_t super_rows = (resident + tiles_o - 1) / tiles_o;
     super_rows = super_rows < 1 ? 1 : (super_rows > 8 ? 8 : super_rows);
     if (const char *e = getenv("DGQ_SUPER_ROWS")) super_rows = atoi(e) > 0 ? atoi(e) : super_rows;
@@ -520,6 +513,7 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     switch (cfg) {
         DGQ_CASE(1, 4, 2, 2, 2, 6, 2);  // 256 x 128, 8 waves of 64 x 64, one workgroup per CU
         DGQ_CASE(2, 2, 2, 1, 2, 3, 4);  // 64 x 128, 4 waves of 32 x 64, four workgroups per CU
+        DGQ_CASE(3, 2, 2, 2, 2, 3, 3);  // 128 x 128, three workgroups per CU, 3-stage ring
         default:
             DGQ_CASE(0, 2, 2, 2, 2, 4, 2);  // 128 x 128, 4 waves of 64 x 64, two workgroups per CU
     }
