@@ -23,6 +23,19 @@ if ROOT not in sys.path:
 
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
+TRAFFIC_NOTE = os.path.join(ROOT, "profiles", "k_linear_a8_config5_hbm_traffic.md")
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc and
+    recorded in the committed summary (a line `traffic_bytes_per_launch: N`); None if absent."""
+    try:
+        for ln in open(TRAFFIC_NOTE):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
 METRIC = "dgq_linear int8 TOPS (% MFMA peak) + xattn_logq GB/s (% HBM), 1 MI355X"
 
 
@@ -35,6 +48,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-batch", type=int, default=2,
                     help="batch elements of fresh data used for (untimed) calibration")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="run only a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB), "
+                         "three times: the reference that scales the profiler's HBM byte counters")
     return ap.parse_args()
 
 
@@ -70,6 +86,15 @@ def main():
     dgq.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.probe_copy:
+        n = 1 << 28
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(probe="copy", read_bytes=4 * n, write_bytes=4 * n, launches=3)))
+        return
     cfg, desc = workload(args.workload)
 
     def up(a):
@@ -181,7 +206,9 @@ def main():
     dom = kernels["linear_a8"]
     roofline = dict(kernel="k_linear<8,false> (dgq_linear, 8-bit activation codes)",
                     bound="mfma", achieved=dom["achieved"], peak=PEAK_INT8_TOPS, unit="TOP/s",
-                    frac=dom["frac"], traffic=None, avg_launch_us=dom["avg_call_us"],
+                    frac=dom["frac"],
+                    traffic=measured_traffic() if args.workload == "config5" else None,
+                    avg_launch_us=dom["avg_call_us"],
                     launches_per_step=dom["calls_per_step"])
 
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
@@ -191,7 +218,7 @@ def main():
         oracle.build()
         t_ops = 0.0
         t_sec = 0.0
-        frac = 128
+        frac = 24
         for ent in layers:
             if ent["M"] < 4096:
                 continue
@@ -201,14 +228,11 @@ def main():
             seed = di.layer_seed(cfg["seed"], li)
             wnp = di.linear_case(seed, 1, 2, ent["C"], ent["O"])["W"]
             og = oracle.calibrate(xs, 8, ent["G"], 2)
+            owq, osw = oracle.quantize_weight(wnp, 8)  # offline on both sides: not timed
             t1 = time.perf_counter()
             oq = oracle.quantize_act(og, xs)
-            owq, osw = oracle.quantize_weight(wnp, 8)
-            t_w = time.perf_counter()
             oracle.linear(og, oq["q"], oq["cls"], owq, osw, None)
-            t2 = time.perf_counter()
-            # weight quantization is offline on both sides: not counted
-            t_sec += (t2 - t1) - (t_w - t1) + 0.0
+            t_sec += time.perf_counter() - t1
             t_ops += 2.0 * rows * ent["C"] * ent["O"]
         cpu = dict(value=round(t_ops / t_sec / 1e12, 6), unit="TOPS", cores=1, kind="oracle",
                    sample=("first 1/%d of the rows of every large linear layer, A8W8, quantize + "

@@ -98,7 +98,12 @@ __global__ __launch_bounds__(256) void k_quantize_act(
         const int64_t re = r < rows ? r : rows - 1;
         const float4 *x4 = reinterpret_cast<const float4 *>(x + re * C);
 #pragma unroll
-        for (int k = 0; k < NV; ++k) v[k] = x4[cidx[k]];
+        for (int k = 0; k < NV; ++k) {
+            // the activations are read exactly once: non-temporal, keep the caches for the codes
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x4 + cidx[k]));
+            v[k] = make_float4(t.x, t.y, t.z, t.w);
+        }
     };
 
     int64_t it = 0;

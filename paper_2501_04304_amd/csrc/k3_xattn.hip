@@ -16,7 +16,7 @@
 //
 // Matrix-core path (head dim a multiple of 8 up to 96, nk <= 126)
 // ----------------------------------------------------------------
-// A workgroup owns one (prompt, head) pair and a range of queries; its four
+// A workgroup owns one (prompt, head) pair and a range of queries; its eight
 // wavefronts each take 32 queries at a time.  The logits are computed
 // TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_f16: a lane then holds, for
 // ONE query (lane % 32), half of that query's keys in its accumulator registers,
@@ -76,6 +76,9 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// workgroup of the matrix-core kernels: eight wavefronts share one copy of K and V^T in LDS
+constexpr int kXWaves = 8, kXThreads = 64 * kXWaves;
+
 // NKB: 32-key blocks (keys padded to 32*NKB, the last two slots reserved).
 // KS:  16-wide steps over the head dimension (d padded to 16*KS).
 template <int NKB_, int KS_>
@@ -87,6 +90,8 @@ struct XCfg {
     static constexpr int KROW = 16 * KS + 8;    // halves per K row (+16 B against bank conflicts)
     static constexpr int VROW = NKP + 8;        // bf16 per V^T row
     static constexpr int NBIAS = 2 * NKB * 16;  // floats: start values per lane half
+    // register budget: two workgroups per CU (128 registers) for head dims up to 64
+    static constexpr int WAVES_PER_SIMD = KS <= 4 ? 4 : 2;
     static constexpr size_t lds_pass1 = (size_t)NKP * KROW * 2 * 2 + NBIAS * 4;
     static constexpr size_t lds_pass2 = lds_pass1 + (size_t)DP * VROW * 2 * 2;
 };
@@ -126,7 +131,7 @@ __device__ __host__ constexpr int key_of(int blk, int i, int hh) {
 }
 
 template <class CF, int PASS, bool DUMP>
-__global__ __launch_bounds__(256, 2) void k_xattn_mfma(
+__global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
     float q_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(256, 2) void k_xattn_mfma(
     float *biasv = reinterpret_cast<float *>(Kl + NKP * KROW);
     uint16_t *Vh = reinterpret_cast<uint16_t *>(biasv + CF::NBIAS);
     uint16_t *Vl = Vh + DP * VROW;
-    __shared__ float red[4];
+    __shared__ float red[kXWaves];
 
     const int32_t b = blockIdx.z, head = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void k_xattn_mfma(
     // ---- stage K (two fp16 pieces), the start values and, in pass 2, V^T ---------------
     {
         const float *kb = k + ((int64_t)b * nk * H + head) * d;
-        for (int idx = tid; idx < NKP * KS * 4; idx += 256) {
+        for (int idx = tid; idx < NKP * KS * 4; idx += kXThreads) {
             const int j = idx / (KS * 4), t4 = (idx - j * (KS * 4)) * 4;
             float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
             if (j < nk && t4 < d) x = *reinterpret_cast<const float4 *>(kb + (int64_t)j * hs + t4);
@@ -158,14 +163,14 @@ __global__ __launch_bounds__(256, 2) void k_xattn_mfma(
             *reinterpret_cast<u32x2 *>(Kh + j * KROW + t4) = hi;
             *reinterpret_cast<u32x2 *>(Kl + j * KROW + t4) = lo;
         }
-        for (int idx = tid; idx < CF::NBIAS; idx += 256) {
+        for (int idx = tid; idx < CF::NBIAS; idx += kXThreads) {
             const int half = idx / (NKB * 16), r = idx - half * (NKB * 16);
             const int key = key_of(r >> 4, r & 15, half);
             biasv[idx] = key < nk ? (key_bias ? key_bias[key] * kLog2e : 0.0f) : -INFINITY;
         }
         if (PASS == 2) {
             const float *vb = v + ((int64_t)b * nk * H + head) * d;
-            for (int idx = tid; idx < NKP * (DP / 4); idx += 256) {
+            for (int idx = tid; idx < NKP * (DP / 4); idx += kXThreads) {
                 const int j = idx / (DP / 4), t4 = (idx - j * (DP / 4)) * 4;
                 // the last two key slots repeat V_0 for the low pieces of the <start> weight
                 const int js = j >= NKP - 2 ? 0 : j;
@@ -223,7 +228,7 @@ __global__ __launch_bounds__(256, 2) void k_xattn_mfma(
     float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
 
     QRaw cur = load_q(q_begin + 32 * wave);
-    for (int32_t q0 = q_begin + 32 * wave; q0 < q_end; q0 += 128) {
+    for (int32_t q0 = q_begin + 32 * wave; q0 < q_end; q0 += 32 * kXWaves) {
         const int32_t qi = q0 + n;
         const bool valid = qi < N;
         // The K and V^T fragments of a lane do not depend on the query block; an opaque
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(256, 2) void k_xattn_mfma(
             ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
         }
         const float lse_i = cur.lse;
-        cur = load_q(q0 + 128);  // prefetch (address clamped, always in bounds)
+        cur = load_q(q0 + 32 * kXWaves);  // prefetch (address clamped, always in bounds)
 
         // ---- S^T = K Q^T in log2 units --------------------------------------------------------
         v16f sm[NKB];
@@ -392,7 +397,9 @@ __global__ __launch_bounds__(256, 2) void k_xattn_mfma(
         if (lane == 0) red[wave] = amax;
         __syncthreads();
         if (tid == 0) {
-            amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+            amax = red[0];
+#pragma unroll
+            for (int w = 1; w < kXWaves; ++w) amax = fmaxf(amax, red[w]);
             // probabilities are non-negative: their bit patterns order like unsigned ints
             atomicMax(reinterpret_cast<unsigned int *>(scale + b),
                       __float_as_uint(__builtin_amdgcn_exp2f(amax)));
@@ -414,18 +421,19 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)CF::lds_pass2);
     if (e != hipSuccess) return e;
-    // queries per workgroup: 128 per trip of the four waves, more trips once there are
-    // enough workgroups to fill the chip several times over
-    const int64_t blocks128 = (N + 127) / 128;
-    int64_t trips = (int64_t)B * H * blocks128 / 1024;
+    // queries per workgroup: 32 per wave and trip, more trips once there are enough
+    // workgroups to fill the chip several times over
+    constexpr int kPerTrip = 32 * kXWaves;
+    const int64_t blocks = (N + kPerTrip - 1) / kPerTrip;
+    int64_t trips = (int64_t)B * H * blocks / 1024;
     trips = trips < 1 ? 1 : (trips > 8 ? 8 : trips);
-    const int32_t qpw = (int32_t)(128 * trips);
+    const int32_t qpw = (int32_t)(kPerTrip * trips);
     const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B);
     const float q_scale = (float)(1.4426950408889634 / sqrt((double)d));
     hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
-    hipLaunchKernelGGL(k1, grid, dim3(256), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
+    hipLaunchKernelGGL(k1, grid, dim3(kXThreads), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
                        bits, q_scale, qpw, out, scale_out, lse2, codes_dump);
-    hipLaunchKernelGGL(k2, grid, dim3(256), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
+    hipLaunchKernelGGL(k2, grid, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
                        bits, q_scale, qpw, out, scale_out, lse2, codes_dump);
     return hipGetLastError();
 }
