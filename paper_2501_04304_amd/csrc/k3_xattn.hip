@@ -45,6 +45,9 @@
 //
 // Other shapes use the plain fp32 kernel at the bottom of the file: one thread
 // per (query, head), logits in registers, K then V broadcast from LDS.
+#include <cstdlib>
+#include <type_traits>
+
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -115,7 +118,7 @@ __device__ inline HiLo split_h2(float a, float b) {
     // instruction, and the two do not round alike next to a tie, which breaks hi + lo = x.
     asm("" : "+v"(r.hi));
     const v2h hr = __builtin_bit_cast(v2h, r.hi);
-    r.lo = pack_h2(a - (float)hr.x, b - (float)hr.y);
+    r.lo = pack_h2(fmaf((float)hr.x, -1.0f, a), fmaf((float)hr.y, -1.0f, b));
     return r;
 }
 
@@ -123,6 +126,13 @@ __device__ inline uint32_t bf16_rne_bits(float x) {  // upper 16 bits hold the b
     uint32_t u = __float_as_uint(x);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u & 0xFFFF0000u;
+}
+
+// median of three = clamp(x, lo, hi) in one instruction (the compiler emits max + min)
+__device__ inline int32_t clamp_i32(int32_t x, int32_t lo, int32_t hi) {
+    int32_t r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+    return r;
 }
 
 // key held by accumulator register i of key block blk in lane half hh
@@ -134,7 +144,7 @@ template <class CF, int PASS, bool DUMP>
 __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
-    float q_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
+    float qk_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
     float *__restrict__ lse2, uint8_t *__restrict__ codes_dump) {
     constexpr int NKB = CF::NKB, KS = CF::KS, NKP = CF::NKP, DB = CF::DB, DP = CF::DP;
     constexpr int KROW = CF::KROW, VROW = CF::VROW;
@@ -151,6 +161,16 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
     const int n = lane & 31, hh = lane >> 5;
     const int64_t hs = (int64_t)H * d;  // stride between tokens
 
+    float s_b = 0.0f, s_eff = 1.0f, l2s = 0.0f;
+    uint32_t pmask = 0xFFFFFFFFu;
+    if (PASS == 2) {
+        s_b = scale[b];
+        // no probability above zero outside the <start> column: only that column contributes
+        s_eff = s_b > 0.0f ? s_b : 1.0f;
+        pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;
+        l2s = __log2f(s_eff);
+    }
+
     // ---- stage K (two fp16 pieces), the start values and, in pass 2, V^T ---------------
     {
         const float *kb = k + ((int64_t)b * nk * H + head) * d;
@@ -158,7 +178,9 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             const int j = idx / (KS * 4), t4 = (idx - j * (KS * 4)) * 4;
             float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
             if (j < nk && t4 < d) x = *reinterpret_cast<const float4 *>(kb + (int64_t)j * hs + t4);
-            const HiLo p0 = split_h2(x.x, x.y), p1 = split_h2(x.z, x.w);
+            // log2(e) / sqrt(d) is folded into K here, once per workgroup, not into every query
+            const HiLo p0 = split_h2(x.x * qk_scale, x.y * qk_scale);
+            const HiLo p1 = split_h2(x.z * qk_scale, x.w * qk_scale);
             const u32x2 hi = {p0.hi, p1.hi}, lo = {p0.lo, p1.lo};
             *reinterpret_cast<u32x2 *>(Kh + j * KROW + t4) = hi;
             *reinterpret_cast<u32x2 *>(Kl + j * KROW + t4) = lo;
@@ -177,7 +199,8 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
                 float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (js < nk && t4 < d)
                     x = *reinterpret_cast<const float4 *>(vb + (int64_t)js * hs + t4);
-                const float xe[4] = {x.x, x.y, x.z, x.w};
+                // V carries the prompt scale, so the product needs no multiply on the way out
+                const float xe[4] = {x.x * s_eff, x.y * s_eff, x.z * s_eff, x.w * s_eff};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const uint32_t hb = bf16_rne_bits(xe[e]);
@@ -215,16 +238,6 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
         return r;
     };
 
-    float s_b = 0.0f, s_eff = 1.0f, l2s = 0.0f;
-    uint32_t pmask = 0xFFFFFFFFu;
-    if (PASS == 2) {
-        s_b = scale[b];
-        // no probability above zero outside the <start> column: only that column contributes
-        s_eff = s_b > 0.0f ? s_b : 1.0f;
-        pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;
-        l2s = __log2f(s_eff);
-    }
-    const float qmax = (float)((1 << bits) - 1);
     float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
 
     QRaw cur = load_q(q_begin + 32 * wave);
@@ -236,20 +249,22 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
         // the register file next to the accumulators).
         int lds_ofs = 0;
         asm volatile("" : "+v"(lds_ofs));
-        // ---- split the scaled query into fp16 pieces ---------------------------------------
+        // ---- split the query into fp16 pieces ----------------------------------------------
         u32x4 qh[KS], ql[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const float4 a = cur.x[s][0], c = cur.x[s][1];
-            const HiLo p0 = split_h2(a.x * q_scale, a.y * q_scale);
-            const HiLo p1 = split_h2(a.z * q_scale, a.w * q_scale);
-            const HiLo p2 = split_h2(c.x * q_scale, c.y * q_scale);
-            const HiLo p3 = split_h2(c.z * q_scale, c.w * q_scale);
+            const HiLo p0 = split_h2(a.x, a.y);
+            const HiLo p1 = split_h2(a.z, a.w);
+            const HiLo p2 = split_h2(c.x, c.y);
+            const HiLo p3 = split_h2(c.z, c.w);
             qh[s] = u32x4{p0.hi, p1.hi, p2.hi, p3.hi};
             ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
         }
         const float lse_i = cur.lse;
-        cur = load_q(q0 + 32 * kXWaves);  // prefetch (address clamped, always in bounds)
+        // prefetch the wave's next block; past its last block re-read this one (a cache hit)
+        // rather than rows that belong to another workgroup
+        cur = load_q(q0 + 32 * kXWaves < q_end ? q0 + 32 * kXWaves : q0);
 
         // ---- S^T = K Q^T in log2 units --------------------------------------------------------
         v16f sm[NKB];
@@ -308,30 +323,45 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
         }
 
         // ---- pass 2: codes -> bf16 powers of two, packed as the next B operand --------------
-        const float c0 = l2s + lse_i;        // code = rne(c0 - S)
-        const float ufl = lse_i - 150.0f;    // S below this: A rounds to zero in fp32
+        // code = clamp(rne(t)), t = c0 - S.  Adding 1.5 * 2^23 leaves rne(t) in the low
+        // mantissa bits, so rounding, clamping (an integer median) and the bf16 exponent
+        // 127 - code are all integer work.  A probability that rounds to zero in fp32
+        // (t above l2s + 150) takes the top code; with 4-bit codes the clamp already does
+        // that unless the prompt scale is below 2^-135, so the common 4-bit path skips it.
+        const float c0 = l2s + lse_i;
+        const float thr = l2s + 150.0f;
+        constexpr int32_t kMagic = 0x4B400000;  // bit pattern of 12582912.0f
+        const int32_t cq = (1 << bits) - 1;
+        const int32_t ce = cq < 127 ? cq : 127;  // 2^-127 and below leave the product as zero
         uint8_t *cd = nullptr;
         if (DUMP) cd = codes_dump + ((((int64_t)b * H + head) * N + qi) * (int64_t)(nk - 1));
         uint32_t pk[NKB][8];
+        auto make_codes = [&](auto rule_tag) {
+            constexpr bool RULE = decltype(rule_tag)::value;
 #pragma unroll
-        for (int blk = 0; blk < NKB; ++blk)
+            for (int blk = 0; blk < NKB; ++blk)
 #pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                uint32_t e[2];
+                for (int i = 0; i < 16; i += 2) {
+                    int32_t e[2];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const float sv = sm[blk][i + u];
-                    float c = fminf(fmaxf(rintf(c0 - sv), 0.0f), qmax);
-                    c = sv < ufl ? qmax : c;
-                    if (DUMP) {
-                        const int key = key_of(blk, i + u, hh);
-                        if (valid && key >= 1 && key < nk) cd[key - 1] = (uint8_t)c;
+                    for (int u = 0; u < 2; ++u) {
+                        float t = c0 - sm[blk][i + u];
+                        if (RULE) t = t > thr ? 300.0f : t;
+                        const int32_t r = __float_as_int(t + 12582912.0f);
+                        if (DUMP) {
+                            const int key = key_of(blk, i + u, hh);
+                            const int32_t c = clamp_i32(r, kMagic, kMagic + cq) - kMagic;
+                            if (valid && key >= 1 && key < nk) cd[key - 1] = (uint8_t)c;
+                        }
+                        e[u] = (kMagic + 127) - clamp_i32(r, kMagic, kMagic + ce);
                     }
-                    const int ex = (int)(127.0f - c);  // biased exponent of 2^-c; <= 0: flush
-                    e[u] = (uint32_t)max(ex, 0);
+                    pk[blk][i >> 1] = ((uint32_t)(e[0] | (e[1] << 16)) << 7) & pmask;
                 }
-                pk[blk][i >> 1] = ((e[0] << 7) | (e[1] << 23)) & pmask;
-            }
+        };
+        if (thr < (float)cq)
+            make_codes(std::true_type{});
+        else
+            make_codes(std::false_type{});
         {
             // <start> weight a' = A_i0 / s in three bf16 pieces (truncation keeps each exact)
             const float s_start = __shfl(sm[0][0], n, kWave);
@@ -383,10 +413,10 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
                 const int dim = 32 * db + 8 * a + 4 * hh;
                 if (valid && dim < d) {
                     float4 t;
-                    t.x = o[db][4 * a + 0] * s_eff;
-                    t.y = o[db][4 * a + 1] * s_eff;
-                    t.z = o[db][4 * a + 2] * s_eff;
-                    t.w = o[db][4 * a + 3] * s_eff;
+                    t.x = o[db][4 * a + 0];
+                    t.y = o[db][4 * a + 1];
+                    t.z = o[db][4 * a + 2];
+                    t.w = o[db][4 * a + 3];
                     *reinterpret_cast<float4 *>(orow + dim) = t;
                 }
             }
@@ -421,20 +451,27 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)CF::lds_pass2);
     if (e != hipSuccess) return e;
-    // queries per workgroup: 32 per wave and trip, more trips once there are enough
-    // workgroups to fill the chip several times over
+    // Queries per workgroup.  Staging K and V costs as much as a few hundred queries, so
+    // a (prompt, head) pair is cut into as few pieces as still give every workgroup slot
+    // of the chip (two per CU) something to do; DGQ_XATTN_WGS overrides the slot count.
     constexpr int kPerTrip = 32 * kXWaves;
-    const int64_t blocks = (N + kPerTrip - 1) / kPerTrip;
-    int64_t trips = (int64_t)B * H * blocks / 1024;
-    trips = trips < 1 ? 1 : (trips > 8 ? 8 : trips);
-    const int32_t qpw = (int32_t)(kPerTrip * trips);
+    static int target_wgs = 0;
+    if (target_wgs == 0) {
+        const char *e = getenv("DGQ_XATTN_WGS");
+        target_wgs = e && atoi(e) > 0 ? atoi(e) : 512;
+    }
+    int64_t pieces = target_wgs / ((int64_t)B * H);
+    pieces = pieces < 1 ? 1 : pieces;
+    int64_t per_piece = (N + pieces - 1) / pieces;
+    per_piece = (per_piece + kPerTrip - 1) / kPerTrip * kPerTrip;
+    const int32_t qpw = (int32_t)per_piece;
     const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B);
-    const float q_scale = (float)(1.4426950408889634 / sqrt((double)d));
+    const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
     hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
     hipLaunchKernelGGL(k1, grid, dim3(kXThreads), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, q_scale, qpw, out, scale_out, lse2, codes_dump);
+                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump);
     hipLaunchKernelGGL(k2, grid, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, q_scale, qpw, out, scale_out, lse2, codes_dump);
+                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump);
     return hipGetLastError();
 }
 
