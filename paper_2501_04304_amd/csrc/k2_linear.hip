@@ -122,33 +122,6 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int32_t o0 = tile_o * CF::TO;
     const int32_t n_chunks = Kp >> 6;
 
-    // ---- start-up order: (1) issue the small global loads (row classes, group table
-    // entries), (2) issue the first chunks' direct-to-LDS loads, (3) only then consume
-    // the small loads, so their latency overlaps the first chunks'.
-    bool row_in[BR];
-    uint8_t row_c1[BR];
-#pragma unroll
-    for (int a = 0; a < BR; ++a) {
-        const int64_t r = r0 + (wr * BR + a) * 32 + m32;
-        row_in[a] = r < rows;
-        row_c1[a] = row_in[a] ? row_class[r] : (uint8_t)0;
-    }
-    float col_sw[BO], col_zb0[BO], col_zb1[BO];  // per-lane output-channel constants
-#pragma unroll
-    for (int b = 0; b < BO; ++b) {
-        const int32_t o = o0 + (wo * BO + b) * 32 + m32;  // o < O_pad always
-        col_sw[b] = sw[o];
-        col_zb0[b] = zb[o];
-        col_zb1[b] = zb[O_pad + o];
-    }
-    int32_t t_end = 0;
-    float t_s0 = 0.0f, t_s1 = 0.0f;
-    if (tid < NG) {
-        t_end = gchunk[tid + 1];
-        t_s0 = s_tab[tid];
-        t_s1 = s_tab[NG + tid];
-    }
-
     // ---- direct-to-LDS load plan: the operands are stored block-tiled, one block =
     // 1 KiB = one chunk of 16 rows (32 rows of packed 4-bit codes), already in the
     // slot-swizzled order LDS wants.  One instruction copies one block (lane j moves
@@ -177,6 +150,33 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
 #pragma unroll
         for (int j = 0; j < CF::LOADS; ++j) DGQ_LDS_DMA16(src[j] + ((int64_t)ch << 10), base + dst[j]);
     };
+
+    // ---- prologue: fill the ring before anything else is loaded ----------------------------
+#pragma unroll
+    for (int st = 0; st < STAGES - 1; ++st)
+        if (st < n_chunks) issue_chunk(st);
+
+    // ---- small global loads, branch-free (clamped indices) so that none of them is
+    // waited for before the lines that consume it, long after the ring is in flight
+    bool row_in[BR];
+    uint8_t row_c1[BR];
+#pragma unroll
+    for (int a = 0; a < BR; ++a) {
+        const int64_t r = r0 + (wr * BR + a) * 32 + m32;
+        row_in[a] = r < rows;
+        row_c1[a] = row_class[row_in[a] ? r : rows - 1];
+    }
+    float col_sw[BO], col_zb0[BO], col_zb1[BO];  // per-lane output-channel constants
+#pragma unroll
+    for (int b = 0; b < BO; ++b) {
+        const int32_t o = o0 + (wo * BO + b) * 32 + m32;  // o < O_pad always
+        col_sw[b] = sw[o];
+        col_zb0[b] = zb[o];
+        col_zb1[b] = zb[O_pad + o];
+    }
+    const int32_t tg = tid < NG ? tid : NG - 1;
+    const int32_t t_end = gchunk[tg + 1];
+    const float t_s0 = s_tab[tg], t_s1 = s_tab[NG + tg];
 
     // ---- fragment read offsets (per lane, per k-step) ---------------------------------
     int a_off[2], b_off[2];
@@ -246,11 +246,6 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                     acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
         }
     };
-
-    // ---- prologue: fill the ring ---------------------------------------------------------
-#pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st)
-        if (st < n_chunks) issue_chunk(st);
 
     // ---- group tables in LDS (behind the ring): last chunk of each group and the two
     // scale rows.  Reading them with LDS instructions keeps scalar memory loads out of
@@ -471,13 +466,17 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
         attr_done = true;
     }
     if (lds > (size_t)kStageBudget) return hipErrorInvalidValue;  // too many groups for the table
-    // Row tiles per super-column: the workgroups resident on one XCD (32 CUs) should
-    // cover whole output rows, so that each row leaves as one long contiguous run,
-    // while still sharing code rows and weight rows in that XCD's L2.
+    // Row tiles per super-column.  The workgroups resident on one XCD (32 CUs) share code
+    // rows and weight rows in that XCD's 4 MB L2.  Narrow outputs: one band of row tiles
+    // covers all column tiles.  Wide outputs (ff.in: the weights alone exceed L2): a band
+    // 16 row tiles high, so the resident set is about 16 x 8 tiles and every weight tile
+    // that streams through L2 is used by 16 row tiles instead of 2 (measured: the L2-miss
+    // reads of the 16384 x 1280 -> 10240 layer were 1.8 GB against 36 MB of operands).
     constexpr int kWgPerCu = CF::OCC * 4 / CF::NW > 0 ? CF::OCC * 4 / CF::NW : 1;
     const int32_t resident = 32 * kWgPerCu;
     int32_t super_rows = (resident + tiles_o - 1) / tiles_o;
     super_rows = super_rows < 1 ? 1 : (super_rows > 8 ? 8 : super_rows);
+    if (tiles_o >= 32) super_rows = 16;
     if (const char *e = getenv("DGQ_SUPER_ROWS")) super_rows = atoi(e) > 0 ? atoi(e) : super_rows;
     hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
                        w.d_zb, g.d_s, g.d_gchunk, rows, w.O, w.O_pad, w.Kp, g.info.n_groups,
