@@ -501,9 +501,10 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
                   : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
     }
-    // short contractions are bound by the output write and by per-tile start-up: use
-    // small tiles and four resident workgroups per CU so that the phases overlap
-    int cfg = w.Kp <= 1536 ? 2 : 0;
+    // Four waves per SIMD in both shapes: the matrix pipe and the vector ALU only overlap
+    // across waves, never inside one.  Large problems take 128 x 128 tiles (fewer operand
+    // bytes per output), small ones 64 x 128 tiles so that every CU still gets work.
+    int cfg = rows >= 16384 ? 4 : 2;
     if (g_force_cfg >= 0) cfg = g_force_cfg;
 #define DGQ_CASE(ID, ...)                                                                          \
     case ID:                                                                                       \
@@ -513,6 +514,8 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         DGQ_CASE(1, 4, 2, 2, 2, 6, 2);  // 256 x 128, 8 waves of 64 x 64, one workgroup per CU
         DGQ_CASE(2, 2, 2, 1, 2, 3, 4);  // 64 x 128, 4 waves of 32 x 64, four workgroups per CU
         DGQ_CASE(3, 2, 2, 2, 2, 3, 3);  // 128 x 128, three workgroups per CU, 3-stage ring
+        DGQ_CASE(4, 4, 2, 1, 2, 4, 4);  // 128 x 128, 8 waves of 32 x 64, two workgroups per CU
+        DGQ_CASE(5, 4, 2, 1, 2, 3, 4);  // the same with a 3-stage ring (three workgroups per CU)
         default:
             DGQ_CASE(0, 2, 2, 2, 2, 4, 2);  // 128 x 128, 4 waves of 64 x 64, two workgroups per CU
     }
