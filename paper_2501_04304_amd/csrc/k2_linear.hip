@@ -9,8 +9,10 @@
 //
 // Work decomposition
 //   workgroup = WR x WO wavefronts; wavefront = BR x BO blocks of
-//               v_mfma_i32_32x32x32_i8 (default 2 x 2 waves of 2 x 2 blocks:
-//               a 128 x 128 output tile)
+//               v_mfma_i32_32x32x32_i8 (default 4 x 2 waves of 1 x 2 blocks:
+//               a 128 x 128 output tile, 32 x 64 per wave, so that 128
+//               registers suffice and four waves share a SIMD: the matrix
+//               pipe and the vector ALU overlap only across waves)
 //   K loop    = 64-position chunks (the K granule).  Chunks travel from global
 //               memory straight into LDS (global_load_lds_dwordx4, no staging
 //               registers) through a ring of stages, one barrier per chunk,
