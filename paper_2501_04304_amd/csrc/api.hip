@@ -394,10 +394,10 @@ int dgq_quantize_act(const dgq_groups_t *h, const float *x, int64_t rows, int8_t
     if (!aligned16(x) || !aligned16(codes))
         return fail(DGQ_EALIGN, "dgq_quantize_act: tensor not 16-byte aligned");
     const Groups *g = reinterpret_cast<const Groups *>(h);
-    // LDS: four fp32 rows + 16-bit permutation + per-chunk tables
-    if ((size_t)g->info.channels * 16 + (size_t)g->info.k_padded * 2 + (size_t)g->n_chunks * 16 + 16 >
+    // LDS: four fp32 rows + 32-bit offset table + keep masks + per-chunk tables
+    if ((size_t)g->info.channels * 16 + (size_t)g->info.k_padded * 5 + (size_t)g->n_chunks * 16 + 16 >
         160 * 1024)
-        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act: too many channels for the LDS row buffers (about 9000)");
+        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act: too many channels for the LDS row buffers (about 7500)");
     DGQ_HIP(launch_quantize_act(*g, x, rows, codes, row_class, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }

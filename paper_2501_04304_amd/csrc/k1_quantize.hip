@@ -14,8 +14,12 @@
 // channel permutation, and writes one dword into the block-tiled code layout the
 // GEMM loads (64 contiguous bytes per row and chunk; the four waves of a
 // workgroup own four consecutive rows each of a 16-row block, so a 1 KiB block
-// is completed by one workgroup).  The permutation (16-bit) and the per-chunk
-// (z, 1/s) pairs sit in LDS, loaded once per workgroup.
+// is completed by one workgroup).  Loaded once per workgroup into LDS: the
+// permutation as byte offsets into the row slice (padding positions point at
+// channel 0), one keep-mask per output dword that clears the padding positions
+// of the packed word (so padding costs nothing per position), and the per-chunk
+// (z, 1/s) pairs.  Per position that leaves: one address add, the gather, subtract,
+// multiply, round, clamp and the byte pack.
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -50,8 +54,10 @@ __device__ inline float quant1(float x, float z, float inv_s, float qmax) {
     return fminf(fmaxf(rintf(u), 0.0f), qmax);
 }
 
-// LDS: [perm16: Kp u16, padded to 16 B][cz: 2 * n_chunks float2][rows: 4 * C floats]
-__host__ __device__ inline size_t lds_perm_bytes(int32_t Kp) { return ((size_t)Kp * 2 + 15) & ~(size_t)15; }
+// LDS: [off32: Kp u32][keep: one u32 per output dword][cz: 2 * n_chunks float2][rows: 4 * C floats]
+__host__ __device__ inline size_t lds_table_bytes(int32_t Kp, int bits) {
+    return (size_t)Kp * 4 + (size_t)(Kp / (bits == 8 ? 4 : 8)) * 4;  // both multiples of 16 (Kp % 64 == 0)
+}
 
 // NV: float4 registers per lane that hold one row (C <= NV * 256).
 template <int BITS, int NV>
@@ -61,19 +67,29 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
     uint8_t *__restrict__ row_class) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    uint16_t *perm16 = reinterpret_cast<uint16_t *>(lds_raw);
-    float2 *cz = reinterpret_cast<float2 *>(lds_raw + lds_perm_bytes(Kp));
+    constexpr int kPer = BITS == 8 ? 4 : 8;  // positions per output dword
+    uint32_t *off32 = reinterpret_cast<uint32_t *>(lds_raw);
+    uint32_t *keep = off32 + Kp;
+    float2 *cz = reinterpret_cast<float2 *>(lds_raw + lds_table_bytes(Kp, BITS));
     float *rowbuf = reinterpret_cast<float *>(cz + 2 * n_chunks);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     float *xs = rowbuf + (size_t)wave * C;  // this wave's copy of the row
     constexpr float qmax = (float)((1 << BITS) - 1);
-    constexpr int kOff = BITS == 8 ? 128 : 0;
     const int32_t c4n = C >> 2;  // float4 per row
+    const int32_t n_dw = Kp / kPer;
 
-    for (int32_t j = tid; j < Kp; j += 256) {
-        const int32_t c = perm[j];
-        perm16[j] = c >= 0 ? (uint16_t)c : (uint16_t)0xffff;
+    for (int32_t d = tid; d < n_dw; d += 256) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int32_t c = perm[d * kPer + k];
+            off32[d * kPer + k] = c >= 0 ? (uint32_t)c * 4u : 0u;
+            // 8 bit: byte k of the word; 4 bit: byte k % 4, low nibble for k < 4, high otherwise
+            const uint32_t field = BITS == 8 ? 0xffu << (8 * k) : 0xfu << (8 * (k & 3) + 4 * (k >> 2));
+            if (c >= 0) m |= field;
+        }
+        keep[d] = m;
     }
     for (int32_t i = tid; i < 2 * n_chunks; i += 256) cz[i] = make_float2(chunk_z[i], chunk_inv[i]);
     __syncthreads();
@@ -140,18 +156,18 @@ __global__ __launch_bounds__(256) void k_quantize_act(
             // fixed place inside a 64-byte (32-byte) row segment and a chunk index that
             // advances by 4 (8 bit) or 8 (4 bit) per step.  Four steps are processed
             // together so that their LDS round trips overlap.
-            constexpr int kPer = BITS == 8 ? 4 : 8;          // positions per dword
             constexpr int kDwPerChunk = 64 / kPer;            // 16 or 8
             constexpr int kChunkStep = kWave / kDwPerChunk;   // chunks per step: 4 or 8
-            const int32_t n_dw = Kp / kPer;
             const int64_t lane_off =
                 (BITS == 8 ? tiled64_offset(r, lane / kDwPerChunk, n_chunks, (lane >> 2) & 3)
                            : tiled32_offset(r, lane / kDwPerChunk, n_chunks, (lane >> 2) & 1)) +
                 (lane & 3) * 4;
             int8_t *out_lane = codes + lane_off;
+            const char *xsb = reinterpret_cast<const char *>(xs);
             for (int32_t d0 = lane; d0 < n_dw; d0 += 4 * kWave) {
-                uint32_t idx[4][kPer];
+                uint32_t off[4][kPer];
                 float2 zi[4];
+                uint32_t km[4];
                 bool live[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -159,28 +175,26 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                     live[t] = d < n_dw;
                     const int32_t dc = live[t] ? d : n_dw - 1;  // clamp: reads stay in range
                     zi[t] = czp[dc / kDwPerChunk];
-                    const ushort4 c0 = *reinterpret_cast<const ushort4 *>(perm16 + kPer * dc);
-                    idx[t][0] = c0.x; idx[t][1] = c0.y; idx[t][2] = c0.z; idx[t][3] = c0.w;
+                    km[t] = keep[dc];
+                    const uint4 o0 = *reinterpret_cast<const uint4 *>(off32 + kPer * dc);
+                    off[t][0] = o0.x; off[t][1] = o0.y; off[t][2] = o0.z; off[t][3] = o0.w;
                     if (BITS == 4) {
-                        const ushort4 c1 = *reinterpret_cast<const ushort4 *>(perm16 + kPer * dc + 4);
-                        idx[t][4] = c1.x; idx[t][5] = c1.y; idx[t][6] = c1.z; idx[t][7] = c1.w;
+                        const uint4 o1 = *reinterpret_cast<const uint4 *>(off32 + kPer * dc + 4);
+                        off[t][4] = o1.x; off[t][5] = o1.y; off[t][6] = o1.z; off[t][7] = o1.w;
                     }
                 }
                 float xv[4][kPer];
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int k = 0; k < kPer; ++k) {
-                        const uint32_t c = idx[t][k] < (uint32_t)C ? idx[t][k] : 0u;  // padding reads channel 0
-                        xv[t][k] = xs[c];
-                    }
+                    for (int k = 0; k < kPer; ++k)
+                        xv[t][k] = *reinterpret_cast<const float *>(xsb + off[t][k]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     uint32_t lo = 0, hi = 0;
 #pragma unroll
                     for (int k = 0; k < kPer; ++k) {
-                        float qf = quant1(xv[t][k], zi[t].x, zi[t].y, qmax);
-                        if (idx[t][k] == 0xffffu) qf = (float)kOff;  // padding: stored container 0
+                        const float qf = quant1(xv[t][k], zi[t].x, zi[t].y, qmax);
                         // exact small integer -> byte k of the word
                         if (k < 4)
                             lo = __builtin_amdgcn_cvt_pk_u8_f32(qf, k, lo);
@@ -188,8 +202,9 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                             hi = __builtin_amdgcn_cvt_pk_u8_f32(qf, k - 4, hi);
                     }
                     // 8 bit: stored code = q - 128 = q ^ 0x80 per byte.  4 bit: byte i holds
-                    // position i (low nibble) and position i + 4 (high nibble).
-                    const uint32_t word = BITS == 8 ? (lo ^ 0x80808080u) : (lo | (hi << 4));
+                    // position i (low nibble) and position i + 4 (high nibble).  Padding
+                    // positions are cleared to the stored value 0.
+                    const uint32_t word = (BITS == 8 ? (lo ^ 0x80808080u) : (lo | (hi << 4))) & km[t];
                     if (live[t])
                         *reinterpret_cast<uint32_t *>(out_lane + ((int64_t)(d0 - lane) / kWave + t) *
                                                                      (kChunkStep * 1024)) = word;
@@ -287,7 +302,7 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     int64_t blocks;
     if (vec4) {
         kern = g.info.act_bits == 8 ? pick_vec<8>(C) : pick_vec<4>(C);
-        lds = lds_perm_bytes(Kp) + sizeof(float) * 4 * (size_t)g.n_chunks +
+        lds = lds_table_bytes(Kp, g.info.act_bits) + sizeof(float) * 4 * (size_t)g.n_chunks +
               sizeof(float) * (size_t)C * kWavesPerBlock;
         blocks = (rows + 15) / 16;
         // resident workgroups per CU by LDS; every workgroup walks several 16-row blocks
