@@ -128,17 +128,20 @@ def test_config2_layers(dgq, oracle, li, mode):
     _run_layer(dgq, oracle, run, cal, mode[0], mode[1], G, sample_rows=rows)
 
 
-@pytest.mark.parametrize("shape", [(16, 4096, 640, 640), (16, 1024, 1280, 10240)])
-def test_config5_sampled(dgq, oracle, shape):
-    """SDXL-scale layers in the launch configuration bench.py times."""
+@pytest.mark.parametrize("mode", [(8, 8), (4, 8)])
+@pytest.mark.parametrize("shape", [(16, 4096, 640, 640), (16, 4096, 640, 5120),
+                                   (16, 1024, 1280, 10240), (16, 1024, 5120, 1280)])
+def test_config5_sampled(dgq, oracle, shape, mode):
+    """SDXL-scale layers (q/k/v/out, both ff.in shapes, the long-K ff.out) in the launch
+    configuration bench.py times, both activation code widths."""
     B, N, C, O = shape
-    run = di.linear_case(5000 + C, B, N, C, O)
-    cal = di.linear_case(5000 + C, B, N, C, O, calib=True)
+    run = di.linear_case(5000 + C + O, B, N, C, O)
+    cal = di.linear_case(5000 + C + O, B, N, C, O, calib=True)
     M = B * N
     rng = np.random.default_rng(1)
     rows = np.unique(np.concatenate([rng.choice(M, 24, replace=False), run["rows_ot"][:4],
                                      [0, M - 1]]))
-    _run_layer(dgq, oracle, run, cal, 8, 8, 128, sample_rows=rows)
+    _run_layer(dgq, oracle, run, cal, mode[0], mode[1], 128, sample_rows=rows)
 
 
 def test_text_context_rows(dgq, oracle):
