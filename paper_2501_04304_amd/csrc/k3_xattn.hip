@@ -91,7 +91,8 @@ struct XCfg {
     static constexpr int DB = (KS + 1) / 2;     // 32-wide blocks of output dims
     static constexpr int DP = 32 * DB;
     static constexpr int KROW = 16 * KS + 8;    // halves per K row (+16 B against bank conflicts)
-    static constexpr int VROW = NKP + 8;        // bf16 per V^T row
+    static constexpr int VROW = NKP + 12;       // bf16 per V^T row: an odd multiple of 2 dwords, so the
+                                                // 8-byte fragment reads of 32 rows hit 64 distinct banks
     static constexpr int NBIAS = 2 * NKB * 16;  // floats: start values per lane half
     // register budget: two workgroups per CU (128 registers) for head dims up to 64
     static constexpr int WAVES_PER_SIMD = KS <= 4 ? 4 : 2;
