@@ -149,23 +149,45 @@ def main():
                 calls.append(("xattn_b%d" % bits, (a, bits), abytes))
     plan()
 
-    def run_call(kind, key):
+    # Arguments are marshalled once (pointers, sizes, stream); inside the step each call is
+    # one ctypes call into the C ABI, so that the host keeps ahead of the 10-20 us kernels.
+    import ctypes as C
+    L = dgq.lib()
+    sp = C.c_void_p(stream.cuda_stream)
+
+    def ptr(t):
+        return C.c_void_p(t.data_ptr())
+
+    def prepared(kind, key):
         if kind.startswith("quantize"):
             ent, m = key
-            dgq.dgq_quantize_act(m["g"], ent["x"], codes=m["codes"], row_class=m["cls"])
-        elif kind.startswith("linear"):
+            a = (C.c_void_p(m["g"].handle), ptr(ent["x"]), C.c_int64(ent["M"]), ptr(m["codes"]),
+                 ptr(m["cls"]), sp)
+            return L.dgq_quantize_act, a
+        if kind.startswith("linear"):
             ent, m = key
-            dgq.dgq_linear(m["g"], m["wt"], m["codes"], m["cls"], y=ent["y"])
-        else:
-            a, bits = key
-            dgq.dgq_xattn_logq(a["q"], a["k"], a["v"], a["kb"], bits, out=a["out"], scale_out=a["s"],
-                               workspace=a["ws"])
+            a = (C.c_void_p(m["g"].handle), C.c_void_p(m["wt"].handle), ptr(m["codes"]),
+                 ptr(m["cls"]), C.c_int64(ent["M"]), ptr(ent["y"]), None, None, C.c_size_t(0), sp)
+            return L.dgq_linear, a
+        a_, bits = key
+        a = (ptr(a_["q"]), ptr(a_["k"]), ptr(a_["v"]), ptr(a_["kb"]), a_["B"], a_["N"], a_["H"],
+             a_["d"], a_["nk"], bits, ptr(a_["out"]), ptr(a_["s"]), None, ptr(a_["ws"]),
+             C.c_size_t(a_["ws"].numel()), sp)
+        return L.dgq_xattn_logq, a
+
+    prep = [prepared(kind, key) for (kind, key, _) in calls]
+
+    def run_call(ci):
+        fn, a = prep[ci]
+        rc = fn(*a)
+        if rc != 0:
+            raise dgq.DgqError(rc, L.dgq_last_error().decode())
 
     def step(events=None):
         for ci, (kind, key, _) in enumerate(calls):
             if events is not None:
                 events[ci][0].record(stream)
-            run_call(kind, key)
+            run_call(ci)
             if events is not None:
                 events[ci][1].record(stream)
 

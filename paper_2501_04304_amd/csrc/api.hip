@@ -8,6 +8,10 @@
 #include <new>
 #include <numeric>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "dgq_internal.h"
 
 namespace dgq {
@@ -15,6 +19,20 @@ namespace dgq {
 static thread_local std::string g_last_error;
 
 void set_error(const std::string &msg) { g_last_error = msg; }
+
+hipError_t ensure_dynamic_lds(const void *kernel, int bytes) {
+    static std::mutex mu;
+    static std::map<std::pair<const void *, int>, int> done;  // (kernel, device) -> bytes set
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    int &cur = done[std::make_pair(kernel, dev)];
+    if (cur >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) cur = bytes;
+    return e;
+}
 
 int hip_fail(hipError_t e, const char *what) {
     set_error(std::string(what) + ": " + hipGetErrorString(e));

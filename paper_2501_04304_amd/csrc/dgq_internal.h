@@ -70,6 +70,10 @@ int hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::dgq::hip_fail(e_, #call); \
     } while (0)
 
+// Raise a kernel's dynamic-LDS limit to `bytes` (the first time only, per kernel and
+// device: the attribute call is a host round trip that hot calls should not repeat).
+hipError_t ensure_dynamic_lds(const void *kernel, int bytes);
+
 // ---- kernel launchers (each returns a hipError_t from the launch) ----------
 
 // Per-row max and min of x [rows, C].

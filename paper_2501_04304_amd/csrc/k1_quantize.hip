@@ -318,8 +318,7 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     }
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), 160 * 1024);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, st, x, rows, C, Kp,

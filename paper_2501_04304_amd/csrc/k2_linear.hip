@@ -459,13 +459,9 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     const dim3 grid((unsigned)(per_xcd * 8));
     size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES + 12 * (size_t)g.info.n_groups;
     auto kern = k_linear<CF, DUMP>;
-    static bool attr_done = false;  // per instantiation
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kStageBudget);
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kStageBudget);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     if (lds > (size_t)kStageBudget) return hipErrorInvalidValue;  // too many groups for the table
     // Row tiles per super-column.  The workgroups resident on one XCD (32 CUs) share code

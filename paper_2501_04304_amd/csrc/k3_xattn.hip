@@ -445,12 +445,9 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
                        hipStream_t st) {
     auto k1 = k_xattn_mfma<CF, 1, false>;
     auto k2 = codes_dump ? k_xattn_mfma<CF, 2, true> : k_xattn_mfma<CF, 2, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k1),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)CF::lds_pass1);
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k1), (int)CF::lds_pass1);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)CF::lds_pass2);
+    e = ensure_dynamic_lds(reinterpret_cast<const void *>(k2), (int)CF::lds_pass2);
     if (e != hipSuccess) return e;
     // Queries per workgroup.  Staging K and V costs as much as a few hundred queries, so
     // a (prompt, head) pair is cut into as few pieces as still give every workgroup slot
@@ -629,11 +626,9 @@ hipError_t launch_passes(const float *q, const float *k, const float *v, const f
     auto k1 = k_xattn<NKP, 1>;
     auto k2 = k_xattn<NKP, 2>;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k1),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k1), (int)lds);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k2),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(k2), (int)lds);
         if (e != hipSuccess) return e;
     }
     // scale_out accumulates a maximum: clear it with a fill kernel (capturable in a graph)
