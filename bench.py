@@ -223,6 +223,20 @@ def main():
                              frac=round(ach / peak, 4),
                              avg_call_us=round(a["ms"] * 1e3 / a["launches"], 2),
                              calls_per_step=a["launches"] // args.steps)
+    # per-layer view of the 8-bit contraction: % of the MFMA peak and % of the layer's own
+    # roofline min(MFMA peak, algorithmic HBM bytes at the HBM peak)
+    per_layer = []
+    for ci, (kind, key, units) in enumerate(calls):
+        if kind != "linear_a8":
+            continue
+        ent, m = key
+        us = sum(ev[k][ci][0].elapsed_time(ev[k][ci][1]) for k in range(args.steps)) * 1e3 / args.steps
+        byt = ent["M"] * m["Kp"] + ent["O"] * m["Kp"] + 4.0 * ent["M"] * ent["O"] + ent["M"]
+        t_roof = max(units / (PEAK_INT8_TOPS * 1e12), byt / (PEAK_HBM_GBS * 1e9))
+        per_layer.append(dict(layer=ent["name"], M=ent["M"], C=ent["C"], O=ent["O"], us=round(us, 2),
+                              tops=round(units / us / 1e6, 1),
+                              frac_mfma=round(units / us / 1e6 / PEAK_INT8_TOPS, 4),
+                              frac_roofline=round(t_roof * 1e6 / us, 4)))
     total_ops = sum(u for (kind, _, u) in calls if kind.startswith("linear"))
     value = total_ops / (ms_per_step * 1e-3) / 1e12
     dom = kernels["linear_a8"]
@@ -265,7 +279,7 @@ def main():
                 scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
-                roofline=roofline, kernels=kernels, cpu_baseline=cpu)
+                roofline=roofline, kernels=kernels, linear_a8_layers=per_layer, cpu_baseline=cpu)
     print(json.dumps(line))
 
 

@@ -499,23 +499,25 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
                   : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
     }
-    // Four waves per SIMD in both shapes: the matrix pipe and the vector ALU only overlap
+    // Four waves per SIMD in every shape: the matrix pipe and the vector ALU only overlap
     // across waves, never inside one.  Large problems take 128 x 128 tiles (fewer operand
-    // bytes per output), small ones 64 x 128 tiles so that every CU still gets work.
-    int cfg = rows >= 16384 ? 4 : 2;
+    // bytes per output), medium ones 64 x 128 tiles so that every CU still gets work, and
+    // problems with fewer tiles than CUs (the projections of the 77-token prompt) 64 x 64
+    // tiles behind an 8-deep ring: there a workgroup is alone on its CU and only the
+    // depth of the ring hides the latency of the chunks.
+    const int64_t t128 = ((rows + 127) / 128) * ((w.O + 127) / 128);
+    const int64_t t64x128 = ((rows + 63) / 64) * ((w.O + 127) / 128);
+    int cfg = t128 >= 512 ? 4 : (t64x128 >= 256 ? 2 : 6);
     if (g_force_cfg >= 0) cfg = g_force_cfg;
 #define DGQ_CASE(ID, ...)                                                                          \
     case ID:                                                                                       \
         return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st) \
                   : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
     switch (cfg) {
-        DGQ_CASE(1, 4, 2, 2, 2, 6, 2);  // 256 x 128, 8 waves of 64 x 64, one workgroup per CU
         DGQ_CASE(2, 2, 2, 1, 2, 3, 4);  // 64 x 128, 4 waves of 32 x 64, four workgroups per CU
-        DGQ_CASE(3, 2, 2, 2, 2, 3, 3);  // 128 x 128, three workgroups per CU, 3-stage ring
-        DGQ_CASE(4, 4, 2, 1, 2, 4, 4);  // 128 x 128, 8 waves of 32 x 64, two workgroups per CU
-        DGQ_CASE(5, 4, 2, 1, 2, 3, 4);  // the same with a 3-stage ring (three workgroups per CU)
+        DGQ_CASE(6, 2, 1, 1, 2, 8, 4);  // 64 x 64, 2 waves of 32 x 64, 8-stage ring
         default:
-            DGQ_CASE(0, 2, 2, 2, 2, 4, 2);  // 128 x 128, 4 waves of 64 x 64, two workgroups per CU
+            DGQ_CASE(4, 4, 2, 1, 2, 4, 4);  // 128 x 128, 8 waves of 32 x 64, two workgroups per CU
     }
 #undef DGQ_CASE
 }

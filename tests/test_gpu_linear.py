@@ -101,6 +101,26 @@ def test_small_layers(dgq, oracle, B, N, C, O, G, ab, wb, P):
     _run_layer(dgq, oracle, run, cal, ab, wb, G, P, bias=bias)
 
 
+@pytest.mark.parametrize("ab", [8, 4])
+@pytest.mark.parametrize("B,N,C,O,G", [
+    (2, 1111, 200, 1000, 64),   # 35 x 8 tiles of 64 x 128: the medium tile shape, ragged
+    (2, 2500, 136, 1700, 64),   # 40 x 14 tiles of 128 x 128: the large tile shape, ragged
+])
+def test_ragged_medium_and_large_tiles(dgq, oracle, B, N, C, O, G, ab):
+    """Row, channel and output counts that are no multiple of anything, at sizes where
+    the launcher picks the 64 x 128 and the 128 x 128 tile (the small cases above all
+    take the 64 x 64 one); oracle on sampled rows that include both ends of the edge tiles."""
+    seed = 300 + C + O
+    run = di.linear_case(seed, B, N, C, O)
+    cal = di.linear_case(seed, B, N, C, O, calib=True)
+    M = B * N
+    rng = np.random.default_rng(seed)
+    edge = [0, 63, 64, 127, 128, M - 130, M - 65, M - 64, M - 2, M - 1]
+    rows = np.unique(np.concatenate([rng.choice(M, 30, replace=False), run["rows_ot"][:6], edge]))
+    bias = rng.standard_normal(O).astype(np.float32)
+    _run_layer(dgq, oracle, run, cal, ab, 8, G, 2, bias=bias, sample_rows=rows)
+
+
 def test_config1_full(dgq, oracle):
     """16x16 latent, 512 x 1280 -> 1280, G = 128, A8W8, seed 0; calibrated both
     on fresh data (clipping occurs) and on the tensor itself."""
