@@ -11,8 +11,9 @@
 //   workgroup = WR x WO wavefronts; wavefront = BR x BO blocks of
 //               v_mfma_i32_32x32x32_i8 (default 4 x 2 waves of 1 x 2 blocks:
 //               a 128 x 128 output tile, 32 x 64 per wave, so that 128
-//               registers suffice and four waves share a SIMD: the matrix
-//               pipe and the vector ALU overlap only across waves)
+//               registers suffice and four waves share a SIMD: a wave's
+//               fold follows its MFMAs, so the matrix pipe and the vector
+//               ALU are kept busy together by waves in different phases)
 //   K loop    = 64-position chunks (the K granule).  Chunks travel from global
 //               memory straight into LDS (global_load_lds_dwordx4, no staging
 //               registers) through a ring of stages, one barrier per chunk,
@@ -499,9 +500,9 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
                   : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
     }
-    // Four waves per SIMD in every shape: the matrix pipe and the vector ALU only overlap
-    // across waves, never inside one.  Large problems take 128 x 128 tiles (fewer operand
-    // bytes per output), medium ones 64 x 128 tiles so that every CU still gets work, and
+    // Four waves per SIMD in every shape: a wave's fold waits for its own MFMAs, so it is
+    // the other waves that keep the matrix pipe busy meanwhile.  Large problems take
+    // 128 x 128 tiles (fewer operand bytes per output), medium ones 64 x 128 tiles so that every CU still gets work, and
     // problems with fewer tiles than CUs (the projections of the 77-token prompt) 64 x 64
     // tiles behind an 8-deep ring: there a workgroup is alone on its CU and only the
     // depth of the ring hides the latency of the chunks.
