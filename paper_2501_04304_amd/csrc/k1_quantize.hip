@@ -28,7 +28,6 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;
-constexpr int kRowsPerWave = 4;  // consecutive rows of a 16-row block per wave
 
 __device__ inline float wave_max(float v) {
 #pragma unroll
@@ -65,7 +64,7 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
     const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
-    uint8_t *__restrict__ row_class) {
+    uint8_t *__restrict__ row_class, int32_t rpw_log2) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     constexpr int kPer = BITS == 8 ? 4 : 8;  // positions per output dword
     uint32_t *off32 = reinterpret_cast<uint32_t *>(lds_raw);
@@ -94,11 +93,15 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     for (int32_t i = tid; i < 2 * n_chunks; i += 256) cz[i] = make_float2(chunk_z[i], chunk_inv[i]);
     __syncthreads();
 
-    // rows: block b of 16 rows -> workgroup, wave w takes rows 16b + 4w .. 16b + 4w + 3
-    const int64_t n_blocks = (rows + 15) >> 4;
+    // rows: a workgroup takes units of 4 << rpw_log2 consecutive rows, wave w the rows
+    // (w << rpw_log2) .. of the unit, one after the other.  rpw_log2 = 2: a unit is one
+    // 16-row block of the tiled code layout; rpw_log2 = 0 (few rows): a quarter of one,
+    // so that four times as many workgroups share the work.
+    const int32_t us = 2 + rpw_log2;
+    const int64_t n_units = (rows + (1 << us) - 1) >> us;
     auto row_of = [&](int64_t it) -> int64_t {  // it-th row of this wave's sequence
-        const int64_t blk = (int64_t)blockIdx.x + (it / kRowsPerWave) * gridDim.x;
-        return blk < n_blocks ? (blk << 4) + wave * kRowsPerWave + (it % kRowsPerWave) : rows;
+        const int64_t u = (int64_t)blockIdx.x + (it >> rpw_log2) * gridDim.x;
+        return u < n_units ? (u << us) + (wave << rpw_log2) + (it & ((1 << rpw_log2) - 1)) : rows;
     };
     // Branch-free loads: a lane index past the end of the row (and a row index past the
     // end of the tensor) is clamped to the last valid one, which re-reads a value that is
@@ -126,10 +129,10 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     int64_t r = row_of(0);
     fetch(r);
     while (true) {
-        // the sequence ends at the first block index past the end; rows inside the last
-        // block but past `rows` are skipped
-        const int64_t blk = (int64_t)blockIdx.x + (it / kRowsPerWave) * gridDim.x;
-        if (blk >= n_blocks) break;
+        // the sequence ends at the first unit index past the end; rows inside the last
+        // unit but past `rows` are skipped
+        const int64_t u = (int64_t)blockIdx.x + (it >> rpw_log2) * gridDim.x;
+        if (u >= n_units) break;
         const int64_t r_next = row_of(it + 1);
         if (r < rows) {
             float mx = -INFINITY, mn = INFINITY;
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
     const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
     const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
-    uint8_t *__restrict__ row_class) {
+    uint8_t *__restrict__ row_class, int32_t /*rpw_log2: unused, one row per wave*/) {
     extern __shared__ float lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     float *xs = lds + (size_t)wave * C;
@@ -276,7 +279,7 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
 }
 
 using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const int32_t *,
-                      const float *, const float *, float, int8_t *, uint8_t *);
+                      const float *, const float *, float, int8_t *, uint8_t *, int32_t);
 
 // NV = float4 loads per lane per row; exact for the usual channel counts (320 .. 5120).
 template <int BITS>
@@ -300,12 +303,17 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     Kern kern;
     size_t lds;
     int64_t blocks;
+    int32_t rpw_log2 = 2;
     if (vec4) {
         kern = g.info.act_bits == 8 ? pick_vec<8>(C) : pick_vec<4>(C);
         lds = lds_table_bytes(Kp, g.info.act_bits) + sizeof(float) * 4 * (size_t)g.n_chunks +
               sizeof(float) * (size_t)C * kWavesPerBlock;
         blocks = (rows + 15) / 16;
-        // resident workgroups per CU by LDS; every workgroup walks several 16-row blocks
+        if (blocks < 256) {  // fewer 16-row blocks than CUs: quarter blocks, one row per wave
+            rpw_log2 = 0;
+            blocks = (rows + 3) / 4;
+        }
+        // resident workgroups per CU by LDS; every workgroup walks several units
         int per_cu = (int)((160 * 1024) / lds);
         per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
         const int64_t cap = 256 * (int64_t)per_cu;
@@ -323,7 +331,7 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, st, x, rows, C, Kp,
                        g.n_chunks, g.d_perm, g.d_chunk_z, g.d_chunk_inv, g.info.tau_pix, codes,
-                       row_class);
+                       row_class, rpw_log2);
     return hipGetLastError();
 }
 
