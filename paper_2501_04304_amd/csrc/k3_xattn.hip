@@ -223,16 +223,19 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
         float4 x[KS][2];
         float lse;
     };
+    // Only the last 16-dimension step can reach past the head dimension (d > 16 (KS - 1),
+    // d % 8 == 0): its slice is clamped (K is zero in LDS there, any finite value will
+    // do); the others sit at fixed distances from one per-lane pointer.
+    const int32_t t_last = min(16 * (KS - 1) + 8 * hh, d - 8) - 8 * hh;
     auto load_q = [&](int32_t q0) {
         QRaw r;
         const int32_t qi = min(q0 + n, N - 1);
-        const float *p = qbase + (int64_t)qi * hs;
+        const float *p = qbase + (int64_t)qi * hs + 8 * hh;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            // past the head dimension K is zero in LDS: any finite value will do there
-            const int32_t t = min(16 * s + 8 * hh, d - 8);
-            r.x[s][0] = *reinterpret_cast<const float4 *>(p + t);
-            r.x[s][1] = *reinterpret_cast<const float4 *>(p + t + 4);
+            const float *ps = s < KS - 1 ? p + 16 * s : p + t_last;
+            r.x[s][0] = *reinterpret_cast<const float4 *>(ps);
+            r.x[s][1] = *reinterpret_cast<const float4 *>(ps + 4);
         }
         r.lse = 0.0f;
         if (PASS == 2) r.lse = lse2[((int64_t)b * H + head) * N + qi];
@@ -263,9 +266,6 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
         }
         const float lse_i = cur.lse;
-        // prefetch the wave's next block; past its last block re-read this one (a cache hit)
-        // rather than rows that belong to another workgroup
-        cur = load_q(q0 + 32 * kXWaves < q_end ? q0 + 32 * kXWaves : q0);
 
         // ---- S^T = K Q^T in log2 units --------------------------------------------------------
         v16f sm[NKB];
@@ -281,19 +281,40 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
                 sm[blk][4 * a + 3] = t.w;
             }
         }
+        {
+            // K fragments are read one (step, key block) ahead of the MFMAs that use them:
+            // left alone the compiler reads each fragment right in front of its MFMAs, and
+            // a wave then spends an LDS round trip per fragment doing nothing.
+            auto k_frag = [&](int t, u32x4 &fh, u32x4 &fl) {
+                const int off = (32 * (t % NKB) + n) * KROW + 16 * (t / NKB) + 8 * hh + lds_ofs;
+                fh = *reinterpret_cast<const u32x4 *>(Kh + off);
+                fl = *reinterpret_cast<const u32x4 *>(Kl + off);
+            };
+            u32x4 fh[2], fl[2];
+            k_frag(0, fh[0], fl[0]);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const v8h bqh = __builtin_bit_cast(v8h, qh[s]);
-            const v8h bql = __builtin_bit_cast(v8h, ql[s]);
-#pragma unroll
-            for (int blk = 0; blk < NKB; ++blk) {
-                const int off = (32 * blk + n) * KROW + 16 * s + 8 * hh + lds_ofs;
-                const v8h akh = __builtin_bit_cast(v8h, *reinterpret_cast<const u32x4 *>(Kh + off));
-                const v8h akl = __builtin_bit_cast(v8h, *reinterpret_cast<const u32x4 *>(Kl + off));
+            for (int t = 0; t < KS * NKB; ++t) {
+                const int s = t / NKB, blk = t % NKB;
+                if (t + 1 < KS * NKB) k_frag(t + 1, fh[(t + 1) & 1], fl[(t + 1) & 1]);
+                asm volatile("" : "+v"(fh[t & 1]), "+v"(fl[t & 1]));  // wait for this pair only
+                const v8h bqh = __builtin_bit_cast(v8h, qh[s]);
+                const v8h bql = __builtin_bit_cast(v8h, ql[s]);
+                const v8h akh = __builtin_bit_cast(v8h, fh[t & 1]);
+                const v8h akl = __builtin_bit_cast(v8h, fl[t & 1]);
                 sm[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bqh, sm[blk], 0, 0, 0);
                 sm[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bql, sm[blk], 0, 0, 0);
                 sm[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(akl, bqh, sm[blk], 0, 0, 0);
             }
+        }
+        // Prefetch the wave's next block (past its last block re-read this one, a cache hit,
+        // rather than rows that belong to another workgroup).  Issued here, not before the
+        // product above: the split query is dead now and the raw one takes its registers;
+        // issued earlier the two overlap, registers spill, and every reload of a spilled
+        // value waits for ALL outstanding vector memory, i.e. for this very prefetch.
+        {
+            int32_t qn = q0 + 32 * kXWaves < q_end ? q0 + 32 * kXWaves : q0;
+            asm volatile("" : "+v"(qn) : "v"(sm[NKB - 1][15]));  // not before the last MFMA
+            cur = load_q(qn);
         }
 
         if (PASS == 1) {
@@ -376,51 +397,54 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             if (hh == 1) pk[NKB - 1][7] = (a2 >> 16) | a3;  // key slots NKP-2 and NKP-1
         }
 
-        // ---- Out^T = V^T P^T -----------------------------------------------------------------
-        v16f o[DB];
+        // ---- Out^T = V^T P^T, one block of 32 output dimensions after the other (both at once
+        // would hold 32 more accumulator registers than the file has left) ----------------
+        float *orow = out + ((int64_t)b * N * H + head) * d + (int64_t)qi * hs;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db) {
+            v16f o;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
-#pragma unroll
-        for (int s16 = 0; s16 < 2 * NKB; ++s16) {
-            u32x4 pb;
-            pb.x = pk[s16 >> 1][4 * (s16 & 1) + 0];
-            pb.y = pk[s16 >> 1][4 * (s16 & 1) + 1];
-            pb.z = pk[s16 >> 1][4 * (s16 & 1) + 2];
-            pb.w = pk[s16 >> 1][4 * (s16 & 1) + 3];
-            const v8bf bp = __builtin_bit_cast(v8bf, pb);
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
+            for (int i = 0; i < 16; ++i) o[i] = 0.0f;
+            // V^T fragments, too, are read one 16-key step ahead
+            auto v_frag = [&](int s16, u32x4 &ah, u32x4 &al) {
                 // slots 0..3: keys 16 s16 + 4 hh + (0..3); slots 4..7: the same + 8
                 const int off = (32 * db + n) * VROW + 16 * s16 + 4 * hh + lds_ofs;
                 const u32x2 h0 = *reinterpret_cast<const u32x2 *>(Vh + off);
                 const u32x2 h1 = *reinterpret_cast<const u32x2 *>(Vh + off + 8);
                 const u32x2 l0 = *reinterpret_cast<const u32x2 *>(Vl + off);
                 const u32x2 l1 = *reinterpret_cast<const u32x2 *>(Vl + off + 8);
-                const u32x4 ah = {h0.x, h0.y, h1.x, h1.y};
-                const u32x4 al = {l0.x, l0.y, l1.x, l1.y};
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, ah), bp,
-                                                                 o[db], 0, 0, 0);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, al), bp,
-                                                                 o[db], 0, 0, 0);
-            }
-        }
-        float *orow = out + ((int64_t)b * N * H + head) * d + (int64_t)qi * hs;
+                ah = u32x4{h0.x, h0.y, h1.x, h1.y};
+                al = u32x4{l0.x, l0.y, l1.x, l1.y};
+            };
+            u32x4 vh[2], vl[2];
+            v_frag(0, vh[0], vl[0]);
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int s16 = 0; s16 < 2 * NKB; ++s16) {
+                if (s16 + 1 < 2 * NKB) v_frag(s16 + 1, vh[(s16 + 1) & 1], vl[(s16 + 1) & 1]);
+                asm volatile("" : "+v"(vh[s16 & 1]), "+v"(vl[s16 & 1]));  // wait for this pair only
+                u32x4 pb;
+                pb.x = pk[s16 >> 1][4 * (s16 & 1) + 0];
+                pb.y = pk[s16 >> 1][4 * (s16 & 1) + 1];
+                pb.z = pk[s16 >> 1][4 * (s16 & 1) + 2];
+                pb.w = pk[s16 >> 1][4 * (s16 & 1) + 3];
+                const v8bf bp = __builtin_bit_cast(v8bf, pb);
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vh[s16 & 1]), bp, o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vl[s16 & 1]), bp, o, 0, 0, 0);
+            }
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
                 const int dim = 32 * db + 8 * a + 4 * hh;
                 if (valid && dim < d) {
                     float4 t;
-                    t.x = o[db][4 * a + 0];
-                    t.y = o[db][4 * a + 1];
-                    t.z = o[db][4 * a + 2];
-                    t.w = o[db][4 * a + 3];
+                    t.x = o[4 * a + 0];
+                    t.y = o[4 * a + 1];
+                    t.z = o[4 * a + 2];
+                    t.w = o[4 * a + 3];
                     *reinterpret_cast<float4 *>(orow + dim) = t;
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     if (PASS == 1) {
