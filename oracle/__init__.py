@@ -159,6 +159,16 @@ def linear(g: Groups, q, cls, wq, sw, bias=None, want_acc: bool = False):
     return y, acc
 
 
+def geglu(y):
+    """y [rows, O] fp32 -> [rows, O/2]: first half times GELU(second half), in double."""
+    y = _f32(y)
+    rows, O = y.shape
+    assert O % 2 == 0
+    out = np.zeros((rows, O // 2), dtype=np.float32)
+    lib().dgqo_geglu(_p(y), C.c_int64(rows), C.c_int32(O), _p(out))
+    return out
+
+
 def attn_probs(Q, K, key_bias=None):
     """Q [B,N,H,d], K [B,nk,H,d] -> A [B,H,N,nk] fp32."""
     Q = _f32(Q)

@@ -531,3 +531,30 @@ void dgqo_xattn_logq(const float *A, const float *V, int32_t B, int32_t N,
     }
     free(acc);
 }
+
+/* ------------------------------------------------------------------------- */
+/* Gated feed-forward activation (for the fused epilogue of the contraction)  */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * The transformer feed-forward of the models the paper quantizes (Section 4.1:
+ * Stable Diffusion v1.4, SDXL-Turbo) gates its first projection: with
+ * y = [a | b] (first and second half of the O output channels),
+ *     out = a * GELU(b),   GELU(t) = t * Phi(t),
+ * Phi the standard normal distribution function.  This is the models'
+ * definition, not a formula of the paper; it is here because the contraction
+ * kernel can apply it before the result ever reaches memory.  Evaluated in
+ * double on the fp32 result of dgqo_linear, rounded once.
+ */
+void dgqo_geglu(const float *y, int64_t rows, int32_t O, float *out)
+{
+    const int32_t oh = O / 2;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int32_t c = 0; c < oh; ++c) {
+            const double a = (double)y[r * O + c];
+            const double b = (double)y[r * O + oh + c];
+            const double phi = 0.5 * (1.0 + erf(b / sqrt(2.0)));
+            out[r * oh + c] = (float)(a * (b * phi));
+        }
+}
+
