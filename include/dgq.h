@@ -187,6 +187,22 @@ int dgq_linear(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes
                int32_t *acc_dump, void *workspace, size_t workspace_bytes,
                void *stream);
 
+/*
+ * The same layer with the gated activation of the transformer feed-forward fused into
+ * the epilogue.  The networks the paper quantizes (Section 4.1: Stable Diffusion
+ * v1.4, SDXL-Turbo) apply, to the result y = [a | b] of the first feed-forward
+ * projection (a = channels [0, O/2), b = channels [O/2, O)),
+ *   out[r,c] = a[r,c] * GELU(b[r,c]),   GELU(t) = t * Phi(t) = t * (1 + erf(t / sqrt 2)) / 2.
+ * y[r,o] is formed exactly as in dgq_linear and never written; erf is evaluated in
+ * fp32.  w is an ordinary dgq_pack_weight handle of all O rows.
+ *   y: fp32 [rows, out_channels / 2]
+ * out_channels must be a multiple of 256 (DGQ_EUNSUPPORTED otherwise).  No
+ * accumulator dump, no workspace.  Enqueues on `stream`; does not synchronise or
+ * allocate.
+ */
+int dgq_linear_geglu(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes,
+                     const uint8_t *row_class, int64_t rows, float *y, void *stream);
+
 size_t dgq_linear_workspace_bytes(const dgq_groups_t *g, const dgq_weight_t *w,
                                   int64_t rows);
 

@@ -54,6 +54,7 @@ def lib():
         L.dgq_weight_free.restype = None
         L.dgq_quantize_act.argtypes = [vp, vp, i64, vp, vp, vp]
         L.dgq_linear.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+        L.dgq_linear_geglu.argtypes = [vp, vp, vp, vp, i64, vp, vp]
         L.dgq_codes_bytes.argtypes = [vp, i64]
         L.dgq_codes_bytes.restype = sz
         L.dgq_linear_workspace_bytes.argtypes = [vp, vp, i64]
@@ -222,6 +223,25 @@ def dgq_linear(groups: Groups, weight: Weight, codes, row_class, y=None, acc_dum
             raise ValueError("acc_dump has the wrong shape")
     _check(lib().dgq_linear(groups.handle, weight.handle, _ptr(codes), _ptr(row_class), rows,
                             _ptr(y), _ptr(acc_dump), None, 0, _stream(stream)))
+    return y
+
+
+def dgq_linear_geglu(groups: Groups, weight: Weight, codes, row_class, y=None, stream=None):
+    """Returns fp32 [rows, O / 2]: first half of the layer's outputs times GELU(second half)."""
+    import torch
+    _dev(codes, torch.int8, "codes")
+    _dev(row_class, torch.uint8, "row_class")
+    rows = row_class.numel()
+    if tuple(codes.shape) != codes_shape(groups, rows):
+        raise ValueError("codes / row_class have the wrong shape")
+    oh = weight.out_channels // 2
+    if y is None:
+        y = torch.empty((rows, oh), dtype=torch.float32, device=codes.device)
+    _dev(y, torch.float32, "y")
+    if tuple(y.shape) != (rows, oh):
+        raise ValueError("y has the wrong shape")
+    _check(lib().dgq_linear_geglu(groups.handle, weight.handle, _ptr(codes), _ptr(row_class),
+                                  rows, _ptr(y), _stream(stream)))
     return y
 
 

@@ -444,7 +444,29 @@ int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *code
         return fail(DGQ_EALIGN, "dgq_linear: tensor not 16-byte aligned");
     if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
         return fail(DGQ_EUNSUPPORTED, "dgq_linear: too many output tiles");
-    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump,
+    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump, false,
+                          static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+int dgq_linear_geglu(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *codes,
+                     const uint8_t *row_class, int64_t rows, float *y, void *stream) {
+    if (!h || !hw || !codes || !row_class || !y)
+        return fail(DGQ_EINVAL, "dgq_linear_geglu: null pointer");
+    if (rows < 1) return fail(DGQ_EINVAL, "dgq_linear_geglu: rows < 1");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    const Weight *w = reinterpret_cast<const Weight *>(hw);
+    if (w->groups != g)
+        return fail(DGQ_ESHAPE, "dgq_linear_geglu: weight was packed for a different group handle");
+    if (w->O % 256 != 0)
+        return fail(DGQ_EUNSUPPORTED,
+                    "dgq_linear_geglu: out_channels must be a multiple of 256 (value and gate "
+                    "halves in whole 128-channel tiles)");
+    if (!aligned16(codes) || !aligned16(y))
+        return fail(DGQ_EALIGN, "dgq_linear_geglu: tensor not 16-byte aligned");
+    if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear_geglu: too many output tiles");
+    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, nullptr, true,
                           static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }

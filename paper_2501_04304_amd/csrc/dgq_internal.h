@@ -100,9 +100,11 @@ hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t 
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
                                uint8_t *row_class, hipStream_t st);
 
+// geglu: y is [rows, O / 2] and receives value * GELU(gate) (first / second half of the
+// output channels); needs O % 256 == 0 and no accumulator dump.
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
-                         hipStream_t st);
+                         bool geglu, hipStream_t st);
 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,

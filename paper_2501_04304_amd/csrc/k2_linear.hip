@@ -92,7 +92,11 @@ struct Cfg {
     static_assert((STAGES - 2) * LOADS < 64, "vmcnt is a 6-bit counter");
 };
 
-template <class CF, bool DUMP>
+// GEGLU: the tile's TO weight rows are TO/2 "value" rows o0/2 .. and the TO/2 "gate" rows
+// O/2 + o0/2 .. of the same output channels; the epilogue writes value * GELU(gate) into
+// y [rows, O/2] (the gated feed-forward of the transformer blocks), so the 2x wider
+// pre-activation never reaches memory.  Needs BO == 2 and O % (2 TO) == 0.
+template <class CF, bool DUMP, bool GEGLU>
 __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int8_t *__restrict__ codes, const uint8_t *__restrict__ row_class,
     const int8_t *__restrict__ wq, const float *__restrict__ sw, const float *__restrict__ zb,
@@ -144,7 +148,12 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             dst[j] = i * 1024;
         } else {
             const int ib = i - CF::AINSTR;
-            src[j] = wq + (((int64_t)(o0 / 16 + ib) * n_chunks) << 10) + lane * 16;
+            int32_t rb = o0 / 16 + ib;  // 16-row block of the packed weights
+            if (GEGLU) {
+                constexpr int HB = CF::BINSTR / 2;  // value blocks first, then the gate blocks
+                rb = ib < HB ? (o0 / 2) / 16 + ib : (O / 2 + o0 / 2) / 16 + (ib - HB);
+            }
+            src[j] = wq + (((int64_t)rb * n_chunks) << 10) + lane * 16;
             dst[j] = CF::ABYTES + ib * 1024;
         }
     }
@@ -172,7 +181,8 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     float col_sw[BO], col_zb0[BO], col_zb1[BO];  // per-lane output-channel constants
 #pragma unroll
     for (int b = 0; b < BO; ++b) {
-        const int32_t o = o0 + (wo * BO + b) * 32 + m32;  // o < O_pad always
+        int32_t o = o0 + (wo * BO + b) * 32 + m32;  // o < O_pad always
+        if (GEGLU) o = (b ? O / 2 : 0) + o0 / 2 + wo * 32 + m32;
         col_sw[b] = sw[o];
         col_zb0[b] = zb[o];
         col_zb1[b] = zb[O_pad + o];
@@ -185,7 +195,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     int a_off[2], b_off[2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-        const int rowa = wr * BR * 32 + m32, rowb = wo * BO * 32 + m32;
+        const int rowa = wr * BR * 32 + m32, rowb = (GEGLU ? wo * 32 : wo * BO * 32) + m32;
         if (ABITS == 8)
             a_off[ks] = rowa * 64 + (((ks * 2 + kh) ^ swz64(rowa)) * 16);
         else
@@ -209,7 +219,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         }
 #pragma unroll
         for (int b = 0; b < BO; ++b)
-            bf[b] = *reinterpret_cast<const v4i *>(base + b_off[ks] + b * 32 * 64);
+            bf[b] = *reinterpret_cast<const v4i *>(base + b_off[ks] + b * (GEGLU ? CF::TO / 2 : 32) * 64);
     };
 
     // Make the compiler wait for a fragment set HERE (before the next set's reads are
@@ -322,6 +332,44 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                         zz = p ? zb1 : zb0;
                     facc[a][b][i] = fmaf(swo, facc[a][b][i], zz);
                 }
+        }
+        if constexpr (GEGLU) {
+            // block 0 holds the value, block 1 the gate of the same output channel:
+            // out = value * gate * Phi(gate), written to y [rows, O / 2]
+            const int32_t oh = O >> 1;
+            const int32_t oc = (o0 >> 1) + wo * 32 + m32;  // < O / 2: the tiles divide it
+#pragma unroll
+            for (int a = 0; a < BR; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float gate = facc[a][1][i];
+                    const float phi = 0.5f * (1.0f + erff(gate * 0.70710678118654752f));
+                    facc[a][0][i] = facc[a][0][i] * (gate * phi);
+                }
+            if (r0 + CF::TR <= rows) {
+                const uint32_t lane_off = (uint32_t)(4 * kh * oh + m32) * 4u;
+                char *tile_ptr = reinterpret_cast<char *>(y + r0 * oh + (o0 >> 1) + wo * 32);
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + (i & 3);
+                        char *rp = tile_ptr + (int64_t)rl * oh * 4;
+                        asm volatile("global_store_dword %0, %1, %2 nt"
+                                     :
+                                     : "v"(lane_off), "v"(facc[a][0][i]), "s"(rp)
+                                     : "memory");
+                    }
+            } else {
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                        if (!((past[a] >> i) & 1)) y[(r0 + rl) * oh + oc] = facc[a][0][i];
+                    }
+            }
+            return;
         }
         // Register i of a block holds row 8 (i / 4) + 4 kh + i % 4 at column m32: one
         // store instruction writes two 128-byte row pieces.  Interior tiles use a scalar
@@ -449,7 +497,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         run(std::false_type{});
 }
 
-template <class CF, bool DUMP>
+template <class CF, bool DUMP, bool GEGLU = false>
 hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
                       const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
                       hipStream_t st) {
@@ -459,7 +507,8 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     const int32_t per_xcd = (int32_t)((T + 7) / 8);
     const dim3 grid((unsigned)(per_xcd * 8));
     size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES + 12 * (size_t)g.info.n_groups;
-    auto kern = k_linear<CF, DUMP>;
+    static_assert(!GEGLU || CF::BO == 2, "the gated epilogue pairs the two blocks of a wave");
+    auto kern = k_linear<CF, DUMP, GEGLU>;
     {
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kStageBudget);
         if (e != hipSuccess) return e;
@@ -489,7 +538,7 @@ static int g_force_cfg = -1;  // tuning hook: environment variable DGQ_LINEAR_CF
 
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
-                         hipStream_t st) {
+                         bool geglu, hipStream_t st) {
     static bool env_read = false;
     if (!env_read) {
         if (const char *e = getenv("DGQ_LINEAR_CFG")) g_force_cfg = atoi(e);
@@ -512,6 +561,9 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     if (g_force_cfg >= 0) cfg = g_force_cfg;
 #define DGQ_CASE(ID, ...)                                                                          \
     case ID:                                                                                       \
+        if (geglu)                                                                                 \
+            return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, true>(g, w, codes, row_class, rows, y, nullptr, st) \
+                      : launch_cfg<Cfg<4, __VA_ARGS__>, false, true>(g, w, codes, row_class, rows, y, nullptr, st); \
         return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st) \
                   : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
     switch (cfg) {

@@ -45,6 +45,7 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_quantize_act(None, None, 4, None, None, None) == -1
     assert b"null" in lib.dgq_last_error()
     assert lib.dgq_linear(None, None, None, None, 4, None, None, None, 0, None) == -1
+    assert lib.dgq_linear_geglu(None, None, None, None, 4, None, None) == -1
     h = C.c_void_p()
     assert lib.dgq_calibrate_groups(None, 4, 64, 8, 64, 2, None, C.byref(h)) == -1
     buf = (C.c_float * 64)()
@@ -62,7 +63,7 @@ def test_argument_errors_without_gpu(lib):
 def test_binding_names_match_the_abi():
     import paper_2501_04304_amd as dgq
     for s in ("dgq_calibrate_groups", "dgq_pack_weight", "dgq_quantize_act", "dgq_linear",
-              "dgq_xattn_logq", "dgq_xattn_workspace_bytes"):
+              "dgq_linear_geglu", "dgq_xattn_logq", "dgq_xattn_workspace_bytes"):
         assert callable(getattr(dgq, s))
 
 
