@@ -247,6 +247,51 @@ def main():
                     avg_launch_us=dom["avg_call_us"],
                     launches_per_step=dom["calls_per_step"])
 
+    # ---------------- beyond the step: the gated feed-forward epilogue fused ----------------
+    # (outside the timed step and outside `value`: the step keeps the unfused layers)
+    fused = []
+    for ent in layers:
+        if not ent["name"].endswith("ff.in") or ent["O"] % 256:
+            continue
+        yg = torch.empty((ent["M"], ent["O"] // 2), dtype=torch.float32, device=dev)
+        for (ab, wb) in cfg["modes"]:
+            m = ent["modes"][(ab, wb)]
+            a = (C.c_void_p(m["g"].handle), C.c_void_p(m["wt"].handle), ptr(m["codes"]),
+                 ptr(m["cls"]), C.c_int64(ent["M"]), ptr(yg), sp)
+            for _ in range(2):
+                if L.dgq_linear_geglu(*a) != 0:
+                    raise dgq.DgqError(-1, L.dgq_last_error().decode())
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n_rep = 10
+            e0.record(stream)
+            for _ in range(n_rep):
+                L.dgq_linear_geglu(*a)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us_f = e0.elapsed_time(e1) * 1e3 / n_rep
+            ci = [i for i, (kind, key, _) in enumerate(calls)
+                  if kind == "linear_a%d" % ab and key[0] is ent][0]
+            us_u = sum(ev[k][ci][0].elapsed_time(ev[k][ci][1]) for k in range(args.steps)) * 1e3 / args.steps
+            ops = 2.0 * ent["M"] * ent["C"] * ent["O"]
+            fused.append(dict(layer=ent["name"], act_bits=ab, us_fused=round(us_f, 2),
+                              us_linear_alone=round(us_u, 2), tops_fused=round(ops / us_f / 1e6, 1)))
+        # what the unfused pipeline pays on top of the plain layer: an elementwise pass over
+        # y (here torch's own kernels: gelu of the gate half, then the product)
+        oh = ent["O"] // 2
+        for _ in range(2):
+            torch.mul(ent["y"][:, :oh], torch.nn.functional.gelu(ent["y"][:, oh:]), out=yg)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(5):
+            torch.mul(ent["y"][:, :oh], torch.nn.functional.gelu(ent["y"][:, oh:]), out=yg)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us_sep = e0.elapsed_time(e1) * 1e3 / 5
+        for f in fused:
+            if f["layer"] == ent["name"]:
+                f["us_separate_activation_pass"] = round(us_sep, 2)
+        del yg
+
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -279,7 +324,8 @@ def main():
                 scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
-                roofline=roofline, kernels=kernels, linear_a8_layers=per_layer, cpu_baseline=cpu)
+                roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
+                linear_geglu=fused, cpu_baseline=cpu)
     print(json.dumps(line))
 
 

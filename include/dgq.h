@@ -193,8 +193,10 @@ int dgq_linear(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes
  * v1.4, SDXL-Turbo) apply, to the result y = [a | b] of the first feed-forward
  * projection (a = channels [0, O/2), b = channels [O/2, O)),
  *   out[r,c] = a[r,c] * GELU(b[r,c]),   GELU(t) = t * Phi(t) = t * (1 + erf(t / sqrt 2)) / 2.
- * y[r,o] is formed exactly as in dgq_linear and never written; erf is evaluated in
- * fp32.  w is an ordinary dgq_pack_weight handle of all O rows.
+ * y[r,o] is formed exactly as in dgq_linear and never written.  Phi comes from the
+ * rational approximation of erfc (Abramowitz and Stegun 7.1.26) in fp32: absolute
+ * error of GELU(t) at most 4e-7 |t|.  w is an ordinary dgq_pack_weight handle of all
+ * O rows.
  *   y: fp32 [rows, out_channels / 2]
  * out_channels must be a multiple of 256 (DGQ_EUNSUPPORTED otherwise).  No
  * accumulator dump, no workspace.  Enqueues on `stream`; does not synchronise or

@@ -3,9 +3,10 @@ epilogue (dgq_linear_geglu) against the CPU oracle.
 
 Two comparisons per case.  (1) The fused kernel forms y exactly as dgq_linear does (same
 accumulators, same fold order, same scale/offset FMA), so against oracle.geglu applied to
-the GPU's own unfused y only the activation differs: products and erf in fp32 instead of
-double, i.e. |err| <= 2e-6 |ref| + 3e-7 max|a| max|b| (the second term covers 1 + erf(t)
-next to -1, where fp32 loses relative but not absolute accuracy).  (2) Against the whole
+the GPU's own unfused y only the activation differs: the kernel takes Phi from a rational
+approximation of erfc (absolute error 1.5e-7 by construction, 3.2e-7 |t| on GELU(t) with its
+fp32 arithmetic, checked on the CPU over [-12, 12]) and multiplies in fp32, i.e.
+|err| <= 2e-6 |ref| + 5e-7 max|a| max|b|.  (2) Against the whole
 oracle chain the 1e-4 * max|y| allowance of the contraction passes through the activation:
 |err| <= 1e-4 max|y| (|GELU(b)| + 1.13 |a|) + the bound of (1), 1.13 being max |GELU'|.
 """
@@ -62,7 +63,7 @@ def _run(dgq, oracle, B, N, C, O, G, act_bits, seed, sample_rows=None):
     # (1) the activation alone
     ref1 = oracle.geglu(y_np[sel]).astype(np.float64)
     a, b = y_np[sel, :O // 2].astype(np.float64), y_np[sel, O // 2:].astype(np.float64)
-    lim1 = 2e-6 * np.abs(ref1) + 3e-7 * np.abs(a).max() * np.abs(b).max()
+    lim1 = 2e-6 * np.abs(ref1) + 5e-7 * np.abs(a).max() * np.abs(b).max()
     err1 = np.abs(out_np[sel] - ref1)
     assert (err1 <= lim1).all(), "activation: worst excess %.3e" % (err1 - lim1).max()
 
