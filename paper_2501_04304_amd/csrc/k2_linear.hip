@@ -53,11 +53,19 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kStageBudget = 160 * 1024;  // LDS bytes per CU
 
-#define DGQ_LDS_DMA16(gptr, lptr)                                                          \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr), \
-                                     (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+// One direct-to-LDS load: lane j copies 16 bytes from sbase + voff to LDS address l0 + 16 j.
+// Written out so that the address is a scalar base plus one 32-bit lane offset (the
+// compiler's form of the builtin keeps a 64-bit address per lane and spends two vector
+// adds per load on it; a vector instruction costs this kernel about four clocks of SIMD
+// time).  M0 carries the LDS address; nothing else in these kernels uses M0.  The load is
+// invisible to the compiler's wait-count bookkeeping, which is what the kernel wants: it
+// places every vmcnt wait itself.
+#define DGQ_LDS_DMA16(sbase, voff, l0)                                                \
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"      \
+                 :                                                                    \
+                 : "v"(voff), "s"(sbase), "s"(l0)                                     \
+                 : "memory", "m0")
 
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = {simm[15:14], simm[3:0]}).
 #define DGQ_WAIT_VMCNT(N) \
     __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
@@ -135,8 +143,13 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     // bytes [16j, 16j+16)); the blocks of a chunk are dealt round-robin to the waves.
     constexpr int kARows = ABITS == 8 ? 16 : 32;  // rows per code block
     const int64_t n_ablocks = (rows + kARows - 1) / kARows;
-    const int8_t *src[CF::LOADS];
+    const int8_t *src[CF::LOADS];  // uniform per wave
     int dst[CF::LOADS];
+    const uint32_t lane16 = lane * 16;
+    auto lds_addr = [](const uint8_t *p) {  // 32-bit LDS address of a pointer into `lds`
+        return (uint32_t)reinterpret_cast<uintptr_t>(
+            (const __attribute__((address_space(3))) uint8_t *)p);
+    };
 #pragma unroll
     for (int j = 0; j < CF::LOADS; ++j) {
         int i = wave + CF::NW * j;
@@ -144,7 +157,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         if (i < CF::AINSTR) {
             int64_t blk = r0 / kARows + i;
             blk = blk < n_ablocks ? blk : n_ablocks - 1;  // clamp: rows past the end are never stored
-            src[j] = codes + ((blk * n_chunks) << 10) + lane * 16;
+            src[j] = codes + ((blk * n_chunks) << 10);
             dst[j] = i * 1024;
         } else {
             const int ib = i - CF::AINSTR;
@@ -153,15 +166,17 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                 constexpr int HB = CF::BINSTR / 2;  // value blocks first, then the gate blocks
                 rb = ib < HB ? (o0 / 2) / 16 + ib : (O / 2 + o0 / 2) / 16 + (ib - HB);
             }
-            src[j] = wq + (((int64_t)rb * n_chunks) << 10) + lane * 16;
+            src[j] = wq + (((int64_t)rb * n_chunks) << 10);
             dst[j] = CF::ABYTES + ib * 1024;
         }
     }
-    auto issue_chunk = [&](int32_t ch) {
-        uint8_t *base = lds + (ch % STAGES) * CF::STAGE_BYTES;
+    auto issue_chunk_at = [&](int32_t ch, int stage) __attribute__((always_inline)) {
+        uint8_t *base = lds + stage * CF::STAGE_BYTES;
 #pragma unroll
-        for (int j = 0; j < CF::LOADS; ++j) DGQ_LDS_DMA16(src[j] + ((int64_t)ch << 10), base + dst[j]);
+        for (int j = 0; j < CF::LOADS; ++j)
+            DGQ_LDS_DMA16(src[j] + ((int64_t)ch << 10), lane16, lds_addr(base + dst[j]));
     };
+    auto issue_chunk = [&](int32_t ch) { issue_chunk_at(ch, ch % STAGES); };
 
     // ---- prologue: fill the ring before anything else is loaded ----------------------------
 #pragma unroll
@@ -425,23 +440,33 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         // work on one k-step the LDS reads of the next one are in flight.  The barrier
         // that publishes chunk ch+1 (and retires the stage chunk ch-1 used) sits between
         // the two k-steps of chunk ch.
-        for (int32_t ch = 0; ch < n_chunks; ++ch) {
-            const uint8_t *base = lds + (ch % STAGES) * CF::STAGE_BYTES;
+        // One chunk.  STEADY: the ring is full and chunk ch + STAGES - 1 exists, so the wait
+        // count is a constant, the next DMA unconditional, and `pos` (the ring stage of
+        // chunk ch) a literal: the stage addresses then sit in the LDS instructions'
+        // offset fields instead of costing vector adds (a vector instruction costs this
+        // kernel about four clocks of SIMD time with nothing hidden behind it).
+        auto chunk = [&](auto steady_tag, const int pos, const int32_t ch) __attribute__((always_inline)) {
+            constexpr bool STEADY = decltype(steady_tag)::value;
+            const int npos = pos + 1 == STAGES ? 0 : pos + 1;
+            const uint8_t *base = lds + pos * CF::STAGE_BYTES;
             touch_frags(af0, bf0);
             load_frags(base, 1, af1, bf1);
             mfma_all(af0, bf0, fresh);
             fresh = false;
             touch_frags(af1, bf1);
-            if (ch + 1 < n_chunks) {
+            if (STEADY || ch + 1 < n_chunks) {
                 asm volatile("" ::: "memory");
                 if (DUMP)
                     DGQ_WAIT_VMCNT(0);
+                else if (STEADY)
+                    DGQ_WAIT_VMCNT((STAGES - 3) * CF::LOADS);
                 else
                     wait_chunks_pending<STAGES - 3, CF::LOADS>(n_chunks - 2 - ch);
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                if (ch + STAGES - 1 < n_chunks) issue_chunk(ch + STAGES - 1);
-                load_frags(lds + ((ch + 1) % STAGES) * CF::STAGE_BYTES, 0, af0, bf0);
+                if (STEADY || ch + STAGES - 1 < n_chunks)
+                    issue_chunk_at(ch + STAGES - 1, pos == 0 ? STAGES - 1 : pos - 1);
+                load_frags(lds + npos * CF::STAGE_BYTES, 0, af0, bf0);
             }
             mfma_all(af1, bf1, false);
 
@@ -486,6 +511,19 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                 ++g;
                 g_end = g < NG ? __builtin_amdgcn_readfirstlane(tab_end[g]) : 0x7fffffff;
             }
+        };
+        int32_t ch = 0;
+        if (!DUMP && STAGES <= 4) {
+            // STAGES chunks per trip, every one of them in the steady state
+            while (ch + 2 * STAGES - 2 < n_chunks) {
+#pragma unroll
+                for (int u = 0; u < STAGES; ++u) chunk(std::true_type{}, u, ch + u);
+                ch += STAGES;
+            }
+        }
+        for (int pos = ch % STAGES; ch < n_chunks; ++ch) {
+            chunk(std::false_type{}, pos, ch);
+            pos = pos + 1 == STAGES ? 0 : pos + 1;
         }
 
         epilogue(mixed_tag, p);
