@@ -363,17 +363,17 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                 }
             if (r0 + CF::TR <= rows) {
                 const uint32_t lane_off = (uint32_t)(4 * kh * oh + m32) * 4u;
-                char *tile_ptr = reinterpret_cast<char *>(y + r0 * oh + (o0 >> 1) + wo * 32);
+                const int64_t row_bytes = (int64_t)oh * 4;
+                char *rp = reinterpret_cast<char *>(y + (r0 + wr * BR * 32) * oh + (o0 >> 1) + wo * 32);
 #pragma unroll
                 for (int a = 0; a < BR; ++a)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + (i & 3);
-                        char *rp = tile_ptr + (int64_t)rl * oh * 4;
                         asm volatile("global_store_dword %0, %1, %2 nt"
                                      :
                                      : "v"(lane_off), "v"(facc[a][0][i]), "s"(rp)
                                      : "memory");
+                        rp += (i & 3) == 3 ? 5 * row_bytes : row_bytes;  // rows 0 1 2 3, 8 9 ...
                     }
             } else {
 #pragma unroll
@@ -393,22 +393,26 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         const bool interior = r0 + CF::TR <= rows && o0 + CF::TO <= O;
         if (interior) {
             const uint32_t lane_off = (uint32_t)(4 * kh * O + m32) * 4u;
-            char *tile_ptr = reinterpret_cast<char *>(y + r0 * O + o0);
+            // scalar row pointer + 32-bit lane offset + the column block as the instruction's
+            // offset field, spelled out so that no vector instruction and one scalar add
+            // per row is spent on addresses (rows go 0 1 2 3, 8 9 10 11, ...)
+            const int64_t row_bytes = (int64_t)O * 4;
+            char *rp = reinterpret_cast<char *>(y + (r0 + wr * BR * 32) * O + o0 + wo * BO * 32);
 #pragma unroll
             for (int a = 0; a < BR; ++a)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int rl = (wr * BR + a) * 32 + 8 * (i >> 2) + (i & 3);
-#pragma unroll
-                    for (int b = 0; b < BO; ++b) {
-                        // scalar base + 32-bit lane offset, spelled out so that no vector
-                        // instruction is spent on the address
-                        char *rp = tile_ptr + ((int64_t)rl * O + (wo * BO + b) * 32) * 4;
-                        asm volatile("global_store_dword %0, %1, %2 nt"
+                    static_assert(BO <= 2, "column blocks are addressed by the offset field");
+                    asm volatile("global_store_dword %0, %1, %2 nt"
+                                 :
+                                 : "v"(lane_off), "v"(facc[a][0][i]), "s"(rp)
+                                 : "memory");
+                    if (BO == 2)
+                        asm volatile("global_store_dword %0, %1, %2 offset:128 nt"
                                      :
-                                     : "v"(lane_off), "v"(facc[a][b][i]), "s"(rp)
+                                     : "v"(lane_off), "v"(facc[a][BO - 1][i]), "s"(rp)
                                      : "memory");
-                    }
+                    rp += (i & 3) == 3 ? 5 * row_bytes : row_bytes;  // after row 31: 8 * 3 + 3 + 5 = 32
                 }
         } else {
 #pragma unroll
