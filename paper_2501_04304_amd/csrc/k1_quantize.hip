@@ -22,6 +22,8 @@
 // multiply, round, clamp and the byte pack.
 #include "dgq_internal.h"
 
+#include <type_traits>
+
 namespace dgq {
 
 namespace {
@@ -29,22 +31,41 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;
 
-__device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float t = __shfl_xor(v, o, kWave);
-        v = t > v ? t : v;
-    }
-    return v;
+// Three-operand max / min as the instruction itself: written through the compiler's
+// fmaxf they come wrapped in one canonicalising instruction per loaded value.
+__device__ inline float max3(float a, float b, float c) {
+    float d;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
 }
-__device__ inline float wave_min(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float t = __shfl_xor(v, o, kWave);
-        v = t < v ? t : v;
-    }
-    return v;
+__device__ inline float min3(float a, float b, float c) {
+    float d;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
 }
+
+// Wave-wide maximum of mx and minimum of mn without LDS traffic, both returned as
+// wave-uniform values.  Four cross-lane (DPP) steps leave every 16-lane row with its own
+// extreme (lane ^ 1, lane ^ 2, mirrored halves, mirrored row), two row broadcasts carry
+// it on to lane 63.  The two chains alternate and one s_nop separates the steps: a DPP
+// operand may be read two wait states after the register was written at the earliest.
+#define DGQ_DPP_STEP(ctrl)                                 \
+    "v_max_f32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n\t" \
+    "v_min_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n\t" \
+    "s_nop 0\n\t"
+__device__ inline void wave_max_min(float &mx, float &mn) {
+    asm("s_nop 1\n\t"
+        DGQ_DPP_STEP("quad_perm:[1,0,3,2] row_mask:0xf")
+        DGQ_DPP_STEP("quad_perm:[2,3,0,1] row_mask:0xf")
+        DGQ_DPP_STEP("row_half_mirror row_mask:0xf")
+        DGQ_DPP_STEP("row_mirror row_mask:0xf")
+        DGQ_DPP_STEP("row_bcast:15 row_mask:0xa")
+        DGQ_DPP_STEP("row_bcast:31 row_mask:0xc")
+        : "+v"(mx), "+v"(mn));
+    mx = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mx), 63));
+    mn = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mn), 63));
+}
+#undef DGQ_DPP_STEP
 
 // q as a float in [0, qmax]; separate subtract and multiply (no contraction).
 __device__ inline float quant1(float x, float z, float inv_s, float qmax) {
@@ -53,10 +74,39 @@ __device__ inline float quant1(float x, float z, float inv_s, float qmax) {
     return fminf(fmaxf(rintf(u), 0.0f), qmax);
 }
 
-// LDS: [off32: Kp u32][keep: one u32 per output dword][cz: 2 * n_chunks float2][rows: 4 * C floats]
-__host__ __device__ inline size_t lds_table_bytes(int32_t Kp, int bits) {
-    return (size_t)Kp * 4 + (size_t)(Kp / (bits == 8 ? 4 : 8)) * 4;  // both multiples of 16 (Kp % 64 == 0)
+// The same value, unrounded, for v_cvt_pk_u8_f32 to finish: that instruction rounds to
+// nearest even and saturates to [0, 255] (NaN -> 0) by itself (checked against
+// rint + clamp on a million values, ties and the values next to them included), so at
+// 8 bit nothing is left to do, and at 4 bit only the upper clamp, which commutes with
+// the rounding because the bound is an integer.  v_med3_f32 returns the minimum of its
+// operands when one is NaN, i.e. 0 here, as the three-step form does.
+template <int BITS>
+__device__ inline float quant_pre(float x, float z, float inv_s) {
+    const float t = __fsub_rn(x, z);
+    const float u = __fmul_rn(t, inv_s);
+    return BITS == 8 ? u : __builtin_amdgcn_fmed3f(u, 0.0f, 15.0f);
 }
+
+// LDS: [off32: kPer u32 per output dword][keep: one u32 per output dword]
+//      [cz: 2 classes x chunks float2][rows: 4 * C floats].
+// The tables are padded to whole steps of 64 output dwords (a step is what the 64 lanes
+// do at once), so a lane of the last, partly filled step reads valid table entries
+// (offset 0, keep-mask 0) and only its store is predicated.
+struct QuantLds {
+    int32_t n_dw, n_steps, n_dw_pad, nch_pad;
+    size_t off_bytes, keep_bytes, cz_bytes;
+    __host__ __device__ QuantLds(int32_t Kp, int bits) {
+        const int per = bits == 8 ? 4 : 8;
+        n_dw = Kp / per;
+        n_steps = (n_dw + 63) >> 6;
+        n_dw_pad = n_steps * 64;
+        nch_pad = n_dw_pad / (64 / per);
+        off_bytes = (size_t)n_dw_pad * per * 4;
+        keep_bytes = (size_t)n_dw_pad * 4;
+        cz_bytes = (size_t)2 * nch_pad * 8;
+    }
+    __host__ __device__ size_t table_bytes() const { return off_bytes + keep_bytes + cz_bytes; }
+};
 
 // NV: float4 registers per lane that hold one row (C <= NV * 256).
 template <int BITS, int NV>
@@ -66,32 +116,21 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
     uint8_t *__restrict__ row_class, int32_t rpw_log2) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    constexpr int kPer = BITS == 8 ? 4 : 8;  // positions per output dword
+    constexpr int kPer = BITS == 8 ? 4 : 8;          // positions per output dword
+    constexpr int kDwPerChunk = 64 / kPer;           // 16 or 8
+    constexpr int kChunkStep = kWave / kDwPerChunk;  // chunks per step: 4 or 8
+    const QuantLds L(Kp, BITS);
     uint32_t *off32 = reinterpret_cast<uint32_t *>(lds_raw);
-    uint32_t *keep = off32 + Kp;
-    float2 *cz = reinterpret_cast<float2 *>(lds_raw + lds_table_bytes(Kp, BITS));
-    float *rowbuf = reinterpret_cast<float *>(cz + 2 * n_chunks);
+    uint32_t *keep = reinterpret_cast<uint32_t *>(lds_raw + L.off_bytes);
+    float2 *cz = reinterpret_cast<float2 *>(lds_raw + L.off_bytes + L.keep_bytes);
+    float *rowbuf = reinterpret_cast<float *>(lds_raw + L.table_bytes());
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    // the wave index as a scalar: rows, row pointers and classes are then wave-uniform
+    // values in scalar registers and the loads and stores take scalar bases
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     float *xs = rowbuf + (size_t)wave * C;  // this wave's copy of the row
-    constexpr float qmax = (float)((1 << BITS) - 1);
-    const int32_t c4n = C >> 2;  // float4 per row
-    const int32_t n_dw = Kp / kPer;
-
-    for (int32_t d = tid; d < n_dw; d += 256) {
-        uint32_t m = 0;
-#pragma unroll
-        for (int k = 0; k < kPer; ++k) {
-            const int32_t c = perm[d * kPer + k];
-            off32[d * kPer + k] = c >= 0 ? (uint32_t)c * 4u : 0u;
-            // 8 bit: byte k of the word; 4 bit: byte k % 4, low nibble for k < 4, high otherwise
-            const uint32_t field = BITS == 8 ? 0xffu << (8 * k) : 0xfu << (8 * (k & 3) + 4 * (k >> 2));
-            if (c >= 0) m |= field;
-        }
-        keep[d] = m;
-    }
-    for (int32_t i = tid; i < 2 * n_chunks; i += 256) cz[i] = make_float2(chunk_z[i], chunk_inv[i]);
-    __syncthreads();
+    const uint32_t c4n = (uint32_t)C >> 2;  // float4 per row
+    const int32_t n_dw = L.n_dw;
 
     // rows: a workgroup takes units of 4 << rpw_log2 consecutive rows, wave w the rows
     // (w << rpw_log2) .. of the unit, one after the other.  rpw_log2 = 2: a unit is one
@@ -103,19 +142,18 @@ __global__ __launch_bounds__(256) void k_quantize_act(
         const int64_t u = (int64_t)blockIdx.x + (it >> rpw_log2) * gridDim.x;
         return u < n_units ? (u << us) + (wave << rpw_log2) + (it & ((1 << rpw_log2) - 1)) : rows;
     };
-    // Branch-free loads: a lane index past the end of the row (and a row index past the
-    // end of the tensor) is clamped to the last valid one, which re-reads a value that is
-    // already part of the row, so max/min and the LDS copy are unaffected.
+    // A lane index past the end of the row is clamped to the last valid one, which
+    // re-reads a value that is already part of the row, so max/min and the LDS copy are
+    // unaffected.
     float4 v[NV];
-    int32_t cidx[NV];
+    uint32_t cidx[NV];
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
-        const int32_t c = lane + k * kWave;
+        const uint32_t c = lane + k * kWave;
         cidx[k] = c < c4n ? c : c4n - 1;
     }
-    auto fetch = [&](int64_t r) {
-        const int64_t re = r < rows ? r : rows - 1;
-        const float4 *x4 = reinterpret_cast<const float4 *>(x + re * C);
+    auto fetch = [&](int64_t r) {  // r < rows, wave-uniform
+        const float4 *x4 = reinterpret_cast<const float4 *>(x + r * C);
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             // the activations are read exactly once: non-temporal, keep the caches for the codes
@@ -125,9 +163,42 @@ __global__ __launch_bounds__(256) void k_quantize_act(
         }
     };
 
+    // the first row travels while the tables are built
     int64_t it = 0;
     int64_t r = row_of(0);
-    fetch(r);
+    if (r < rows) fetch(r);
+
+    for (int32_t d = tid; d < L.n_dw_pad; d += 256) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int32_t j = d * kPer + k;
+            const int32_t c = j < Kp ? perm[j] : -1;
+            off32[j] = c >= 0 ? (uint32_t)c * 4u : 0u;
+            // 8 bit: byte k of the word; 4 bit: byte k % 4, low nibble for k < 4, high otherwise
+            const uint32_t field = BITS == 8 ? 0xffu << (8 * k) : 0xfu << (8 * (k & 3) + 4 * (k >> 2));
+            if (c >= 0) m |= field;
+        }
+        keep[d] = m;
+    }
+    for (int32_t i = tid; i < 2 * L.nch_pad; i += 256) {
+        const int32_t p = i >= L.nch_pad, ch = i - p * L.nch_pad;
+        cz[i] = ch < n_chunks ? make_float2(chunk_z[p * n_chunks + ch], chunk_inv[p * n_chunks + ch])
+                              : make_float2(0.0f, 0.0f);
+    }
+    __syncthreads();
+
+    // Output dword d of the row covers positions 4d..4d+3 (8 bit) or 8d..8d+7 (4 bit).
+    // Lane l handles dwords l, l + 64, ... (one per step); in the tiled layout that is a
+    // fixed place inside a 64-byte (32-byte) row segment and a chunk index that advances
+    // by 4 (8 bit) or 8 (4 bit) per step, so every table and the output are read and
+    // written at a per-lane base plus a multiple of the step.
+    const char *off_lane = reinterpret_cast<const char *>(off32) + lane * (kPer * 4);
+    const char *keep_lane = reinterpret_cast<const char *>(keep) + lane * 4;
+    const uint32_t slot_lane = BITS == 8 ? (lane >> 2) & 3 : (lane >> 2) & 1;  // 16-byte slot
+    const uint32_t out_lane = (uint32_t)(lane / kDwPerChunk) * 1024u + (lane & 3) * 4u;
+    const char *xsb = reinterpret_cast<const char *>(xs);
+
     while (true) {
         // the sequence ends at the first unit index past the end; rows inside the last
         // unit but past `rows` are skipped
@@ -140,65 +211,57 @@ __global__ __launch_bounds__(256) void k_quantize_act(
 #pragma unroll
             for (int k = 0; k < NV; ++k) {
                 s4[cidx[k]] = v[k];
-                mx = fmaxf(fmaxf(fmaxf(v[k].x, v[k].y), fmaxf(v[k].z, v[k].w)), mx);
-                mn = fminf(fminf(fminf(v[k].x, v[k].y), fminf(v[k].z, v[k].w)), mn);
+                mx = max3(max3(v[k].x, v[k].y, v[k].z), v[k].w, mx);
+                mn = min3(min3(v[k].x, v[k].y, v[k].z), v[k].w, mn);
             }
-            fetch(r_next);  // in flight while this row is quantized
-            mx = wave_max(mx);
-            mn = wave_min(mn);
-            const int p = __fsub_rn(mx, mn) > tau ? 1 : 0;
+            if (r_next < rows) fetch(r_next);  // in flight while this row is quantized
+            wave_max_min(mx, mn);
+            const int p = __builtin_amdgcn_readfirstlane(__fsub_rn(mx, mn) > tau ? 1 : 0);
             if (lane == 0) row_class[r] = (uint8_t)p;
-            const float2 *czp = cz + p * n_chunks;
+            const char *cz_lane = reinterpret_cast<const char *>(cz + p * L.nch_pad + lane / kDwPerChunk);
             // The LDS slice is private to this wave and a wave's LDS operations complete
             // in issue order, so a compiler-level fence is all that is needed.
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
 
-            // Output dword d of the row covers positions 4d..4d+3 (8 bit) or 8d..8d+7
-            // (4 bit).  Lane l handles dwords l, l + 64, ...; in the tiled layout that is a
-            // fixed place inside a 64-byte (32-byte) row segment and a chunk index that
-            // advances by 4 (8 bit) or 8 (4 bit) per step.  Four steps are processed
-            // together so that their LDS round trips overlap.
-            constexpr int kDwPerChunk = 64 / kPer;            // 16 or 8
-            constexpr int kChunkStep = kWave / kDwPerChunk;   // chunks per step: 4 or 8
-            const int64_t lane_off =
-                (BITS == 8 ? tiled64_offset(r, lane / kDwPerChunk, n_chunks, (lane >> 2) & 3)
-                           : tiled32_offset(r, lane / kDwPerChunk, n_chunks, (lane >> 2) & 1)) +
-                (lane & 3) * 4;
-            int8_t *out_lane = codes + lane_off;
-            const char *xsb = reinterpret_cast<const char *>(xs);
-            for (int32_t d0 = lane; d0 < n_dw; d0 += 4 * kWave) {
-                uint32_t off[4][kPer];
-                float2 zi[4];
-                uint32_t km[4];
-                bool live[4];
+            // this row's place in the tiled layout: scalar base, per-lane 32-bit offset
+            const uint32_t t16 = (uint32_t)r & (BITS == 8 ? 15u : 31u);
+            int8_t *out_row = codes + (((r >> (BITS == 8 ? 4 : 5)) * n_chunks) << 10) +
+                              t16 * (BITS == 8 ? 64u : 32u);
+            const uint32_t out_off =
+                out_lane + ((slot_lane ^ (uint32_t)(BITS == 8 ? swz64((int)t16) : swz32((int)t16))) << 4);
+
+            // NT steps together, so that their LDS round trips overlap
+            auto steps = [&](auto nt_tag, const int32_t j0) __attribute__((always_inline)) {
+                constexpr int NT = decltype(nt_tag)::value;
+                uint32_t off[NT][kPer];
+                float2 zi[NT];
+                uint32_t km[NT];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int32_t d = d0 + t * kWave;
-                    live[t] = d < n_dw;
-                    const int32_t dc = live[t] ? d : n_dw - 1;  // clamp: reads stay in range
-                    zi[t] = czp[dc / kDwPerChunk];
-                    km[t] = keep[dc];
-                    const uint4 o0 = *reinterpret_cast<const uint4 *>(off32 + kPer * dc);
+                for (int t = 0; t < NT; ++t) {
+                    const uint32_t j = (uint32_t)(j0 + t);
+                    zi[t] = *reinterpret_cast<const float2 *>(cz_lane + j * (kChunkStep * 8));
+                    km[t] = *reinterpret_cast<const uint32_t *>(keep_lane + j * 256u);
+                    const uint4 o0 = *reinterpret_cast<const uint4 *>(off_lane + j * (64u * kPer * 4));
                     off[t][0] = o0.x; off[t][1] = o0.y; off[t][2] = o0.z; off[t][3] = o0.w;
-                    if (BITS == 4) {
-                        const uint4 o1 = *reinterpret_cast<const uint4 *>(off32 + kPer * dc + 4);
+                    if constexpr (BITS == 4) {
+                        const uint4 o1 = *reinterpret_cast<const uint4 *>(off_lane + j * (64u * kPer * 4) + 16);
                         off[t][4] = o1.x; off[t][5] = o1.y; off[t][6] = o1.z; off[t][7] = o1.w;
                     }
                 }
-                float xv[4][kPer];
+                float xv[NT][kPer];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < NT; ++t)
 #pragma unroll
                     for (int k = 0; k < kPer; ++k)
                         xv[t][k] = *reinterpret_cast<const float *>(xsb + off[t][k]);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
+                for (int t = 0; t < NT; ++t) {
                     uint32_t lo = 0, hi = 0;
 #pragma unroll
                     for (int k = 0; k < kPer; ++k) {
-                        const float qf = quant1(xv[t][k], zi[t].x, zi[t].y, qmax);
-                        // exact small integer -> byte k of the word
+                        const float qf = quant_pre<BITS>(xv[t][k], zi[t].x, zi[t].y);
+                        // rounds, saturates and places byte k of the word
                         if (k < 4)
                             lo = __builtin_amdgcn_cvt_pk_u8_f32(qf, k, lo);
                         else
@@ -208,15 +271,23 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                     // position i (low nibble) and position i + 4 (high nibble).  Padding
                     // positions are cleared to the stored value 0.
                     const uint32_t word = (BITS == 8 ? (lo ^ 0x80808080u) : (lo | (hi << 4))) & km[t];
-                    if (live[t])
-                        *reinterpret_cast<uint32_t *>(out_lane + ((int64_t)(d0 - lane) / kWave + t) *
-                                                                     (kChunkStep * 1024)) = word;
+                    const uint32_t j = (uint32_t)(j0 + t);
+                    if ((int32_t)(lane + 64u * j) < n_dw)
+                        *reinterpret_cast<uint32_t *>(out_row + (out_off + j * (kChunkStep * 1024u))) = word;
                 }
+            };
+            int32_t j0 = 0;
+            for (; j0 + 4 <= L.n_steps; j0 += 4) steps(std::integral_constant<int, 4>{}, j0);
+            switch (L.n_steps - j0) {
+                case 3: steps(std::integral_constant<int, 3>{}, j0); break;
+                case 2: steps(std::integral_constant<int, 2>{}, j0); break;
+                case 1: steps(std::integral_constant<int, 1>{}, j0); break;
+                default: break;
             }
             // the next row overwrites xs
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-        } else {
+        } else if (r_next < rows) {
             fetch(r_next);
         }
         r = r_next;
@@ -249,8 +320,7 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
             mx = fmaxf(v, mx);
             mn = fminf(v, mn);
         }
-        mx = wave_max(mx);
-        mn = wave_min(mn);
+        wave_max_min(mx, mn);
         const int p = __fsub_rn(mx, mn) > tau ? 1 : 0;
         if (lane == 0) row_class[r] = (uint8_t)p;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -306,8 +376,7 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     int32_t rpw_log2 = 2;
     if (vec4) {
         kern = g.info.act_bits == 8 ? pick_vec<8>(C) : pick_vec<4>(C);
-        lds = lds_table_bytes(Kp, g.info.act_bits) + sizeof(float) * 4 * (size_t)g.n_chunks +
-              sizeof(float) * (size_t)C * kWavesPerBlock;
+        lds = QuantLds(Kp, g.info.act_bits).table_bytes() + sizeof(float) * (size_t)C * kWavesPerBlock;
         blocks = (rows + 15) / 16;
         if (blocks < 256) {  // fewer 16-row blocks than CUs: quarter blocks, one row per wave
             rpw_log2 = 0;
