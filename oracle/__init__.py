@@ -79,6 +79,8 @@ class Groups:
     D_channel: float
     D_pixel: float
     cal_row_class: np.ndarray
+    taus: np.ndarray = None   # [P-1] ascending row-range thresholds (class = number below the range)
+    mode: int = -1            # -1 hybrid grid; 0 / 1 single-dimension grouping along channel / pixel
 
 
 def calibrate(x, act_bits: int, G: int, P: int = 2, granule: int = GRANULE) -> Groups:
@@ -111,7 +113,55 @@ def calibrate(x, act_bits: int, G: int, P: int = 2, granule: int = GRANULE) -> G
                   tau_pix=np.float32(tau.value),
                   s=np.ascontiguousarray(s[:, :ng]), z=np.ascontiguousarray(z[:, :ng]),
                   inv_s=np.ascontiguousarray(inv_s[:, :ng]),
-                  D_channel=float(D[0]), D_pixel=float(D[1]), cal_row_class=rc_cls)
+                  D_channel=float(D[0]), D_pixel=float(D[1]), cal_row_class=rc_cls,
+                  taus=np.array([tau.value], dtype=np.float32))
+
+
+def k_means(v, K: int):
+    """Exact 1-D K-means.  Returns (k, bounds [k+1], taus [k-1], order)."""
+    v = _f32(v)
+    bounds = np.zeros(K + 1, dtype=np.int64)
+    taus = np.zeros(max(K - 1, 1), dtype=np.float32)
+    order = np.empty(v.size, dtype=np.int64)
+    lib().dgqo_k_means.restype = C.c_int32
+    k = int(lib().dgqo_k_means(_p(v), C.c_int64(v.size), C.c_int32(K), _p(bounds), _p(taus), _p(order)))
+    return k, bounds[:k + 1].copy(), taus[:k - 1].copy(), order
+
+
+def calibrate_kmeans(x, act_bits: int, K: int, dim: int = -1, granule: int = GRANULE) -> Groups:
+    """Grouping along one dimension (dim -1: argmax D_d, 0: channel, 1: pixel) into K clusters."""
+    x = _f32(x)
+    rows, Cc = x.shape
+    assert 1 <= K <= 16
+    ng_cap = K
+    kp_cap = Cc + granule * (K + 1)
+    scal = np.zeros(8, dtype=np.int32)
+    perm = np.full(kp_cap, -1, dtype=np.int32)
+    goff = np.zeros(ng_cap + 1, dtype=np.int32)
+    glen = np.zeros(ng_cap, dtype=np.int32)
+    taus = np.zeros(64, dtype=np.float32)
+    s = np.zeros((K, ng_cap), dtype=np.float32)
+    z = np.zeros((K, ng_cap), dtype=np.float32)
+    inv_s = np.zeros((K, ng_cap), dtype=np.float32)
+    D = np.zeros(2, dtype=np.float64)
+    rc_cls = np.zeros(rows, dtype=np.uint8)
+    rc = lib().dgqo_calibrate_kmeans(_p(x), C.c_int64(rows), C.c_int32(Cc), C.c_int32(act_bits),
+                                     C.c_int32(K), C.c_int32(dim), C.c_int32(granule),
+                                     C.c_int32(ng_cap), C.c_int32(kp_cap), _p(scal), _p(perm),
+                                     _p(goff), _p(glen), _p(taus), _p(s), _p(z), _p(inv_s),
+                                     _p(D), _p(rc_cls))
+    if rc != 0:
+        raise RuntimeError("oracle calibrate_kmeans: capacity too small")
+    ng, kp, P = int(scal[0]), int(scal[1]), int(scal[6])
+    taus = taus[:P - 1].copy() if P > 1 else np.array([np.inf], dtype=np.float32)
+    return Groups(C=Cc, act_bits=act_bits, G=0, P=P, NG=ng, Kp=kp, n_outlier_channels=0,
+                  n_regular_groups=0, dstar=int(scal[4]), n_class1_rows=int(scal[5]),
+                  perm=perm[:kp].copy(), goff=goff[:ng + 1].copy(), glen=glen[:ng].copy(),
+                  tau_pix=np.float32(taus[0]),
+                  s=np.ascontiguousarray(s[:P, :ng]), z=np.ascontiguousarray(z[:P, :ng]),
+                  inv_s=np.ascontiguousarray(inv_s[:P, :ng]),
+                  D_channel=float(D[0]), D_pixel=float(D[1]), cal_row_class=rc_cls,
+                  taus=taus, mode=int(scal[7]))
 
 
 def quantize_act(g: Groups, x, want_dq: bool = False):
@@ -123,10 +173,11 @@ def quantize_act(g: Groups, x, want_dq: bool = False):
     cls = np.zeros(rows, dtype=np.uint8)
     xdq = np.zeros((rows, g.C), dtype=np.float64) if want_dq else None
     clip = np.zeros((rows, g.C), dtype=np.uint8) if want_dq else None
-    lib().dgqo_quantize_act(_p(x), C.c_int64(rows), C.c_int32(g.C), C.c_int32(g.act_bits),
-                            C.c_int32(g.NG), C.c_int32(g.NG), _p(g.perm), _p(g.goff),
-                            _p(g.glen), C.c_float(float(g.tau_pix)), _p(g.s), _p(g.z),
-                            _p(g.inv_s), _p(q), _p(cls), _p(xdq), _p(clip))
+    taus = _f32(g.taus if g.taus is not None else [g.tau_pix])
+    lib().dgqo_quantize_act_multi(_p(x), C.c_int64(rows), C.c_int32(g.C), C.c_int32(g.act_bits),
+                                  C.c_int32(g.NG), C.c_int32(g.NG), _p(g.perm), _p(g.goff),
+                                  _p(g.glen), _p(taus), C.c_int32(taus.size), _p(g.s), _p(g.z),
+                                  _p(g.inv_s), _p(q), _p(cls), _p(xdq), _p(clip))
     return dict(q=q, cls=cls, xdq=xdq, clip=clip)
 
 

@@ -294,11 +294,253 @@ int dgqo_calibrate(const float *x, int64_t rows, int32_t C, int32_t act_bits,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Exact 1-D K-means and the single-dimension grouping of Section 3.3        */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * K-means of a 1-D sample, solved exactly.  In one dimension an optimal
+ * clustering consists of intervals of the sorted sample, so the minimum of the
+ * within-cluster sum of squares over all partitions into k intervals is found
+ * by dynamic programming over the sorted values a[0..n):
+ *     cost(i, j) = (S2[j] - S2[i]) - (S[j] - S[i])^2 / (j - i)     cluster a[i..j)
+ *     best[1][j] = cost(0, j)
+ *     best[k][j] = min_{i} best[k-1][i] + cost(i, j),  a[i-1] < a[i] (equal values
+ *                  stay together), first minimum wins
+ * with S, S2 the running sums of a and a^2 in double, taken in sorted order
+ * (ties in the sort by index).  k = min(K, number of distinct values).
+ *   bounds[0..k]  cluster c is sorted positions [bounds[c], bounds[c+1])
+ *   taus[0..k-1)  threshold between clusters c and c+1: midpoint of their means,
+ *                 rounded to fp32 and clamped into [a[b-1], nextbelow(a[b])], so
+ *                 that "number of taus below v" reproduces the clusters
+ *   order[n]      (nullable) sorted index order
+ * Returns k.
+ */
+int32_t dgqo_k_means(const float *v, int64_t n, int32_t K, int64_t *bounds, float *taus,
+                     int64_t *order_out)
+{
+    dgqo_kv *a = (dgqo_kv *)malloc(sizeof(dgqo_kv) * (size_t)(n > 0 ? n : 1));
+    for (int64_t i = 0; i < n; ++i) {
+        a[i].v = v[i];
+        a[i].i = i;
+    }
+    qsort(a, (size_t)n, sizeof(dgqo_kv), dgqo_kv_cmp);
+    if (order_out)
+        for (int64_t i = 0; i < n; ++i) order_out[i] = a[i].i;
+    int64_t distinct = n > 0 ? 1 : 0;
+    for (int64_t i = 1; i < n; ++i) distinct += a[i - 1].v < a[i].v;
+    int32_t k_use = (int32_t)(distinct < K ? distinct : K);
+    if (k_use < 1) k_use = 1;
+    double *S = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *S2 = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    S[0] = 0.0;
+    S2[0] = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double x = (double)a[i].v;
+        S[i + 1] = S[i] + x;
+        S2[i + 1] = S2[i] + x * x;
+    }
+    /* best[k][j], from[k][j] for k = 1..k_use, j = 0..n; unreachable = negative from */
+    double *best = (double *)malloc(sizeof(double) * (size_t)(k_use + 1) * (size_t)(n + 1));
+    int64_t *from = (int64_t *)malloc(sizeof(int64_t) * (size_t)(k_use + 1) * (size_t)(n + 1));
+#define AT(k, j) ((size_t)(k) * (size_t)(n + 1) + (size_t)(j))
+    for (int32_t k = 0; k <= k_use; ++k)
+        for (int64_t j = 0; j <= n; ++j) from[AT(k, j)] = -1;
+    for (int64_t j = 1; j <= n; ++j) {
+        double d = S[j] - S[0];
+        best[AT(1, j)] = (S2[j] - S2[0]) - (d * d) / (double)j;
+        from[AT(1, j)] = 0;
+    }
+    for (int32_t k = 2; k <= k_use; ++k)
+        for (int64_t j = k; j <= n; ++j) {
+            int64_t arg = -1;
+            double bv = 0.0;
+            for (int64_t i = k - 1; i < j; ++i) {
+                if (from[AT(k - 1, i)] < 0) continue;      /* i values cannot form k-1 clusters */
+                if (!(a[i - 1].v < a[i].v)) continue;      /* no cut between equal values */
+                double d = S[j] - S[i];
+                double c = (S2[j] - S2[i]) - (d * d) / (double)(j - i);
+                double t = best[AT(k - 1, i)] + c;
+                if (arg < 0 || t < bv) {
+                    bv = t;
+                    arg = i;
+                }
+            }
+            if (arg >= 0) {
+                best[AT(k, j)] = bv;
+                from[AT(k, j)] = arg;
+            }
+        }
+    bounds[k_use] = n;
+    for (int32_t k = k_use; k >= 1; --k) bounds[k - 1] = from[AT(k, bounds[k])];
+#undef AT
+    for (int32_t c = 0; c + 1 < k_use; ++c) {
+        int64_t b0 = bounds[c], b1 = bounds[c + 1], b2 = bounds[c + 2];
+        double mean_l = (S[b1] - S[b0]) / (double)(b1 - b0);
+        double mean_r = (S[b2] - S[b1]) / (double)(b2 - b1);
+        float tau = (float)(0.5 * (mean_l + mean_r));
+        float lo = a[b1 - 1].v;
+        float hi = nextafterf(a[b1].v, -INFINITY);
+        if (tau < lo) tau = lo;
+        if (tau > hi) tau = hi;
+        taus[c] = tau;
+    }
+    free(a); free(S); free(S2); free(best); free(from);
+    return k_use;
+}
+
+/*
+ * Grouping along ONE dimension (Section 3.3): D_d for d in {channel, pixel},
+ * d* = argmax (dim < 0) or the given dimension (0 channel, 1 pixel); the vectors
+ * of d* (channels: all rows of a column; pixels: all channels of a row) are
+ * clustered into K groups by their range max - min with dgqo_k_means; every
+ * group k gets s_k = (max x - min x) / 2^b (1 if max == min) and z_k = min x over
+ * the calibration activations that belong to it.
+ *   channel: one pixel class; group g = cluster g in ascending range, channels in
+ *            (range, index) order, padded to the granule
+ *   pixel:   one channel group (all channels in natural order, padded); class p
+ *            of a row = number of taus below its range
+ * Outputs as dgqo_calibrate, except: scal[6] = number of pixel classes P,
+ * taus[P-1], tables s, z, inv_s [P][ng_cap] (class-major, stride ng_cap),
+ * scal[2] = scal[3] = 0.
+ */
+int dgqo_calibrate_kmeans(const float *x, int64_t rows, int32_t C, int32_t act_bits,
+                          int32_t K, int32_t dim, int32_t granule, int32_t ng_cap,
+                          int32_t kp_cap, int32_t *scal, int32_t *perm, int32_t *goff,
+                          int32_t *glen, float *taus, float *s, float *z, float *inv_s,
+                          double *D, uint8_t *row_class)
+{
+    float *rmx = (float *)malloc(sizeof(float) * (size_t)rows);
+    float *rmn = (float *)malloc(sizeof(float) * (size_t)rows);
+    float *cmx = (float *)malloc(sizeof(float) * (size_t)C);
+    float *cmn = (float *)malloc(sizeof(float) * (size_t)C);
+    for (int32_t c = 0; c < C; ++c) {
+        cmx[c] = -INFINITY;
+        cmn[c] = INFINITY;
+    }
+    for (int64_t r = 0; r < rows; ++r) {
+        float mx = -INFINITY, mn = INFINITY;
+        for (int32_t c = 0; c < C; ++c) {
+            float v = x[r * C + c];
+            if (v > mx) mx = v;
+            if (v < mn) mn = v;
+            if (v > cmx[c]) cmx[c] = v;
+            if (v < cmn[c]) cmn[c] = v;
+        }
+        rmx[r] = mx;
+        rmn[r] = mn;
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+        const float *vmx = pass == 0 ? cmx : rmx, *vmn = pass == 0 ? cmn : rmn;
+        int64_t cnt = pass == 0 ? C : rows;
+        double mxmx = -INFINITY, mnmx = INFINITY, mxmn = -INFINITY, mnmn = INFINITY;
+        for (int64_t i = 0; i < cnt; ++i) {
+            if (vmx[i] > mxmx) mxmx = vmx[i];
+            if (vmx[i] < mnmx) mnmx = vmx[i];
+            if (vmn[i] > mxmn) mxmn = vmn[i];
+            if (vmn[i] < mnmn) mnmn = vmn[i];
+        }
+        D[pass] = (mxmx - mnmx) + (mxmn - mnmn);
+    }
+    int32_t dstar = (D[1] > D[0]) ? 1 : 0;
+    int32_t use = dim < 0 ? dstar : dim;
+    const float levels = (float)(1 << act_bits);
+    int rc = 0;
+    int64_t bounds[65];
+    if (K > 64) K = 64;
+    if (use == 0) {
+        /* channels clustered by range over all rows */
+        float *cw = (float *)malloc(sizeof(float) * (size_t)C);
+        int64_t *order = (int64_t *)malloc(sizeof(int64_t) * (size_t)C);
+        float dummy[64];
+        for (int32_t c = 0; c < C; ++c) cw[c] = cmx[c] - cmn[c];
+        int32_t ng = dgqo_k_means(cw, C, K, bounds, dummy, order);
+        int32_t pos = 0;
+        for (int32_t g = 0; g < ng && rc == 0; ++g) {
+            int32_t len = (int32_t)(bounds[g + 1] - bounds[g]);
+            int32_t plen = round_up(len, granule);
+            if (g >= ng_cap || pos + plen > kp_cap) { rc = -1; break; }
+            goff[g] = pos;
+            glen[g] = len;
+            float mx = -INFINITY, mn = INFINITY;
+            for (int32_t j = 0; j < plen; ++j) {
+                int32_t c = j < len ? (int32_t)order[bounds[g] + j] : -1;
+                perm[pos + j] = c;
+                if (c >= 0) {
+                    if (cmx[c] > mx) mx = cmx[c];
+                    if (cmn[c] < mn) mn = cmn[c];
+                }
+            }
+            float sc = (mx - mn) / levels;
+            if (!(mx > mn)) sc = 1.0f;
+            s[g] = sc;
+            z[g] = mn;
+            inv_s[g] = 1.0f / sc;
+            pos += plen;
+        }
+        if (rc == 0) {
+            goff[ng] = pos;
+            scal[0] = ng;
+            scal[1] = pos;
+            scal[6] = 1;
+            if (row_class) memset(row_class, 0, (size_t)rows);
+        }
+        scal[5] = 0;
+        free(cw); free(order);
+    } else {
+        /* pixels clustered by range over all channels */
+        float *rw = (float *)malloc(sizeof(float) * (size_t)rows);
+        for (int64_t r = 0; r < rows; ++r) rw[r] = rmx[r] - rmn[r];
+        int32_t P = dgqo_k_means(rw, rows, K, bounds, taus, NULL);
+        int32_t plen = round_up(C, granule);
+        if (ng_cap < 1 || plen > kp_cap) rc = -1;
+        if (rc == 0) {
+            goff[0] = 0;
+            goff[1] = plen;
+            glen[0] = C;
+            for (int32_t j = 0; j < plen; ++j) perm[j] = j < C ? j : -1;
+            float mx[64], mn[64];
+            for (int32_t p = 0; p < P; ++p) {
+                mx[p] = -INFINITY;
+                mn[p] = INFINITY;
+            }
+            int64_t n_upper = 0;
+            for (int64_t r = 0; r < rows; ++r) {
+                int p = 0;
+                for (int32_t k = 0; k + 1 < P; ++k) p += rw[r] > taus[k];
+                if (row_class) row_class[r] = (uint8_t)p;
+                n_upper += p > 0;
+                if (rmx[r] > mx[p]) mx[p] = rmx[r];
+                if (rmn[r] < mn[p]) mn[p] = rmn[r];
+            }
+            for (int32_t p = 0; p < P; ++p) {
+                float sc = (mx[p] - mn[p]) / levels;
+                if (!(mx[p] > mn[p])) sc = 1.0f;
+                s[p * ng_cap] = sc;
+                z[p * ng_cap] = mn[p];
+                inv_s[p * ng_cap] = 1.0f / sc;
+            }
+            scal[0] = 1;
+            scal[1] = plen;
+            scal[5] = (int32_t)n_upper;
+            scal[6] = P;
+        }
+        free(rw);
+    }
+    scal[2] = 0;
+    scal[3] = 0;
+    scal[4] = dstar;
+    scal[7] = use;
+    free(rmx); free(rmn); free(cmx); free(cmn);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Activation codes (linear quantizer with the cell's scale and offset)      */
 /* ------------------------------------------------------------------------- */
 
 /*
- * For every row: class p = [max - min > tau_pix] decided on the run-time row;
+ * For every row: class p = number of thresholds below max - min (one threshold
+ * tau_pix for two classes), decided on the run-time row;
  * for every real position j of group g: t = x - z[p,g]; u = t * inv_s[p,g];
  * q = clamp(rne(u), 0, 2^b - 1).  q is the code the paper defines (unsigned).
  *   q_out   [rows, K'] codes at permuted positions (0 at padding)
@@ -306,12 +548,13 @@ int dgqo_calibrate(const float *x, int64_t rows, int32_t C, int32_t act_bits,
  *   xdq_out [rows, C]  (nullable) s*q + z in double, original channel order
  *   clip_out[rows, C]  (nullable) 1 where u < -0.5 or u > 2^b - 0.5
  */
-void dgqo_quantize_act(const float *x, int64_t rows, int32_t C, int32_t act_bits,
-                       int32_t ng, int32_t ng_cap, const int32_t *perm,
-                       const int32_t *goff, const int32_t *glen, float tau_pix,
-                       const float *s, const float *z, const float *inv_s,
-                       uint8_t *q_out, uint8_t *cls_out, double *xdq_out,
-                       uint8_t *clip_out)
+void dgqo_quantize_act_multi(const float *x, int64_t rows, int32_t C, int32_t act_bits,
+                             int32_t ng, int32_t ng_cap, const int32_t *perm,
+                             const int32_t *goff, const int32_t *glen,
+                             const float *taus, int32_t n_tau,
+                             const float *s, const float *z, const float *inv_s,
+                             uint8_t *q_out, uint8_t *cls_out, double *xdq_out,
+                             uint8_t *clip_out)
 {
     const int32_t kp = goff[ng];
     const float qmax = (float)((1 << act_bits) - 1);
@@ -323,7 +566,10 @@ void dgqo_quantize_act(const float *x, int64_t rows, int32_t C, int32_t act_bits
             if (v < mn) mn = v;
         }
         float w = mx - mn;
-        int p = w > tau_pix;
+        /* nearest centroid of clusters that are intervals of the range = number of
+           thresholds below the range (taus ascending) */
+        int p = 0;
+        for (int32_t k = 0; k < n_tau; ++k) p += w > taus[k];
         cls_out[r] = (uint8_t)p;
         for (int32_t j = 0; j < kp; ++j) q_out[r * kp + j] = 0;
         for (int32_t g = 0; g < ng; ++g) {
@@ -343,6 +589,18 @@ void dgqo_quantize_act(const float *x, int64_t rows, int32_t C, int32_t act_bits
             }
         }
     }
+}
+
+/* Two pixel classes: one threshold. */
+void dgqo_quantize_act(const float *x, int64_t rows, int32_t C, int32_t act_bits,
+                       int32_t ng, int32_t ng_cap, const int32_t *perm,
+                       const int32_t *goff, const int32_t *glen, float tau_pix,
+                       const float *s, const float *z, const float *inv_s,
+                       uint8_t *q_out, uint8_t *cls_out, double *xdq_out,
+                       uint8_t *clip_out)
+{
+    dgqo_quantize_act_multi(x, rows, C, act_bits, ng, ng_cap, perm, goff, glen, &tau_pix, 1,
+                            s, z, inv_s, q_out, cls_out, xdq_out, clip_out);
 }
 
 /* ------------------------------------------------------------------------- */
