@@ -67,11 +67,24 @@ typedef struct dgq_weight dgq_weight_t;
    positions; padded positions carry code 0 and weight 0. */
 #define DGQ_K_GRANULE 64
 
+/* Most pixel classes a group handle can hold (the paper uses K = 8 or 16 groups). */
+#define DGQ_MAX_PIXEL_CLASSES 16
+
+/* dgq_groups_info_t.grouping */
+#define DGQ_GROUPING_GRID 0     /* dgq_calibrate_groups: pixel classes x channel groups  */
+#define DGQ_GROUPING_CHANNEL 1  /* dgq_calibrate_kmeans along the channel dimension      */
+#define DGQ_GROUPING_PIXEL 2    /* dgq_calibrate_kmeans along the pixel dimension        */
+
+/* dgq_calibrate_kmeans `dimension` */
+#define DGQ_DIM_AUTO (-1)    /* d* = argmax_d D_d (Eq. 5)                                */
+#define DGQ_DIM_CHANNEL 0
+#define DGQ_DIM_PIXEL 1
+
 typedef struct dgq_groups_info {
     int32_t channels;            /* C                                               */
     int32_t act_bits;            /* 4 or 8                                          */
     int32_t group_size;          /* G                                               */
-    int32_t n_pixel_classes;     /* P as requested (1 or 2)                         */
+    int32_t n_pixel_classes;     /* P: as requested (grid), clusters found (pixel)  */
     int32_t n_groups;            /* NG                                              */
     int32_t k_padded;            /* K' = padded contraction length                  */
     int32_t n_outlier_channels;  /* size of the upper range cluster                 */
@@ -81,6 +94,8 @@ typedef struct dgq_groups_info {
     int32_t n_class1_rows;       /* calibration rows in the outlier pixel class     */
     float tau_pix;               /* row-range threshold (+inf: single class)        */
     double d_channel, d_pixel;   /* D_d of Section 3.3                              */
+    int32_t grouping;            /* DGQ_GROUPING_*                                  */
+    int32_t reserved;
 } dgq_groups_info_t;
 
 /*
@@ -104,6 +119,36 @@ int dgq_calibrate_groups(const float *x_cal, int64_t rows, int32_t channels,
                          int32_t n_pixel_classes, void *stream,
                          dgq_groups_t **out);
 
+/*
+ * Calibration of one layer exactly as Section 3.3 states it: ONE dimension is grouped.
+ *   1. D_channel and D_pixel (Eq. 4) from the per-channel and per-pixel maxima and minima
+ *      of the whole tensor; d* = argmax (Eq. 5; channel on a tie), or `dimension` if it
+ *      is not DGQ_DIM_AUTO
+ *   2. the vectors of d* (channels: a column of x_cal; pixels: a row) are clustered by
+ *      their range max - min into n_clusters groups by K-means, solved exactly (dynamic
+ *      programme over the sorted ranges; fewer clusters if there are fewer distinct ranges)
+ *   3. each group k: s_k = (max - min) / 2^act_bits (1 if max == min), z_k = min over the
+ *      calibration activations that belong to it (Eq. 6)
+ * Channel dimension: one pixel class, n_groups = clusters found, the channels of a
+ * group in (range, index) order, every group padded to DGQ_K_GRANULE positions (groups
+ * have whatever size the clustering gives them; group_size reads 0).
+ * Pixel dimension: one channel group (natural channel order), n_pixel_classes = clusters
+ * found (<= DGQ_MAX_PIXEL_CLASSES); at run time the class of a row is the number of
+ * thresholds below its range (dgq_groups_thresholds), i.e. the nearest cluster centre.
+ * One handle is one (layer, timestep) entry of the S, Z tables of Eq. 7: calibrate one
+ * per denoising step and pass the step's handle to the hot calls.
+ * 1 <= n_clusters <= DGQ_MAX_PIXEL_CLASSES.  Pixel dimension: rows <= 32768 (the host
+ * clustering takes O(n_clusters * rows^2) operations), else DGQ_EUNSUPPORTED.  Blocks.
+ * The handle works with dgq_pack_weight, dgq_quantize_act and dgq_linear as any other;
+ * dgq_linear_geglu and acc_dump need n_pixel_classes <= 2.
+ */
+int dgq_calibrate_kmeans(const float *x_cal, int64_t rows, int32_t channels,
+                         int32_t act_bits, int32_t n_clusters, int32_t dimension,
+                         void *stream, dgq_groups_t **out);
+
+/* Host copy of the n_pixel_classes - 1 ascending row-range thresholds (taus: host). */
+int dgq_groups_thresholds(const dgq_groups_t *g, float *taus);
+
 /* Host copy of the scalar results.  info: host. */
 int dgq_groups_info(const dgq_groups_t *g, dgq_groups_info_t *info);
 
@@ -112,7 +157,8 @@ int dgq_groups_info(const dgq_groups_t *g, dgq_groups_info_t *info);
  *   perm [K']   original channel at padded position j, -1 for padding
  *   goff [NG+1] first padded position of each group (multiples of the granule)
  *   glen [NG]   channels in each group
- *   s, z [2*NG] cell tables, class-major: s[p*NG + g]
+ *   s, z [max(P,2)*NG] cell tables, class-major: s[p*NG + g] (P = n_pixel_classes; with
+ *               P = 1 the second row repeats the first)
  */
 int dgq_groups_tables(const dgq_groups_t *g, int32_t *perm, int32_t *goff,
                       int32_t *glen, float *s, float *z);
@@ -145,7 +191,8 @@ void dgq_weight_free(dgq_weight_t *w);
 /*
  * Activation quantizer (linear quantizer of Section 3.1 with the cell
  * parameters of Section 3.3).  For every row r of x [rows, C]:
- *   class p = [max_c x - min_c x > tau_pix]                 (decided at run time)
+ *   class p = [max_c x - min_c x > tau_pix], in general the number of thresholds
+ *             below max_c x - min_c x                       (decided at run time)
  *   for every real padded position j in group g, c = perm[j]:
  *     q = clamp(rne((x[r,c] - z[p,g]) * (1/s[p,g])), 0, 2^b - 1)
  *     stored code = q - code_offset;  padding positions store 0.

@@ -30,7 +30,12 @@ class GroupsInfo(C.Structure):
                 ("n_pixel_classes", C.c_int32), ("n_groups", C.c_int32), ("k_padded", C.c_int32),
                 ("n_outlier_channels", C.c_int32), ("n_regular_groups", C.c_int32),
                 ("dstar", C.c_int32), ("code_offset", C.c_int32), ("n_class1_rows", C.c_int32),
-                ("tau_pix", C.c_float), ("d_channel", C.c_double), ("d_pixel", C.c_double)]
+                ("tau_pix", C.c_float), ("d_channel", C.c_double), ("d_pixel", C.c_double),
+                ("grouping", C.c_int32), ("reserved", C.c_int32)]
+
+
+DIM_AUTO, DIM_CHANNEL, DIM_PIXEL = -1, 0, 1
+GROUPING_GRID, GROUPING_CHANNEL, GROUPING_PIXEL = 0, 1, 2
 
 
 def lib():
@@ -44,6 +49,8 @@ def lib():
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         L.dgq_calibrate_groups.argtypes = [vp, i64, i32, i32, i32, i32, vp, C.POINTER(vp)]
+        L.dgq_calibrate_kmeans.argtypes = [vp, i64, i32, i32, i32, i32, vp, C.POINTER(vp)]
+        L.dgq_groups_thresholds.argtypes = [vp, vp]
         L.dgq_groups_info.argtypes = [vp, C.POINTER(GroupsInfo)]
         L.dgq_groups_tables.argtypes = [vp, vp, vp, vp, vp, vp]
         L.dgq_groups_free.argtypes = [vp]
@@ -103,11 +110,16 @@ class Groups:
         perm = np.empty(kp, np.int32)
         goff = np.empty(ng + 1, np.int32)
         glen = np.empty(ng, np.int32)
-        s = np.empty((2, ng), np.float32)
-        z = np.empty((2, ng), np.float32)
+        p = max(self.info.n_pixel_classes, 2)
+        s = np.empty((p, ng), np.float32)
+        z = np.empty((p, ng), np.float32)
         _check(lib().dgq_groups_tables(self.handle, perm.ctypes.data, goff.ctypes.data,
                                        glen.ctypes.data, s.ctypes.data, z.ctypes.data))
-        return dict(perm=perm, goff=goff, glen=glen, s=s, z=z)
+        taus = np.empty(max(self.info.n_pixel_classes - 1, 1), np.float32)
+        taus[:] = np.inf
+        _check(lib().dgq_groups_thresholds(self.handle, taus.ctypes.data))
+        return dict(perm=perm, goff=goff, glen=glen, s=s, z=z,
+                    taus=taus[:max(self.info.n_pixel_classes - 1, 0)])
 
     def free(self):
         if self.handle:
@@ -156,6 +168,19 @@ def dgq_calibrate_groups(x_cal, act_bits: int, group_size: int, n_pixel_classes:
     h = C.c_void_p()
     _check(lib().dgq_calibrate_groups(_ptr(x_cal), rows, ch, act_bits, group_size,
                                       n_pixel_classes, _stream(stream), C.byref(h)))
+    info = GroupsInfo()
+    _check(lib().dgq_groups_info(h, C.byref(info)))
+    return Groups(handle=h.value, info=info)
+
+
+def dgq_calibrate_kmeans(x_cal, act_bits: int, n_clusters: int, dimension: int = DIM_AUTO,
+                         stream=None) -> Groups:
+    import torch
+    _dev(x_cal, torch.float32, "x_cal")
+    rows, ch = x_cal.shape
+    h = C.c_void_p()
+    _check(lib().dgq_calibrate_kmeans(_ptr(x_cal), rows, ch, act_bits, n_clusters, dimension,
+                                      _stream(stream), C.byref(h)))
     info = GroupsInfo()
     _check(lib().dgq_groups_info(h, C.byref(info)))
     return Groups(handle=h.value, info=info)

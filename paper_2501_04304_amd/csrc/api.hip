@@ -119,6 +119,90 @@ Split split_two_clusters(const std::vector<float> &v) {
     return sp;
 }
 
+// Exact K-means of a 1-D sample (the grouping "by range using K-means" of
+// Section 3.3).  An optimal 1-D clustering is a partition of the sorted sample into
+// intervals, so the optimum over all partitions into k intervals is reached by a dynamic
+// programme: with running sums S, S2 of the sorted values and their squares (double,
+// sorted order, ties by index)
+//     cost(i, j) = (S2[j] - S2[i]) - (S[j] - S[i])^2 / (j - i)
+//     best[1][j] = cost(0, j),   best[k][j] = min_i best[k-1][i] + cost(i, j)
+// over cuts i between two distinct values, the first minimum winning; k is the smaller
+// of K and the number of distinct values.  The threshold between two neighbouring
+// clusters is the midpoint of their means, rounded to fp32 and clamped between the two
+// values it separates, so "number of thresholds below v" names v's cluster.  The order
+// of the floating-point operations is part of the definition, as in the two-cluster case.
+// Time O(K n^2): calibration is offline.
+struct Clusters {
+    std::vector<int64_t> bounds;  // cluster c = sorted positions [bounds[c], bounds[c+1])
+    std::vector<float> taus;      // bounds.size() - 2 thresholds, ascending
+    std::vector<int64_t> order;   // indices sorted by (value, index)
+};
+constexpr int64_t kMaxKMeansSamples = 32768;
+
+Clusters cluster_by_range(const std::vector<float> &v, int32_t K) {
+    Clusters cl;
+    const int64_t n = (int64_t)v.size();
+    cl.order.resize(n);
+    std::iota(cl.order.begin(), cl.order.end(), (int64_t)0);
+    std::sort(cl.order.begin(), cl.order.end(), [&](int64_t a, int64_t b) {
+        return v[a] < v[b] || (v[a] == v[b] && a < b);
+    });
+    std::vector<float> a(n);
+    for (int64_t i = 0; i < n; ++i) a[i] = v[cl.order[i]];
+    int64_t distinct = 1;
+    for (int64_t i = 1; i < n; ++i) distinct += a[i - 1] < a[i] ? 1 : 0;
+    const int32_t k_use = (int32_t)std::max<int64_t>(1, std::min<int64_t>(K, distinct));
+    std::vector<double> S(n + 1, 0.0), S2(n + 1, 0.0);
+    for (int64_t i = 0; i < n; ++i) {
+        const double x = a[i];
+        S[i + 1] = S[i] + x;
+        S2[i + 1] = S2[i] + x * x;
+    }
+    auto cost = [&](int64_t i, int64_t j) {
+        const double d = S[j] - S[i];
+        return (S2[j] - S2[i]) - (d * d) / (double)(j - i);
+    };
+    // layer k: best total cost of the first j values in k clusters and the cut that reaches it
+    std::vector<std::vector<double>> best(k_use + 1, std::vector<double>(n + 1, 0.0));
+    std::vector<std::vector<int64_t>> cut(k_use + 1, std::vector<int64_t>(n + 1, -1));
+    for (int64_t j = 1; j <= n; ++j) {
+        best[1][j] = cost(0, j);
+        cut[1][j] = 0;
+    }
+    for (int32_t k = 2; k <= k_use; ++k)
+        for (int64_t j = k; j <= n; ++j) {
+            int64_t arg = -1;
+            double bv = 0.0;
+            const std::vector<double> &prev = best[k - 1];
+            const std::vector<int64_t> &prev_cut = cut[k - 1];
+            for (int64_t i = k - 1; i < j; ++i) {
+                if (prev_cut[i] < 0 || !(a[i - 1] < a[i])) continue;
+                const double t = prev[i] + cost(i, j);
+                if (arg < 0 || t < bv) {
+                    bv = t;
+                    arg = i;
+                }
+            }
+            if (arg >= 0) {
+                best[k][j] = bv;
+                cut[k][j] = arg;
+            }
+        }
+    cl.bounds.assign(k_use + 1, 0);
+    cl.bounds[k_use] = n;
+    for (int32_t k = k_use; k >= 1; --k) cl.bounds[k - 1] = cut[k][cl.bounds[k]];
+    for (int32_t c = 0; c + 1 < k_use; ++c) {
+        const int64_t b0 = cl.bounds[c], b1 = cl.bounds[c + 1], b2 = cl.bounds[c + 2];
+        const double mean_lo = (S[b1] - S[b0]) / (double)(b1 - b0);
+        const double mean_hi = (S[b2] - S[b1]) / (double)(b2 - b1);
+        float tau = (float)(0.5 * (mean_lo + mean_hi));
+        tau = std::max(tau, a[b1 - 1]);
+        tau = std::min(tau, std::nextafterf(a[b1], -INFINITY));
+        cl.taus.push_back(tau);
+    }
+    return cl;
+}
+
 // D_d of Section 3.3 from the per-vector maxima and minima along one dimension.
 double variability(const std::vector<float> &vmax, const std::vector<float> &vmin) {
     const auto mx = std::minmax_element(vmax.begin(), vmax.end());
@@ -134,13 +218,46 @@ int upload(T **dst, const std::vector<T> &src) {
     return DGQ_OK;
 }
 
+// Device copies of a finished host description: per-chunk (z, 1/s) rows for the
+// quantizer, scale and offset rows and group boundaries for the contraction, thresholds.
+int upload_tables(Groups *g) {
+    const int32_t NG = (int32_t)g->glen.size();
+    const int32_t T = g->n_tab;
+    g->n_chunks = (int32_t)g->perm.size() / kGranule;
+    (void)hipGetDevice(&g->device);
+    std::vector<float> chunk_z((size_t)T * g->n_chunks), chunk_inv((size_t)T * g->n_chunks);
+    std::vector<float> zoff((size_t)T * NG);
+    std::vector<int32_t> gchunk(NG + 1);
+    for (int32_t k = 0; k <= NG; ++k) gchunk[k] = g->goff[k] / kGranule;
+    for (int p = 0; p < T; ++p)
+        for (int32_t k = 0; k < NG; ++k) {
+            for (int32_t ch = gchunk[k]; ch < gchunk[k + 1]; ++ch) {
+                chunk_z[(size_t)p * g->n_chunks + ch] = g->z[p * NG + k];
+                chunk_inv[(size_t)p * g->n_chunks + ch] = g->inv_s[p * NG + k];
+            }
+            zoff[(size_t)p * NG + k] =
+                (float)((double)g->z[p * NG + k] + (double)g->info.code_offset * (double)g->s[p * NG + k]);
+        }
+    int rc = upload(&g->d_perm, g->perm);
+    if (rc == DGQ_OK) rc = upload(&g->d_chunk_z, chunk_z);
+    if (rc == DGQ_OK) rc = upload(&g->d_chunk_inv, chunk_inv);
+    if (rc == DGQ_OK) rc = upload(&g->d_s, g->s);
+    if (rc == DGQ_OK) rc = upload(&g->d_z, g->z);
+    if (rc == DGQ_OK) rc = upload(&g->d_zoff, zoff);
+    if (rc == DGQ_OK) rc = upload(&g->d_taus, g->taus);
+    if (rc == DGQ_OK) rc = upload(&g->d_gchunk, gchunk);
+    return rc;
+}
+
 void release(Groups *g) {
     if (!g) return;
     (void)hipFree(g->d_perm);
     (void)hipFree(g->d_chunk_z);
     (void)hipFree(g->d_chunk_inv);
     (void)hipFree(g->d_s);
+    (void)hipFree(g->d_z);
     (void)hipFree(g->d_zoff);
+    (void)hipFree(g->d_taus);
     (void)hipFree(g->d_gchunk);
     delete g;
 }
@@ -295,25 +412,12 @@ int dgq_calibrate_groups(const float *x_cal, int64_t rows, int32_t channels, int
     in.tau_pix = tau;
     in.d_channel = d_channel;
     in.d_pixel = d_pixel;
-    g->n_chunks = Kp / kGranule;
-    (void)hipGetDevice(&g->device);
+    in.grouping = DGQ_GROUPING_GRID;
 
     // 6. device tables
-    std::vector<float> chunk_z(2 * (size_t)g->n_chunks), chunk_inv(2 * (size_t)g->n_chunks);
-    std::vector<int32_t> gchunk(NG + 1);
-    for (int32_t k = 0; k <= NG; ++k) gchunk[k] = g->goff[k] / kGranule;
-    for (int p = 0; p < 2; ++p)
-        for (int32_t k = 0; k < NG; ++k)
-            for (int32_t ch = gchunk[k]; ch < gchunk[k + 1]; ++ch) {
-                chunk_z[(size_t)p * g->n_chunks + ch] = g->z[p * NG + k];
-                chunk_inv[(size_t)p * g->n_chunks + ch] = g->inv_s[p * NG + k];
-            }
-    int rc = upload(&g->d_perm, g->perm);
-    if (rc == DGQ_OK) rc = upload(&g->d_chunk_z, chunk_z);
-    if (rc == DGQ_OK) rc = upload(&g->d_chunk_inv, chunk_inv);
-    if (rc == DGQ_OK) rc = upload(&g->d_s, g->s);
-    if (rc == DGQ_OK) rc = upload(&g->d_zoff, g->z);
-    if (rc == DGQ_OK) rc = upload(&g->d_gchunk, gchunk);
+    g->n_tab = 2;
+    g->taus.assign(1, tau);
+    const int rc = upload_tables(g);
     if (rc != DGQ_OK) {
         release(g);
         return rc;
@@ -325,6 +429,150 @@ int dgq_calibrate_groups(const float *x_cal, int64_t rows, int32_t channels, int
 int dgq_groups_info(const dgq_groups_t *h, dgq_groups_info_t *info) {
     if (!h || !info) return fail(DGQ_EINVAL, "dgq_groups_info: null pointer");
     *info = reinterpret_cast<const Groups *>(h)->info;
+    return DGQ_OK;
+}
+
+int dgq_calibrate_kmeans(const float *x_cal, int64_t rows, int32_t channels, int32_t act_bits,
+                         int32_t n_clusters, int32_t dimension, void *stream, dgq_groups_t **out) {
+    if (!x_cal || !out) return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: null pointer");
+    *out = nullptr;
+    if (rows < 1 || channels < 1) return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: empty tensor");
+    if (act_bits != 4 && act_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: act_bits must be 4 or 8");
+    if (n_clusters < 1 || n_clusters > kMaxClasses)
+        return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: n_clusters must be 1..16");
+    if (dimension < DGQ_DIM_AUTO || dimension > DGQ_DIM_PIXEL)
+        return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: dimension must be DGQ_DIM_AUTO, _CHANNEL or _PIXEL");
+    if (!aligned16(x_cal)) return fail(DGQ_EALIGN, "dgq_calibrate_kmeans: x_cal not 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t C = channels;
+
+    // ranges of the vectors of both dimensions (Eq. 4): per pixel over its channels, per
+    // channel over all pixels
+    DevBuf d_rmx, d_rmn, d_part;
+    DGQ_HIP(d_rmx.alloc(sizeof(float) * rows));
+    DGQ_HIP(d_rmn.alloc(sizeof(float) * rows));
+    DGQ_HIP(launch_row_minmax(x_cal, rows, C, d_rmx.as<float>(), d_rmn.as<float>(), st));
+    const int32_t slabs = (int32_t)std::min<int64_t>(rows, 256);
+    DGQ_HIP(d_part.alloc(sizeof(float) * (size_t)slabs * 4 * C));
+    DGQ_HIP(launch_col_minmax_by_class(x_cal, rows, C, d_rmx.as<float>(), d_rmn.as<float>(),
+                                       INFINITY, slabs, d_part.as<float>(), st));  // one class
+    std::vector<float> rmx(rows), rmn(rows), part((size_t)slabs * 4 * C);
+    DGQ_HIP(hipMemcpyAsync(rmx.data(), d_rmx.p, sizeof(float) * rows, hipMemcpyDeviceToHost, st));
+    DGQ_HIP(hipMemcpyAsync(rmn.data(), d_rmn.p, sizeof(float) * rows, hipMemcpyDeviceToHost, st));
+    DGQ_HIP(hipMemcpyAsync(part.data(), d_part.p, sizeof(float) * part.size(), hipMemcpyDeviceToHost, st));
+    DGQ_HIP(hipStreamSynchronize(st));
+    std::vector<float> cmx(C, -INFINITY), cmn(C, INFINITY);
+    for (int32_t sl = 0; sl < slabs; ++sl) {
+        const float *pp = part.data() + (size_t)sl * 4 * C;
+        for (int32_t c = 0; c < C; ++c) {
+            cmx[c] = std::max(cmx[c], pp[c]);
+            cmn[c] = std::min(cmn[c], pp[C + c]);
+        }
+    }
+    const double d_channel = variability(cmx, cmn);
+    const double d_pixel = variability(rmx, rmn);
+    const int32_t dstar = d_pixel > d_channel ? 1 : 0;  // Eq. 5
+    const int32_t dim = dimension == DGQ_DIM_AUTO ? dstar : dimension;
+    if (dim == DGQ_DIM_PIXEL && rows > kMaxKMeansSamples)
+        return fail(DGQ_EUNSUPPORTED,
+                    "dgq_calibrate_kmeans: the exact clustering of pixels takes at most 32768 calibration rows");
+
+    Groups *g = new (std::nothrow) Groups();
+    if (!g) return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: out of host memory");
+    const float levels = (float)(1 << act_bits);
+    auto cell = [&](float mx, float mn, int32_t at) {  // Eq. 6
+        const float sc = mx > mn ? (mx - mn) / levels : 1.0f;
+        g->s[at] = sc;
+        g->z[at] = mn;
+        g->inv_s[at] = 1.0f / sc;
+    };
+    int32_t P = 1, n_upper = 0;
+    g->goff.push_back(0);
+    if (dim == DGQ_DIM_CHANNEL) {
+        std::vector<float> cw(C);
+        for (int32_t c = 0; c < C; ++c) cw[c] = cmx[c] - cmn[c];
+        const Clusters cl = cluster_by_range(cw, n_clusters);
+        const int32_t NG = (int32_t)cl.bounds.size() - 1;
+        g->n_tab = 2;  // a second, identical class row: the kernels always see two
+        g->s.assign(2 * NG, 1.0f);
+        g->z.assign(2 * NG, 0.0f);
+        g->inv_s.assign(2 * NG, 1.0f);
+        for (int32_t k = 0; k < NG; ++k) {
+            const int32_t len = (int32_t)(cl.bounds[k + 1] - cl.bounds[k]);
+            const int32_t padded = (len + kGranule - 1) / kGranule * kGranule;
+            float mx = -INFINITY, mn = INFINITY;
+            for (int32_t j = 0; j < padded; ++j) {
+                const int32_t c = j < len ? (int32_t)cl.order[cl.bounds[k] + j] : -1;
+                g->perm.push_back(c);
+                if (c >= 0) {
+                    mx = std::max(mx, cmx[c]);
+                    mn = std::min(mn, cmn[c]);
+                }
+            }
+            g->glen.push_back(len);
+            g->goff.push_back((int32_t)g->perm.size());
+            cell(mx, mn, k);
+            cell(mx, mn, NG + k);
+        }
+        g->taus.assign(1, INFINITY);
+    } else {
+        std::vector<float> width(rows);
+        for (int64_t r = 0; r < rows; ++r) width[r] = rmx[r] - rmn[r];
+        const Clusters cl = cluster_by_range(width, n_clusters);
+        P = (int32_t)cl.bounds.size() - 1;
+        const int32_t padded = (C + kGranule - 1) / kGranule * kGranule;
+        for (int32_t j = 0; j < padded; ++j) g->perm.push_back(j < C ? j : -1);
+        g->glen.push_back(C);
+        g->goff.push_back(padded);
+        g->n_tab = std::max(P, 2);
+        g->s.assign(g->n_tab, 1.0f);
+        g->z.assign(g->n_tab, 0.0f);
+        g->inv_s.assign(g->n_tab, 1.0f);
+        g->taus = cl.taus;
+        if (g->taus.empty()) g->taus.assign(1, INFINITY);
+        for (int32_t p = 0; p < P; ++p) {
+            float mx = -INFINITY, mn = INFINITY;
+            for (int64_t i = cl.bounds[p]; i < cl.bounds[p + 1]; ++i) {
+                mx = std::max(mx, rmx[cl.order[i]]);
+                mn = std::min(mn, rmn[cl.order[i]]);
+            }
+            cell(mx, mn, p);
+            if (P == 1) cell(mx, mn, 1);
+        }
+        n_upper = (int32_t)(rows - cl.bounds[1]);
+    }
+
+    dgq_groups_info_t &in = g->info;
+    in.channels = C;
+    in.act_bits = act_bits;
+    in.group_size = 0;
+    in.n_pixel_classes = P;
+    in.n_groups = (int32_t)g->glen.size();
+    in.k_padded = (int32_t)g->perm.size();
+    in.n_outlier_channels = 0;
+    in.n_regular_groups = 0;
+    in.dstar = dstar;
+    in.code_offset = act_bits == 8 ? 128 : 0;
+    in.n_class1_rows = n_upper;
+    in.tau_pix = g->taus[0];
+    in.d_channel = d_channel;
+    in.d_pixel = d_pixel;
+    in.grouping = dim == DGQ_DIM_CHANNEL ? DGQ_GROUPING_CHANNEL : DGQ_GROUPING_PIXEL;
+    const int rc = upload_tables(g);
+    if (rc != DGQ_OK) {
+        release(g);
+        return rc;
+    }
+    *out = reinterpret_cast<dgq_groups_t *>(g);
+    return DGQ_OK;
+}
+
+int dgq_groups_thresholds(const dgq_groups_t *h, float *taus) {
+    if (!h || !taus) return fail(DGQ_EINVAL, "dgq_groups_thresholds: null pointer");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    const int32_t n = std::max(g->info.n_pixel_classes - 1, 0);
+    for (int32_t k = 0; k < n; ++k) taus[k] = g->taus[k];
     return DGQ_OK;
 }
 
@@ -371,8 +619,8 @@ int dgq_pack_weight(const dgq_groups_t *h, const float *w, const float *bias, in
         e = hipMalloc(reinterpret_cast<void **>(&wt->d_zb), sizeof(float) * 2 * wt->O_pad);
     if (e == hipSuccess)
         e = launch_pack_weight(w, bias, wt->O, wt->O_pad, wt->C, wt->Kp, g->info.n_groups, w_bits,
-                               g->info.code_offset, g->d_perm, g->d_gchunk, g->d_s, g->d_zoff,
-                               wt->d_wq, wt->d_sw, wt->d_zb, st);
+                               g->info.code_offset, g->d_perm, g->d_gchunk, g->d_s, g->d_z,
+                               g->n_tab, wt->d_wq, wt->d_sw, wt->d_zb, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) {
         release(wt);
@@ -413,7 +661,8 @@ int dgq_quantize_act(const dgq_groups_t *h, const float *x, int64_t rows, int8_t
         return fail(DGQ_EALIGN, "dgq_quantize_act: tensor not 16-byte aligned");
     const Groups *g = reinterpret_cast<const Groups *>(h);
     // LDS: four fp32 rows + 32-bit offset table + keep masks + per-chunk tables
-    if ((size_t)g->info.channels * 16 + (size_t)g->info.k_padded * 5 + (size_t)g->n_chunks * 16 + 16 >
+    if ((size_t)g->info.channels * 16 + (size_t)g->info.k_padded * 5 +
+            (size_t)(g->n_chunks + 8) * 8 * g->n_tab + 1300 >
         160 * 1024)
         return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act: too many channels for the LDS row buffers (about 7500)");
     DGQ_HIP(launch_quantize_act(*g, x, rows, codes, row_class, static_cast<hipStream_t>(stream)));
@@ -444,6 +693,8 @@ int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *code
         return fail(DGQ_EALIGN, "dgq_linear: tensor not 16-byte aligned");
     if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
         return fail(DGQ_EUNSUPPORTED, "dgq_linear: too many output tiles");
+    if (g->n_tab > 2 && acc_dump)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear: acc_dump needs at most two pixel classes");
     DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump, false,
                           static_cast<hipStream_t>(stream)));
     return DGQ_OK;
@@ -462,6 +713,8 @@ int dgq_linear_geglu(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t
         return fail(DGQ_EUNSUPPORTED,
                     "dgq_linear_geglu: out_channels must be a multiple of 256 (value and gate "
                     "halves in whole 128-channel tiles)");
+    if (g->n_tab > 2)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear_geglu: needs at most two pixel classes");
     if (!aligned16(codes) || !aligned16(y))
         return fail(DGQ_EALIGN, "dgq_linear_geglu: tensor not 16-byte aligned");
     if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)

@@ -13,6 +13,7 @@ namespace dgq {
 
 constexpr int kGranule = DGQ_K_GRANULE;  // positions per K chunk
 constexpr int kTileO = 256;              // weights are padded to a multiple of every GEMM tile width
+constexpr int kMaxClasses = DGQ_MAX_PIXEL_CLASSES;
 
 // ---- block-tiled operand layout shared by the quantizer, the weight packer and the
 // GEMM.  A block is 1 KiB = one 64-position chunk of 16 rows (64 B per row: int8
@@ -41,13 +42,17 @@ struct Groups {
     int32_t n_chunks = 0;  // K' / kGranule
     // host copies
     std::vector<int32_t> perm, goff, glen;
-    std::vector<float> s, z, inv_s;  // [2][NG]
+    int32_t n_tab = 2;               // class rows in the tables: 2, or P when P > 2
+    std::vector<float> s, z, inv_s;  // [n_tab][NG]
+    std::vector<float> taus;         // [n_tab - 1] ascending row-range thresholds; +inf = unused
     // device tables
     int32_t *d_perm = nullptr;     // [K'] original channel or -1
-    float *d_chunk_z = nullptr;    // [2][n_chunks]  offset of the chunk's group
-    float *d_chunk_inv = nullptr;  // [2][n_chunks]  1/s of the chunk's group
-    float *d_s = nullptr;          // [2][NG]
-    float *d_zoff = nullptr;       // [2][NG]  z + code_offset * s (double -> fp32 not used; see pack)
+    float *d_chunk_z = nullptr;    // [n_tab][n_chunks]  offset of the chunk's group
+    float *d_chunk_inv = nullptr;  // [n_tab][n_chunks]  1/s of the chunk's group
+    float *d_s = nullptr;          // [n_tab][NG]
+    float *d_z = nullptr;          // [n_tab][NG]
+    float *d_zoff = nullptr;       // [n_tab][NG]  z + code_offset * s
+    float *d_taus = nullptr;       // [n_tab - 1]
     int32_t *d_gchunk = nullptr;   // [NG+1] first chunk of each group
     int device = 0;
 };
@@ -57,7 +62,9 @@ struct Weight {
     int32_t O = 0, O_pad = 0, C = 0, Kp = 0, w_bits = 8;
     int8_t *d_wq = nullptr;  // [O_pad x K'] permuted + padded rows, block-tiled (64 B per row)
     float *d_sw = nullptr;   // [O_pad]
-    float *d_zb = nullptr;   // [2][O_pad]
+    // [2][O_pad].  Two class rows: zb[p][o].  More than two classes (one channel group):
+    // row 0 = sw[o] * sum_j wq[o,j], row 1 = bias[o]; zb[p][o] = zoff[p] * row 0 + row 1.
+    float *d_zb = nullptr;
     int device = 0;
 };
 
@@ -91,7 +98,7 @@ hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int3
                               int32_t C, int32_t Kp, int32_t NG, int32_t w_bits,
                               int32_t code_offset, const int32_t *perm,
                               const int32_t *gchunk, const float *s, const float *z,
-                              int8_t *wq, float *sw, float *zb, hipStream_t st);
+                              int32_t n_classes, int8_t *wq, float *sw, float *zb, hipStream_t st);
 
 // Inverse of the K' layout: wq_out [O][C] original order.
 hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t Kp,

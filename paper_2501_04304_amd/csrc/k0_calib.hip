@@ -83,8 +83,8 @@ __global__ __launch_bounds__(256) void k_pack_weight(
     const float *__restrict__ w, const float *__restrict__ bias, int32_t O, int32_t C,
     int32_t Kp, int32_t NG, int32_t w_bits, int32_t code_offset,
     const int32_t *__restrict__ perm, const int32_t *__restrict__ gchunk,
-    const float *__restrict__ s, const float *__restrict__ z, int8_t *__restrict__ wq,
-    float *__restrict__ sw, float *__restrict__ zb, int32_t O_pad) {
+    const float *__restrict__ s, const float *__restrict__ z, int32_t n_classes,
+    int8_t *__restrict__ wq, float *__restrict__ sw, float *__restrict__ zb, int32_t O_pad) {
     extern __shared__ int32_t smem[];
     int32_t *gsum = smem;
     int32_t *chunk2grp = smem + NG;
@@ -133,7 +133,16 @@ __global__ __launch_bounds__(256) void k_pack_weight(
         at(j) = (int8_t)v;
     }
     __syncthreads();
-    if (tid < 2) {
+    if (n_classes > 2) {
+        // more than two pixel classes come with a single channel group: the class enters
+        // the zero-point term as one factor, zb[p][o] = zoff[p] * (sw[o] * wsum[o]) + bias[o],
+        // and the two class-independent rows are stored instead of one row per class
+        if (tid == 0) {
+            zb[o] = (float)((double)sc * (double)gsum[0]);
+            zb[O_pad + o] = bias ? bias[o] : 0.0f;
+            sw[o] = sc;
+        }
+    } else if (tid < 2) {
         const int p = tid;
         double t = 0.0;
         for (int32_t g = 0; g < NG; ++g) {
@@ -182,11 +191,11 @@ hipError_t launch_col_minmax_by_class(const float *x, int64_t rows, int32_t C, c
 hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int32_t O_pad,
                               int32_t C, int32_t Kp, int32_t NG, int32_t w_bits,
                               int32_t code_offset, const int32_t *perm, const int32_t *gchunk,
-                              const float *s, const float *z, int8_t *wq, float *sw, float *zb,
-                              hipStream_t st) {
+                              const float *s, const float *z, int32_t n_classes, int8_t *wq,
+                              float *sw, float *zb, hipStream_t st) {
     const size_t lds = sizeof(int32_t) * (size_t)(NG + Kp / kGranule);
     hipLaunchKernelGGL(k_pack_weight, dim3(O_pad), dim3(256), lds, st, w, bias, O, C, Kp, NG,
-                       w_bits, code_offset, perm, gchunk, s, z, wq, sw, zb, O_pad);
+                       w_bits, code_offset, perm, gchunk, s, z, n_classes, wq, sw, zb, O_pad);
     return hipGetLastError();
 }
 

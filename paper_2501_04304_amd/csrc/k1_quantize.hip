@@ -88,14 +88,14 @@ __device__ inline float quant_pre(float x, float z, float inv_s) {
 }
 
 // LDS: [off32: kPer u32 per output dword][keep: one u32 per output dword]
-//      [cz: 2 classes x chunks float2][rows: 4 * C floats].
+//      [cz: classes x chunks float2][rows: 4 * C floats].
 // The tables are padded to whole steps of 64 output dwords (a step is what the 64 lanes
 // do at once), so a lane of the last, partly filled step reads valid table entries
 // (offset 0, keep-mask 0) and only its store is predicated.
 struct QuantLds {
     int32_t n_dw, n_steps, n_dw_pad, nch_pad;
     size_t off_bytes, keep_bytes, cz_bytes;
-    __host__ __device__ QuantLds(int32_t Kp, int bits) {
+    __host__ __device__ QuantLds(int32_t Kp, int bits, int classes) {
         const int per = bits == 8 ? 4 : 8;
         n_dw = Kp / per;
         n_steps = (n_dw + 63) >> 6;
@@ -103,7 +103,7 @@ struct QuantLds {
         nch_pad = n_dw_pad / (64 / per);
         off_bytes = (size_t)n_dw_pad * per * 4;
         keep_bytes = (size_t)n_dw_pad * 4;
-        cz_bytes = (size_t)2 * nch_pad * 8;
+        cz_bytes = (size_t)classes * nch_pad * 8;
     }
     __host__ __device__ size_t table_bytes() const { return off_bytes + keep_bytes + cz_bytes; }
 };
@@ -113,13 +113,13 @@ template <int BITS, int NV>
 __global__ __launch_bounds__(256) void k_quantize_act(
     const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
-    const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
-    uint8_t *__restrict__ row_class, int32_t rpw_log2) {
+    const float *__restrict__ chunk_inv, const float *__restrict__ taus, int32_t n_tau,
+    int8_t *__restrict__ codes, uint8_t *__restrict__ row_class, int32_t rpw_log2) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     constexpr int kPer = BITS == 8 ? 4 : 8;          // positions per output dword
     constexpr int kDwPerChunk = 64 / kPer;           // 16 or 8
     constexpr int kChunkStep = kWave / kDwPerChunk;  // chunks per step: 4 or 8
-    const QuantLds L(Kp, BITS);
+    const QuantLds L(Kp, BITS, n_tau + 1);
     uint32_t *off32 = reinterpret_cast<uint32_t *>(lds_raw);
     uint32_t *keep = reinterpret_cast<uint32_t *>(lds_raw + L.off_bytes);
     float2 *cz = reinterpret_cast<float2 *>(lds_raw + L.off_bytes + L.keep_bytes);
@@ -181,8 +181,8 @@ __global__ __launch_bounds__(256) void k_quantize_act(
         }
         keep[d] = m;
     }
-    for (int32_t i = tid; i < 2 * L.nch_pad; i += 256) {
-        const int32_t p = i >= L.nch_pad, ch = i - p * L.nch_pad;
+    for (int32_t i = tid; i < (n_tau + 1) * L.nch_pad; i += 256) {
+        const int32_t p = i / L.nch_pad, ch = i - p * L.nch_pad;
         cz[i] = ch < n_chunks ? make_float2(chunk_z[p * n_chunks + ch], chunk_inv[p * n_chunks + ch])
                               : make_float2(0.0f, 0.0f);
     }
@@ -198,6 +198,9 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     const uint32_t slot_lane = BITS == 8 ? (lane >> 2) & 3 : (lane >> 2) & 1;  // 16-byte slot
     const uint32_t out_lane = (uint32_t)(lane / kDwPerChunk) * 1024u + (lane & 3) * 4u;
     const char *xsb = reinterpret_cast<const char *>(xs);
+    // lane k holds threshold k: the class of a row is the number of thresholds below its
+    // range (the nearest cluster centre), counted with one compare and a mask population count
+    const float tau_lane = lane < n_tau ? taus[lane] : INFINITY;
 
     while (true) {
         // the sequence ends at the first unit index past the end; rows inside the last
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(256) void k_quantize_act(
             }
             if (r_next < rows) fetch(r_next);  // in flight while this row is quantized
             wave_max_min(mx, mn);
-            const int p = __builtin_amdgcn_readfirstlane(__fsub_rn(mx, mn) > tau ? 1 : 0);
+            const int p = __builtin_popcountll(__ballot(__fsub_rn(mx, mn) > tau_lane));
             if (lane == 0) row_class[r] = (uint8_t)p;
             const char *cz_lane = reinterpret_cast<const char *>(cz + p * L.nch_pad + lane / kDwPerChunk);
             // The LDS slice is private to this wave and a wave's LDS operations complete
@@ -301,14 +304,16 @@ template <int BITS>
 __global__ __launch_bounds__(256) void k_quantize_act_any(
     const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
-    const float *__restrict__ chunk_inv, float tau, int8_t *__restrict__ codes,
-    uint8_t *__restrict__ row_class, int32_t /*rpw_log2: unused, one row per wave*/) {
+    const float *__restrict__ chunk_inv, const float *__restrict__ taus, int32_t n_tau,
+    int8_t *__restrict__ codes, uint8_t *__restrict__ row_class,
+    int32_t /*rpw_log2: unused, one row per wave*/) {
     extern __shared__ float lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     float *xs = lds + (size_t)wave * C;
     constexpr float qmax = (float)((1 << BITS) - 1);
     constexpr int kOff = BITS == 8 ? 128 : 0;
     constexpr int kPer = BITS == 8 ? 4 : 8;  // positions per output dword
+    const float tau_lane = lane < n_tau ? taus[lane] : INFINITY;
 
     for (int64_t r = (int64_t)blockIdx.x * kWavesPerBlock + wave; r < rows;
          r += (int64_t)gridDim.x * kWavesPerBlock) {
@@ -321,7 +326,7 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
             mn = fminf(v, mn);
         }
         wave_max_min(mx, mn);
-        const int p = __fsub_rn(mx, mn) > tau ? 1 : 0;
+        const int p = __builtin_popcountll(__ballot(__fsub_rn(mx, mn) > tau_lane));
         if (lane == 0) row_class[r] = (uint8_t)p;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -349,7 +354,8 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
 }
 
 using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const int32_t *,
-                      const float *, const float *, float, int8_t *, uint8_t *, int32_t);
+                      const float *, const float *, const float *, int32_t, int8_t *, uint8_t *,
+                      int32_t);
 
 // NV = float4 loads per lane per row; exact for the usual channel counts (320 .. 5120).
 template <int BITS>
@@ -376,7 +382,8 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     int32_t rpw_log2 = 2;
     if (vec4) {
         kern = g.info.act_bits == 8 ? pick_vec<8>(C) : pick_vec<4>(C);
-        lds = QuantLds(Kp, g.info.act_bits).table_bytes() + sizeof(float) * (size_t)C * kWavesPerBlock;
+        lds = QuantLds(Kp, g.info.act_bits, g.n_tab).table_bytes() +
+              sizeof(float) * (size_t)C * kWavesPerBlock;
         blocks = (rows + 15) / 16;
         if (blocks < 256) {  // fewer 16-row blocks than CUs: quarter blocks, one row per wave
             rpw_log2 = 0;
@@ -399,7 +406,7 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, st, x, rows, C, Kp,
-                       g.n_chunks, g.d_perm, g.d_chunk_z, g.d_chunk_inv, g.info.tau_pix, codes,
+                       g.n_chunks, g.d_perm, g.d_chunk_z, g.d_chunk_inv, g.d_taus, g.n_tab - 1, codes,
                        row_class, rpw_log2);
     return hipGetLastError();
 }

@@ -125,11 +125,18 @@ struct Cfg {
 // O/2 + o0/2 .. of the same output channels; the epilogue writes value * GELU(gate) into
 // y [rows, O/2] (the gated feed-forward of the transformer blocks), so the 2x wider
 // pre-activation never reaches memory.  Needs BO == 2 and O % (2 TO) == 0.
-template <class CF, bool DUMP, bool GEGLU>
+//
+// MULTI: more than two pixel classes and ONE channel group (the pixel-dimension grouping
+// of Section 3.3).  The class of the row behind every accumulator register travels as a
+// 4-bit field; the single fold and the epilogue read that class's scale and offset from a
+// small LDS table, and the zero-point term is zoff[class] * (sw[o] * wsum[o]) + bias[o],
+// whose two class-independent rows arrive in place of zb[0] and zb[1].
+template <class CF, bool DUMP, bool GEGLU, bool MULTI>
 __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int8_t *__restrict__ codes, const uint8_t *__restrict__ row_class,
     const int8_t *__restrict__ wq, const float *__restrict__ sw, const float *__restrict__ zb,
-    const float *__restrict__ s_tab, const int32_t *__restrict__ gchunk, int64_t rows, int32_t O,
+    const float *__restrict__ s_tab, const float *__restrict__ zoff_tab, int32_t P,
+    const int32_t *__restrict__ gchunk, int64_t rows, int32_t O,
     int32_t O_pad, int32_t Kp, int32_t NG, int32_t tiles_r, int32_t tiles_o, int32_t per_xcd,
     int32_t super_rows, float *__restrict__ y, int32_t *__restrict__ acc_dump) {
     constexpr int ABITS = CF::ABITS, BR = CF::BR, BO = CF::BO, STAGES = CF::STAGES;
@@ -225,7 +232,9 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     }
     const int32_t tg = tid < NG ? tid : NG - 1;
     const int32_t t_end = gchunk[tg + 1];
-    const float t_s0 = s_tab[tg], t_s1 = s_tab[NG + tg];
+    // MULTI: thread t < P carries class t's scale and offset
+    const int32_t tp = tid < P ? tid : P - 1;
+    const float t_s0 = MULTI ? s_tab[tp] : s_tab[tg], t_s1 = MULTI ? zoff_tab[tp] : s_tab[NG + tg];
 
     // ---- fragment read offsets (per lane, per k-step) ---------------------------------
     int a_off[2], b_off[2];
@@ -301,12 +310,18 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     // the main loop, so its LDS waits can be partial (LDS returns in order).
     int32_t *tab_end = reinterpret_cast<int32_t *>(lds + STAGES * CF::STAGE_BYTES);
     float *tab_s = reinterpret_cast<float *>(tab_end + NG);
-    if (tid < NG) {
+    if (MULTI) {  // tab_s = [s[0..P) | zoff[0..P)], one group
+        if (tid == 0) tab_end[0] = t_end;
+        if (tid < P) {
+            tab_s[tid] = t_s0;
+            tab_s[P + tid] = t_s1;
+        }
+    } else if (tid < NG) {
         tab_end[tid] = t_end;
         tab_s[tid] = t_s0;
         tab_s[NG + tid] = t_s1;
     }
-    for (int32_t i = tid + CF::THREADS; i < NG; i += CF::THREADS) {  // more groups than threads
+    for (int32_t i = tid + CF::THREADS; !MULTI && i < NG; i += CF::THREADS) {  // more groups than threads
         tab_end[i] = gchunk[i + 1];
         tab_s[i] = s_tab[i];
         tab_s[NG + i] = s_tab[NG + i];
@@ -337,7 +352,30 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             }
         }
     }
-    const bool mixed = any1 && !all1;  // wave-uniform
+    bool mixed = any1 && !all1;  // wave-uniform
+    // MULTI: 4-bit class of the row behind accumulator register i in clsn[a][i / 8]; rows
+    // past the end carry the last row's class (their results are never stored)
+    uint32_t clsn[BR][2];
+    int32_t c_first = 0;
+    if constexpr (MULTI) {
+        c_first = __builtin_amdgcn_readfirstlane((int32_t)row_c1[0]);
+        bool same = true;
+#pragma unroll
+        for (int a = 0; a < BR; ++a) {
+            same = same && __ballot((int32_t)row_c1[a] != c_first) == 0;
+            clsn[a][0] = clsn[a][1] = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = 8 * (i >> 2) + 4 * kh + (i & 3);
+                const uint32_t c = (uint32_t)__shfl((int32_t)row_c1[a], m, 64) & 15u;
+                clsn[a][i >> 3] |= c << (4 * (i & 7));
+            }
+            // opaque from here on: otherwise the sixteen unpacked values are kept (and
+            // spilled) across the loop instead of these two registers
+            asm volatile("" : "+v"(clsn[a][0]), "+v"(clsn[a][1]));
+        }
+        mixed = !same;
+    }
 
 
     // ---- wait for chunk 0 and for everyone's table entries ---------------------------------
@@ -353,6 +391,27 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     auto epilogue = [&](auto mixed_tag, const int32_t p) {
         constexpr bool MIXED = decltype(mixed_tag)::value;
         // ---- epilogue: y = sw[o] * sum + zb[class][o], in place -------------------------
+        if constexpr (MULTI) {
+            // zb[class][o] = zoff[class] * (sw[o] * wsum[o]) + bias[o]; one table read per
+            // row register, used for both column blocks, four registers at a time
+#pragma unroll
+            for (int a = 0; a < BR; ++a)
+#pragma unroll
+                for (int i0 = 0; i0 < 16; i0 += 4) {
+                    float zo[4];
+#pragma unroll
+                    for (int i = i0; i < i0 + 4; ++i) {
+                        const int32_t c = MIXED ? (int32_t)((clsn[a][i >> 3] >> (4 * (i & 7))) & 15u) : p;
+                        zo[i - i0] = tab_s[P + c];
+                    }
+#pragma unroll
+                    for (int i = i0; i < i0 + 4; ++i)
+#pragma unroll
+                        for (int b = 0; b < BO; ++b)
+                            facc[a][b][i] = fmaf(col_sw[b], facc[a][b][i], fmaf(zo[i - i0], col_zb0[b], col_zb1[b]));
+                    asm volatile("" ::: "memory");  // keep the next four reads behind these
+                }
+        } else {
 #pragma unroll
         for (int b = 0; b < BO; ++b) {
             const float swo = col_sw[b];
@@ -368,6 +427,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                         zz = p ? zb1 : zb0;
                     facc[a][b][i] = fmaf(swo, facc[a][b][i], zz);
                 }
+        }
         }
         if constexpr (GEGLU) {
             // block 0 holds the value, block 1 the gate of the same output channel:
@@ -451,10 +511,11 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     // The loop and the epilogue, instantiated for uniform-class and mixed-class waves.
     auto run = [&](auto mixed_tag) {
         constexpr bool MIXED = decltype(mixed_tag)::value;
-        const int32_t p = (!MIXED && any1) ? 1 : 0;  // the wave's class when it is uniform
+        // the wave's class when it is uniform
+        const int32_t p = MULTI ? (MIXED ? 0 : c_first) : ((!MIXED && any1) ? 1 : 0);
         v4i af0[BR], bf0[BO], af1[BR], bf1[BO];
         load_frags(lds, 0, af0, bf0);
-        const float *s_p = tab_s + p * NG;
+        const float *s_p = tab_s + p * NG;  // MULTI: NG == 1, so s_p[0] is class p's scale
         int32_t g = 0;
         int32_t g_end = __builtin_amdgcn_readfirstlane(tab_end[0]);
         bool fresh = true;
@@ -504,6 +565,22 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
 #pragma unroll
                             for (int i = 0; i < 16; ++i)
                                 facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
+                } else if (MULTI) {
+#pragma unroll
+                    for (int a = 0; a < BR; ++a)
+#pragma unroll
+                        for (int i0 = 0; i0 < 16; i0 += 4) {
+                            float sg[4];
+#pragma unroll
+                            for (int i = i0; i < i0 + 4; ++i)
+                                sg[i - i0] = tab_s[(clsn[a][i >> 3] >> (4 * (i & 7))) & 15u];
+#pragma unroll
+                            for (int i = i0; i < i0 + 4; ++i)
+#pragma unroll
+                                for (int b = 0; b < BO; ++b)
+                                    facc[a][b][i] = fmaf((float)acc[a][b][i], sg[i - i0], facc[a][b][i]);
+                            asm volatile("" ::: "memory");
+                        }
                 } else {
                     const float s0 = tab_s[g], s1 = tab_s[NG + g];
 #pragma unroll
@@ -558,7 +635,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         run(std::false_type{});
 }
 
-template <class CF, bool DUMP, bool GEGLU = false>
+template <class CF, bool DUMP, bool GEGLU = false, bool MULTI = false>
 hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
                       const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
                       hipStream_t st) {
@@ -567,9 +644,11 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     const int64_t T = (int64_t)tiles_r * tiles_o;
     const int32_t per_xcd = (int32_t)((T + 7) / 8);
     const dim3 grid((unsigned)(per_xcd * 8));
-    size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES + 12 * (size_t)g.info.n_groups;
+    size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES +
+                 (MULTI ? 4 + 8 * (size_t)g.n_tab : 12 * (size_t)g.info.n_groups);
     static_assert(!GEGLU || CF::BO == 2, "the gated epilogue pairs the two blocks of a wave");
-    auto kern = k_linear<CF, DUMP, GEGLU>;
+    static_assert(!(GEGLU && MULTI), "the gated epilogue is built for at most two pixel classes");
+    auto kern = k_linear<CF, DUMP, GEGLU, MULTI>;
     {
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kStageBudget);
         if (e != hipSuccess) return e;
@@ -588,7 +667,8 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     if (tiles_o >= 32) super_rows = 16;
     if (const char *e = getenv("DGQ_SUPER_ROWS")) super_rows = atoi(e) > 0 ? atoi(e) : super_rows;
     hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
-                       w.d_zb, g.d_s, g.d_gchunk, rows, w.O, w.O_pad, w.Kp, g.info.n_groups,
+                       w.d_zb, g.d_s, g.d_zoff, g.n_tab, g.d_gchunk, rows, w.O, w.O_pad, w.Kp,
+                       g.info.n_groups,
                        tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump);
     return hipGetLastError();
 }
@@ -606,6 +686,8 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         env_read = true;
     }
     const bool a8 = g.info.act_bits == 8;
+    const bool multi = g.n_tab > 2;  // more than two pixel classes (one channel group)
+    if (multi && (geglu || acc_dump || g.info.n_groups != 1)) return hipErrorInvalidValue;
     if (acc_dump) {
         return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
                   : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
@@ -625,6 +707,9 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         if (geglu)                                                                                 \
             return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, true>(g, w, codes, row_class, rows, y, nullptr, st) \
                       : launch_cfg<Cfg<4, __VA_ARGS__>, false, true>(g, w, codes, row_class, rows, y, nullptr, st); \
+        if (multi)                                                                                 \
+            return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st) \
+                      : launch_cfg<Cfg<4, __VA_ARGS__>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st); \
         return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st) \
                   : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
     switch (cfg) {

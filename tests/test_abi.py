@@ -54,6 +54,12 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_calibrate_groups(p, 1, 64, 8, 96, 2, None, C.byref(h)) == -1  # group size
     assert lib.dgq_calibrate_groups(p, 1, 64, 8, 64, 3, None, C.byref(h)) == -1  # classes
     assert lib.dgq_calibrate_groups(p, 0, 64, 8, 64, 2, None, C.byref(h)) == -1  # empty
+    assert lib.dgq_calibrate_kmeans(None, 4, 64, 8, 8, -1, None, C.byref(h)) == -1
+    assert lib.dgq_calibrate_kmeans(p, 1, 64, 8, 0, -1, None, C.byref(h)) == -1   # clusters
+    assert lib.dgq_calibrate_kmeans(p, 1, 64, 8, 17, -1, None, C.byref(h)) == -1  # clusters
+    assert lib.dgq_calibrate_kmeans(p, 1, 64, 8, 8, 2, None, C.byref(h)) == -1    # dimension
+    assert lib.dgq_calibrate_kmeans(p, 1, 64, 6, 8, 0, None, C.byref(h)) == -1    # act_bits
+    assert lib.dgq_groups_thresholds(None, None) == -1
     assert lib.dgq_xattn_logq(p, p, p, None, 1, 1, 1, 8, 77, 5, p, p, None, None, 0, None) == -1
     assert lib.dgq_xattn_logq(p, p, p, None, 1, 1, 1, 8, 1, 8, p, p, None, None, 0, None) == -4
     assert lib.dgq_xattn_logq(p, p, p, None, 1, 1, 1, 300, 77, 8, p, p, None, None, 0, None) == -4
@@ -62,8 +68,8 @@ def test_argument_errors_without_gpu(lib):
 
 def test_binding_names_match_the_abi():
     import paper_2501_04304_amd as dgq
-    for s in ("dgq_calibrate_groups", "dgq_pack_weight", "dgq_quantize_act", "dgq_linear",
-              "dgq_linear_geglu", "dgq_xattn_logq", "dgq_xattn_workspace_bytes"):
+    for s in ("dgq_calibrate_groups", "dgq_calibrate_kmeans", "dgq_pack_weight",
+              "dgq_quantize_act", "dgq_linear", "dgq_linear_geglu", "dgq_xattn_logq", "dgq_xattn_workspace_bytes"):
         assert callable(getattr(dgq, s))
 
 
