@@ -110,7 +110,7 @@ def main():
         x = up(run["X"])
         w = up(run["W"])
         xc = up(cal["X"])
-        ent = dict(name=name, M=M, C=C, O=O, G=G, x=x, modes={})
+        ent = dict(name=name, M=M, B=B, N=N, C=C, O=O, G=G, x=x, seed=seed, modes={})
         for (ab, wb) in cfg["modes"]:
             g = dgq.dgq_calibrate_groups(xc, ab, G, 2)
             wt = dgq.dgq_pack_weight(g, w, None, wb)
@@ -292,6 +292,94 @@ def main():
                 f["us_separate_activation_pass"] = round(us_sep, 2)
         del yg
 
+    # ---------------- beyond the step: the single-dimension grouping of Section 3.3 ----------
+    # K = 16 clusters of pixels or of channels (dgq_calibrate_kmeans) on two layers, A8W8,
+    # next to the same layers under the step's pixel-class x channel-group grid; and one
+    # layer swept over T = 25 per-timestep table entries (Eq. 7), each step with its own handle.
+    def time_calls(fn, a, n_rep=10):
+        for _ in range(2):
+            if fn(*a) != 0:
+                raise dgq.DgqError(-1, L.dgq_last_error().decode())
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n_rep):
+            fn(*a)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n_rep
+
+    def step_us(kind, ent):
+        ci = [i for i, (k_, key, _) in enumerate(calls) if k_ == kind and key[0] is ent][0]
+        return sum(ev[k][ci][0].elapsed_time(ev[k][ci][1]) for k in range(args.steps)) * 1e3 / args.steps
+
+    kmeans = []
+    sweep = None
+    if args.workload == "config5":
+        for ent in layers:
+            if ent["name"] not in ("hi.q", "lo.ff.out"):
+                continue
+            cal = di.linear_case(ent["seed"], min(ent["B"], args.calib_batch), ent["N"], ent["C"],
+                                 ent["O"], calib=True, with_weight=False)
+            xc = up(cal["X"])
+            w = up(di.linear_case(ent["seed"], 1, 2, ent["C"], ent["O"])["W"])
+            for dim, dname in ((dgq.DIM_PIXEL, "pixel"), (dgq.DIM_CHANNEL, "channel")):
+                g = dgq.dgq_calibrate_kmeans(xc, 8, 16, dim)
+                wt = dgq.dgq_pack_weight(g, w, None, 8)
+                codes = torch.empty(dgq.codes_shape(g, ent["M"]), dtype=torch.int8, device=dev)
+                cls = torch.empty(ent["M"], dtype=torch.uint8, device=dev)
+                us_q = time_calls(L.dgq_quantize_act, (C.c_void_p(g.handle), ptr(ent["x"]),
+                                                       C.c_int64(ent["M"]), ptr(codes), ptr(cls), sp))
+                us_l = time_calls(L.dgq_linear, (C.c_void_p(g.handle), C.c_void_p(wt.handle), ptr(codes),
+                                                 ptr(cls), C.c_int64(ent["M"]), ptr(ent["y"]), None,
+                                                 None, C.c_size_t(0), sp))
+                ops = 2.0 * ent["M"] * ent["C"] * ent["O"]
+                kmeans.append(dict(layer=ent["name"], dimension=dname, clusters=16,
+                                   pixel_classes=g.info.n_pixel_classes, channel_groups=g.info.n_groups,
+                                   k_padded=g.info.k_padded, d_star=("pixel" if g.info.dstar else "channel"),
+                                   us_quantize=round(us_q, 2), us_linear=round(us_l, 2),
+                                   tops_linear=round(ops / us_l / 1e6, 1),
+                                   us_quantize_grid=round(step_us("quantize_a8", ent), 2),
+                                   us_linear_grid=round(step_us("linear_a8", ent), 2)))
+                wt.free()
+                g.free()
+                del codes, cls
+            if ent["name"] == "hi.q":
+                T = 25
+                hs = []
+                for t in range(T):
+                    xt = xc * float(1.0 + 0.5 * np.sin(0.7 * t))  # the range drifts with the step
+                    g = dgq.dgq_calibrate_kmeans(xt, 8, 16, dgq.DIM_CHANNEL)
+                    hs.append((g, dgq.dgq_pack_weight(g, w, None, 8)))
+                    del xt
+                kp = max(g.info.k_padded for g, _ in hs)
+                codes = torch.empty((ent["M"] // 16 + 1) * (kp // 64) * 1024, dtype=torch.int8, device=dev)
+                cls = torch.empty(ent["M"], dtype=torch.uint8, device=dev)
+                argsq = [(C.c_void_p(g.handle), ptr(ent["x"]), C.c_int64(ent["M"]), ptr(codes), ptr(cls), sp)
+                         for g, _ in hs]
+                argsl = [(C.c_void_p(g.handle), C.c_void_p(wt.handle), ptr(codes), ptr(cls),
+                          C.c_int64(ent["M"]), ptr(ent["y"]), None, None, C.c_size_t(0), sp) for g, wt in hs]
+
+                def sweep_once():
+                    for t in range(T):
+                        if L.dgq_quantize_act(*argsq[t]) != 0 or L.dgq_linear(*argsl[t]) != 0:
+                            raise dgq.DgqError(-1, L.dgq_last_error().decode())
+                sweep_once()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                sweep_once()
+                sweep_once()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                sweep = dict(layer=ent["name"], timesteps=T, dimension="channel", clusters=16,
+                             us_per_timestep=round(e0.elapsed_time(e1) * 1e3 / (2 * T), 2),
+                             table_bytes=T * 16 * 2 * 4)
+                for g, wt in hs:
+                    wt.free()
+                    g.free()
+                del codes, cls
+            del xc, w
+
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -325,7 +413,7 @@ def main():
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
-                linear_geglu=fused, cpu_baseline=cpu)
+                linear_geglu=fused, kmeans_grouping=kmeans, timestep_sweep=sweep, cpu_baseline=cpu)
     print(json.dumps(line))
 
 
