@@ -364,11 +364,16 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         for (int a = 0; a < BR; ++a) {
             same = same && __ballot((int32_t)row_c1[a] != c_first) == 0;
             clsn[a][0] = clsn[a][1] = 0;
+            // rows 8 q + 4 kh + (0..3) sit in four neighbouring lanes: fetch their classes as
+            // one packed value per lane (class of row m in bits 4 (m & 3) .. of lane m & ~3's
+            // word), so that four cross-lane reads instead of sixteen build the fields
+            uint32_t quad = (uint32_t)row_c1[a] & 15u;
+            quad |= ((uint32_t)__shfl_down((int32_t)quad, 1, 64) & 15u) << 4;   // rows m, m+1
+            quad |= ((uint32_t)__shfl_down((int32_t)quad, 2, 64) & 0xffu) << 8; // rows m .. m+3
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = 8 * (i >> 2) + 4 * kh + (i & 3);
-                const uint32_t c = (uint32_t)__shfl((int32_t)row_c1[a], m, 64) & 15u;
-                clsn[a][i >> 3] |= c << (4 * (i & 7));
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t four = (uint32_t)__shfl((int32_t)quad, 8 * q + 4 * kh, 64) & 0xffffu;
+                clsn[a][q >> 1] |= four << (16 * (q & 1));
             }
             // opaque from here on: otherwise the sixteen unpacked values are kept (and
             // spilled) across the loop instead of these two registers
@@ -529,6 +534,46 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         // chunk ch) a literal: the stage addresses then sit in the LDS instructions'
         // offset fields instead of costing vector adds (a vector instruction costs this
         // kernel about four clocks of SIMD time with nothing hidden behind it).
+        // ---- fold the finished group's int32 block into the fp32 sum with its scale ---
+        auto fold_group = [&]() __attribute__((always_inline)) {
+            if (!MIXED) {
+                const float sg = s_p[g];
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int b = 0; b < BO; ++b)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
+            } else if (MULTI) {
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int i0 = 0; i0 < 16; i0 += 4) {
+                        float sg[4];
+#pragma unroll
+                        for (int i = i0; i < i0 + 4; ++i)
+                            sg[i - i0] = tab_s[(clsn[a][i >> 3] >> (4 * (i & 7))) & 15u];
+#pragma unroll
+                        for (int i = i0; i < i0 + 4; ++i)
+#pragma unroll
+                            for (int b = 0; b < BO; ++b)
+                                facc[a][b][i] = fmaf((float)acc[a][b][i], sg[i - i0], facc[a][b][i]);
+                        asm volatile("" ::: "memory");
+                    }
+            } else {
+                const float s0 = tab_s[g], s1 = tab_s[NG + g];
+#pragma unroll
+                for (int a = 0; a < BR; ++a)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float sg = ((cls1[a] >> i) & 1) ? s1 : s0;
+#pragma unroll
+                        for (int b = 0; b < BO; ++b)
+                            facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
+                    }
+            }
+        };
         auto chunk = [&](auto steady_tag, const int pos, const int32_t ch) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;
             const int npos = pos + 1 == STAGES ? 0 : pos + 1;
@@ -554,45 +599,10 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             }
             mfma_all(af1, bf1, false);
 
-            if (ch + 1 == g_end) {
-                // ---- fold this group's int32 block into the fp32 sum with its scale ---
-                if (!MIXED) {
-                    const float sg = s_p[g];
-#pragma unroll
-                    for (int a = 0; a < BR; ++a)
-#pragma unroll
-                        for (int b = 0; b < BO; ++b)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i)
-                                facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
-                } else if (MULTI) {
-#pragma unroll
-                    for (int a = 0; a < BR; ++a)
-#pragma unroll
-                        for (int i0 = 0; i0 < 16; i0 += 4) {
-                            float sg[4];
-#pragma unroll
-                            for (int i = i0; i < i0 + 4; ++i)
-                                sg[i - i0] = tab_s[(clsn[a][i >> 3] >> (4 * (i & 7))) & 15u];
-#pragma unroll
-                            for (int i = i0; i < i0 + 4; ++i)
-#pragma unroll
-                                for (int b = 0; b < BO; ++b)
-                                    facc[a][b][i] = fmaf((float)acc[a][b][i], sg[i - i0], facc[a][b][i]);
-                            asm volatile("" ::: "memory");
-                        }
-                } else {
-                    const float s0 = tab_s[g], s1 = tab_s[NG + g];
-#pragma unroll
-                    for (int a = 0; a < BR; ++a)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const float sg = ((cls1[a] >> i) & 1) ? s1 : s0;
-#pragma unroll
-                            for (int b = 0; b < BO; ++b)
-                                facc[a][b][i] = fmaf((float)acc[a][b][i], sg, facc[a][b][i]);
-                        }
-                }
+            // MULTI has one group: its only fold follows the loop, so the fp32 block does not
+            // occupy registers inside it
+            if (!MULTI && ch + 1 == g_end) {
+                fold_group();
                 if (DUMP) {
 #pragma unroll
                     for (int a = 0; a < BR; ++a)
@@ -626,6 +636,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             pos = pos + 1 == STAGES ? 0 : pos + 1;
         }
 
+        if constexpr (MULTI) fold_group();
         epilogue(mixed_tag, p);
     };
 
