@@ -250,6 +250,18 @@ def xattn_logq(A, V, bits: int, want_ahat: bool = False):
     return dict(s=s, codes=codes, margin=margin, ahat=ahat, out=out)
 
 
+def quantize_value(V, bits: int = 8):
+    """V [B,nk,H,d] -> dict(vhat fp32 [B,nk,H,d], codes u8, params [B,H,2] = (s, z))."""
+    V = _f32(V)
+    B, nk, H, d = V.shape
+    vhat = np.zeros_like(V)
+    codes = np.zeros(V.shape, dtype=np.uint8)
+    params = np.zeros((B, H, 2), dtype=np.float32)
+    lib().dgqo_quantize_value(_p(V), C.c_int32(B), C.c_int32(nk), C.c_int32(H), C.c_int32(d),
+                              C.c_int32(bits), _p(vhat), _p(codes), _p(params))
+    return dict(vhat=vhat, codes=codes, params=params)
+
+
 def xattn(Q, K, V, key_bias, bits: int, want_ahat: bool = False):
     A = attn_probs(Q, K, key_bias)
     r = xattn_logq(A, V, bits, want_ahat)

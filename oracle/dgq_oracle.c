@@ -816,3 +816,51 @@ void dgqo_geglu(const float *y, int64_t rows, int32_t O, float *out)
         }
 }
 
+
+/* ------------------------------------------------------------------------- */
+/* Quantized value tensor of the attention product (Section 3.3, A^ V^)      */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * V^ of the product A^ V^: the value tensor goes through the linear quantizer of
+ * Section 3.1 with the range of its own (prompt, head) slice,
+ *   s = (max - min) / 2^b (1 if max == min),  z = min   over V[b, :, h, :]
+ *   q = clamp(rne((v - z) * (1/s)), 0, 2^b - 1)         (fp32, separate operations)
+ *   v^ = s * q + z, rounded once to fp32
+ * V, vhat: [B, nk, H, d]; codes (nullable): [B, nk, H, d]; params (nullable):
+ * [B, H, 2] = (s, z).
+ */
+void dgqo_quantize_value(const float *V, int32_t B, int32_t nk, int32_t H, int32_t d,
+                         int32_t bits, float *vhat, uint8_t *codes, float *params)
+{
+    const float qmax = (float)((1 << bits) - 1);
+    const float levels = (float)(1 << bits);
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t h = 0; h < H; ++h) {
+            float mx = -INFINITY, mn = INFINITY;
+            for (int32_t j = 0; j < nk; ++j)
+                for (int32_t t = 0; t < d; ++t) {
+                    float v = V[(((int64_t)b * nk + j) * H + h) * d + t];
+                    if (v > mx) mx = v;
+                    if (v < mn) mn = v;
+                }
+            float s = (mx - mn) / levels;
+            if (!(mx > mn)) s = 1.0f;
+            float inv = 1.0f / s;
+            if (params) {
+                params[((int64_t)b * H + h) * 2 + 0] = s;
+                params[((int64_t)b * H + h) * 2 + 1] = mn;
+            }
+            for (int32_t j = 0; j < nk; ++j)
+                for (int32_t t = 0; t < d; ++t) {
+                    int64_t at = (((int64_t)b * nk + j) * H + h) * d + t;
+                    float u = (V[at] - mn) * inv;
+                    float qf = nearbyintf(u);
+                    if (qf < 0.0f) qf = 0.0f;
+                    if (qf > qmax) qf = qmax;
+                    if (!(qf == qf)) qf = 0.0f;
+                    if (codes) codes[at] = (uint8_t)qf;
+                    vhat[at] = (float)((double)s * (double)qf + (double)mn);
+                }
+        }
+}
