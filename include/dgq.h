@@ -292,6 +292,26 @@ const char *dgq_last_error(void);
 /* Library version as major*10000 + minor*100 + patch. */
 int dgq_version(void);
 
+/*
+ * The quantized value tensor V^ of the attention product A^ V^ (Section 3.3).  Every
+ * (prompt, head) slice V[b, :, h, :] goes through the linear quantizer of Section 3.1
+ * with its own range:
+ *   s = (max - min) / 2^v_bits (1 if max == min),  z = min
+ *   q = clamp(rne((v - z) * (1/s)), 0, 2^v_bits - 1)      (separate fp32 operations)
+ *   v_hat = s * q + z                                      (rounded once to fp32)
+ * Pass v_hat as `v` to dgq_xattn_logq: the kernel then forms exactly A^ V^, the
+ * power-of-two weights times the dequantized codes (on this hardware the matrix cores do
+ * what shift-and-add does elsewhere).  The text context does not change over the
+ * denoising steps, so this is one small launch per prompt, not per step.
+ *   v, v_hat: fp32 [B, nk, H, d] (may be the same buffer);  v_bits: 4 or 8
+ *   codes:  NULL, or uint8 [B, nk, H, d] receiving q
+ *   params: NULL, or fp32 [B, H, 2] receiving (s, z)
+ * Enqueues on `stream`; neither synchronises nor allocates.
+ */
+int dgq_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
+                       int32_t v_bits, float *v_hat, uint8_t *codes, float *params,
+                       void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -69,6 +69,7 @@ def lib():
         L.dgq_xattn_logq.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
                                      vp, sz, vp]
         L.dgq_xattn_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.dgq_quantize_value.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.dgq_xattn_workspace_bytes.restype = sz
         L.dgq_last_error.restype = C.c_char_p
         L.dgq_version.restype = C.c_int
@@ -307,3 +308,19 @@ def dgq_xattn_logq(q, k, v, key_bias, attn_bits: int, out=None, scale_out=None, 
                                 attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
                                 _ptr(workspace), wbytes, _stream(stream)))
     return out, scale_out
+
+
+def dgq_quantize_value(v, v_bits: int = 8, v_hat=None, want_codes: bool = False,
+                       want_params: bool = False, stream=None):
+    """v [B,nk,H,d] fp32 -> v_hat (and, on request, the codes and the (s, z) pairs)."""
+    import torch
+    _dev(v, torch.float32, "v")
+    B, nk, H, d = v.shape
+    if v_hat is None:
+        v_hat = torch.empty_like(v)
+    codes = torch.empty(v.shape, dtype=torch.uint8, device=v.device) if want_codes else None
+    params = torch.empty((B, H, 2), dtype=torch.float32, device=v.device) if want_params else None
+    _check(lib().dgq_quantize_value(_ptr(v), B, nk, H, d, v_bits, _ptr(v_hat),
+                                    _ptr(codes) if codes is not None else None,
+                                    _ptr(params) if params is not None else None, _stream(stream)))
+    return v_hat, codes, params

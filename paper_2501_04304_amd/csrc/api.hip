@@ -750,4 +750,18 @@ int dgq_xattn_logq(const float *q, const float *k, const float *v, const float *
     return DGQ_OK;
 }
 
+int dgq_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d, int32_t v_bits,
+                       float *v_hat, uint8_t *codes, float *params, void *stream) {
+    if (!v || !v_hat) return fail(DGQ_EINVAL, "dgq_quantize_value: null pointer");
+    if (B < 1 || nk < 1 || H < 1 || d < 1) return fail(DGQ_EINVAL, "dgq_quantize_value: empty tensor");
+    if (v_bits != 4 && v_bits != 8) return fail(DGQ_EINVAL, "dgq_quantize_value: v_bits must be 4 or 8");
+    if (B > 65535 || (int64_t)nk * d > (int64_t)1 << 30)
+        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_value: B above 65535 or a slice above 2^30 elements");
+    if (!aligned16(v) || !aligned16(v_hat))
+        return fail(DGQ_EALIGN, "dgq_quantize_value: tensor not 16-byte aligned");
+    DGQ_HIP(launch_quantize_value(v, B, nk, H, d, v_bits, v_hat, codes, params,
+                                  static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
 }  // extern "C"

@@ -118,6 +118,10 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
                         float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
                         hipStream_t st);
 
+hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
+                                 int32_t bits, float *vhat, uint8_t *codes, float *params,
+                                 hipStream_t st);
+
 size_t xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk);
 
 }  // namespace dgq

@@ -639,6 +639,54 @@ __global__ __launch_bounds__(256) void k_xattn(
     }
 }
 
+// V^ of the product A^ V^ (Section 3.3): one workgroup per (prompt, head) finds the range
+// of its [nk, d] slice, quantizes with s = (max - min) / 2^b, z = min (separate subtract
+// and multiply, round to nearest even, clamp) and writes the reconstruction s q + z
+// (one fused multiply-add, i.e. rounded once), optionally the codes and (s, z).
+__global__ __launch_bounds__(256) void k_quantize_value(
+    const float *v, int32_t nk, int32_t H, int32_t d, int32_t bits, float *vhat /* may be v */,
+    uint8_t *__restrict__ codes, float *__restrict__ params) {
+    __shared__ float red_mx[4], red_mn[4];
+    const int32_t b = blockIdx.y, h = blockIdx.x;
+    const int64_t base = ((int64_t)b * nk * H + h) * d, hs = (int64_t)H * d;
+    const int32_t n = nk * d;
+    float mx = -INFINITY, mn = INFINITY;
+    for (int32_t i = threadIdx.x; i < n; i += 256) {
+        const int32_t j = i / d, t = i - j * d;
+        const float x = v[base + (int64_t)j * hs + t];
+        mx = x > mx ? x : mx;
+        mn = x < mn ? x : mn;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float a = __shfl_xor(mx, o, kWave), c = __shfl_xor(mn, o, kWave);
+        mx = a > mx ? a : mx;
+        mn = c < mn ? c : mn;
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red_mx[threadIdx.x >> 6] = mx;
+        red_mn[threadIdx.x >> 6] = mn;
+    }
+    __syncthreads();
+    mx = fmaxf(fmaxf(red_mx[0], red_mx[1]), fmaxf(red_mx[2], red_mx[3]));
+    mn = fminf(fminf(red_mn[0], red_mn[1]), fminf(red_mn[2], red_mn[3]));
+    const float levels = (float)(1 << bits), qmax = levels - 1.0f;
+    const float s = mx > mn ? __fdiv_rn(__fsub_rn(mx, mn), levels) : 1.0f;
+    const float inv = __fdiv_rn(1.0f, s);
+    if (params && threadIdx.x == 0) {
+        params[((int64_t)b * H + h) * 2 + 0] = s;
+        params[((int64_t)b * H + h) * 2 + 1] = mn;
+    }
+    for (int32_t i = threadIdx.x; i < n; i += 256) {
+        const int32_t j = i / d, t = i - j * d;
+        const int64_t at = base + (int64_t)j * hs + t;
+        const float u = __fmul_rn(__fsub_rn(v[at], mn), inv);
+        float qf = fminf(fmaxf(rintf(u), 0.0f), qmax);  // NaN -> 0
+        if (codes) codes[at] = (uint8_t)qf;
+        vhat[at] = __fmaf_rn(s, qf, mn);
+    }
+}
+
 template <int NKP>
 hipError_t launch_passes(const float *q, const float *k, const float *v, const float *key_bias,
                          int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
@@ -671,6 +719,14 @@ hipError_t launch_passes(const float *q, const float *k, const float *v, const f
 size_t xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk) {
     if (!mfma_shape(d, nk)) return 0;
     return ((size_t)B * H * N * sizeof(float) + 255) / 256 * 256;
+}
+
+hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
+                                 int32_t bits, float *vhat, uint8_t *codes, float *params,
+                                 hipStream_t st) {
+    hipLaunchKernelGGL(k_quantize_value, dim3(H, B), dim3(256), 0, st, v, nk, H, d, bits, vhat,
+                       codes, params);
+    return hipGetLastError();
 }
 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,

@@ -1,0 +1,128 @@
+"""GPU parity of the quantized value tensor V^ (dgq_quantize_value) and of the attention
+product on it, A^ V^ of Section 3.3, against the CPU oracle: value codes, (s, z) and the
+reconstruction bit-exact; the product within 1e-4 * max|ref|; attention codes as in
+test_gpu_xattn (they do not depend on V)."""
+import numpy as np
+import pytest
+
+import dgq_inputs as di
+from support import assert_close_fp32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgq():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2501_04304_amd as m
+    m.lib()
+    return m
+
+
+def _dev(a):
+    import torch
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _value_parity(dgq, oracle, V, bits):
+    import torch
+    ref = oracle.quantize_value(V, bits)
+    vhat, codes, params = dgq.dgq_quantize_value(_dev(V), bits, want_codes=True, want_params=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), ref["codes"])
+    assert np.array_equal(params.cpu().numpy().view(np.uint32), ref["params"].view(np.uint32))
+    assert np.array_equal(vhat.cpu().numpy().view(np.uint32), ref["vhat"].view(np.uint32))
+    return ref, vhat
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("B,nk,H,d", [(2, 77, 8, 40), (3, 77, 10, 64), (1, 5, 3, 7), (2, 100, 2, 160),
+                                      (1, 1, 1, 1)])
+def test_value_codes_bit_exact(dgq, oracle, B, nk, H, d, bits):
+    rng = np.random.default_rng(100 + nk + d)
+    V = (rng.standard_normal((B, nk, H, d)) * rng.uniform(0.3, 4.0, size=(B, 1, H, 1))).astype(np.float32)
+    _value_parity(dgq, oracle, V, bits)
+
+
+def test_value_in_place_and_without_outputs(dgq, oracle):
+    import torch
+    rng = np.random.default_rng(7)
+    V = rng.standard_normal((2, 77, 4, 64)).astype(np.float32)
+    ref = oracle.quantize_value(V, 8)
+    buf = _dev(V)
+    out, codes, params = dgq.dgq_quantize_value(buf, 8, v_hat=buf)
+    torch.cuda.synchronize()
+    assert codes is None and params is None and out.data_ptr() == buf.data_ptr()
+    assert np.array_equal(buf.cpu().numpy(), ref["vhat"])
+    # a constant slice: s = 1, code 0, value unchanged
+    Vc = np.full((1, 9, 2, 8), -0.375, np.float32)
+    vh, c, p = dgq.dgq_quantize_value(_dev(Vc), 8, want_codes=True, want_params=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(vh.cpu().numpy(), Vc) and int(c.max()) == 0
+    assert np.all(p.cpu().numpy()[..., 0] == 1.0)
+
+
+@pytest.mark.parametrize("abits,vbits", [(8, 8), (4, 8), (4, 4)])
+@pytest.mark.parametrize("B,N,H,d,nk", [
+    (2, 300, 3, 40, 77),   # the matrix-core kernels, ragged query tile
+    (1, 64, 2, 64, 77),
+    (2, 70, 2, 37, 77),    # the per-thread kernels (head dim not a multiple of 8)
+    (1, 40, 2, 40, 100),
+])
+def test_product_on_quantized_values(dgq, oracle, B, N, H, d, nk, abits, vbits):
+    """A^ V^: quantize V on the GPU, run the attention on it, compare with the oracle's
+    attention on the oracle's V^."""
+    import torch
+    from oracle.guard import DELTA, guarded_attention_case
+    c, _ = guarded_attention_case(900 + d + nk, B, N, H, d, nk=nk, bits_list=(abits,))
+    ref_v, vhat = _value_parity(dgq, oracle, c["V"], vbits)
+    ref = oracle.xattn(c["Q"], c["K"], ref_v["vhat"], c["key_bias"], abits)
+    codes = torch.full((B, H, N, nk - 1), 0xEE, dtype=torch.uint8, device="cuda")
+    out, s = dgq.dgq_xattn_logq(_dev(c["Q"]), _dev(c["K"]), vhat, _dev(c["key_bias"]), abits,
+                                codes_dump=codes)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(s.cpu().numpy() - ref["s"]) <= 1e-5 * ref["s"])
+    assert (ref["margin"] >= DELTA).all()
+    assert np.array_equal(codes.cpu().numpy(), ref["codes"])
+    assert_close_fp32(out.cpu().numpy(), ref["out"], "out")
+    # and the quantization of V is visible: the product differs from the one on raw V
+    ref_raw = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], abits)
+    assert np.abs(ref_raw["out"] - ref["out"]).max() > 1e-4 * np.abs(ref["out"]).max()
+
+
+def test_config5_shape_sampled(dgq, oracle):
+    """The SDXL-scale attention of the bench (16 prompts x 10 heads x 4096 queries, d = 64,
+    8-bit codes) on quantized values; the oracle checks two whole prompts, which is what a
+    per-prompt scale allows."""
+    import torch
+    from oracle.guard import DELTA
+    name, B, N, H, d, nk, d_ctx = di.config5()["attention"][0]
+    c = di.attention_case(5000, B, N, H, d, nk=nk, d_ctx=d_ctx)
+    vhat, _, _ = dgq.dgq_quantize_value(_dev(c["V"]), 8)
+    out, s = dgq.dgq_xattn_logq(_dev(c["Q"]), _dev(c["K"]), vhat, _dev(c["key_bias"]), 8)
+    torch.cuda.synchronize()
+    out, s, vh = out.cpu().numpy(), s.cpu().numpy(), vhat.cpu().numpy()
+    for b in (0, B - 1):
+        rv = oracle.quantize_value(c["V"][b:b + 1], 8)
+        assert np.array_equal(vh[b:b + 1], rv["vhat"])
+        ref = oracle.xattn(c["Q"][b:b + 1], c["K"][b:b + 1], rv["vhat"], c["key_bias"], 8)
+        assert abs(s[b] - ref["s"][0]) <= 1e-5 * ref["s"][0]
+        safe = ref["margin"][0] >= DELTA
+        good = np.transpose(safe.all(-1), (1, 0))  # [N, H]: rows without a marginal code
+        assert good.mean() > 0.9
+        err = np.abs(out[b] - ref["out"][0])[good]
+        assert err.max() <= 1e-4 * np.abs(ref["out"][0]).max()
+
+
+def test_argument_errors(dgq):
+    import torch
+    v = torch.zeros((1, 4, 1, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(dgq.DgqError) as e:
+        dgq.dgq_quantize_value(v, 5)
+    assert e.value.code == -1
+    big = torch.zeros(4 * 8 + 4, dtype=torch.float32, device="cuda")
+    vm = big[1:33].view(1, 4, 1, 8)
+    with pytest.raises(dgq.DgqError) as e:
+        dgq._check(dgq.lib().dgq_quantize_value(vm.data_ptr(), 1, 4, 1, 8, 8, v.data_ptr(), None, None, None))
+    assert e.value.code == -2
