@@ -383,6 +383,21 @@ def main():
                 del codes, cls
             del xc, w
 
+    # ---------------- beyond the step: the attention product on the quantized value tensor ---
+    value_quant = []
+    if not args.step_only:
+        for a_ in attns:
+            vhat = torch.empty_like(a_["v"])
+            us_v = time_calls(L.dgq_quantize_value, (ptr(a_["v"]), a_["B"], a_["nk"], a_["H"], a_["d"], 8,
+                                                     ptr(vhat), None, None, sp))
+            us_a = time_calls(L.dgq_xattn_logq, (ptr(a_["q"]), ptr(a_["k"]), ptr(vhat), ptr(a_["kb"]), a_["B"],
+                                                 a_["N"], a_["H"], a_["d"], a_["nk"], 8, ptr(a_["out"]),
+                                                 ptr(a_["s"]), None, ptr(a_["ws"]),
+                                                 C.c_size_t(a_["ws"].numel()), sp))
+            value_quant.append(dict(attention=a_["name"], v_bits=8, attn_bits=8,
+                                    us_quantize_value=round(us_v, 2), us_attention_on_v_hat=round(us_a, 2)))
+            del vhat
+
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -416,7 +431,7 @@ def main():
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
-                linear_geglu=fused, kmeans_grouping=kmeans, timestep_sweep=sweep, cpu_baseline=cpu)
+                linear_geglu=fused, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, cpu_baseline=cpu)
     print(json.dumps(line))
 
 
