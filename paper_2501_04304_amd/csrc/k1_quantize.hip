@@ -22,6 +22,7 @@
 // multiply, round, clamp and the byte pack.
 #include "dgq_internal.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace dgq {
@@ -392,6 +393,8 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
         // resident workgroups per CU by LDS; every workgroup walks several units
         int per_cu = (int)((160 * 1024) / lds);
         per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+        static const int env_cap = getenv("DGQ_QUANT_WGPC") ? atoi(getenv("DGQ_QUANT_WGPC")) : 0;  // tuning hook
+        if (env_cap > 0 && per_cu > env_cap) per_cu = env_cap;
         const int64_t cap = 256 * (int64_t)per_cu;
         if (blocks > cap) blocks = cap;
     } else {
