@@ -707,7 +707,7 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     // the other waves that keep the matrix pipe busy meanwhile.  Large problems take
     // 128 x 128 tiles (fewer operand bytes per output), medium ones 64 x 128 tiles so that every CU still gets work, and
     // problems with fewer tiles than CUs (the projections of the 77-token prompt) 64 x 64
-    // tiles behind an 8-deep ring: there a workgroup is alone on its CU and only the
+    // tiles of four 32 x 32 waves behind an 8-deep ring: there a workgroup is alone on its CU and only the
     // depth of the ring hides the latency of the chunks.
     const int64_t t128 = ((rows + 127) / 128) * ((w.O + 127) / 128);
     const int64_t t64x128 = ((rows + 63) / 64) * ((w.O + 127) / 128);
@@ -725,7 +725,17 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                   : launch_cfg<Cfg<4, __VA_ARGS__>, false>(g, w, codes, row_class, rows, y, nullptr, st)
     switch (cfg) {
         DGQ_CASE(2, 2, 2, 1, 2, 3, 4);  // 64 x 128, 4 waves of 32 x 64, four workgroups per CU
-        DGQ_CASE(6, 2, 1, 1, 2, 8, 4);  // 64 x 64, 2 waves of 32 x 64, 8-stage ring
+        case 6:  // 64 x 64 behind an 8-stage ring: 4 waves of 32 x 32 (13-15 % faster on the
+                 // 1232-row projections than 2 waves of 32 x 64); the gated epilogue needs
+                 // two column blocks per wave and keeps the 2-wave shape
+            if (geglu)
+                return a8 ? launch_cfg<Cfg<8, 2, 1, 1, 2, 8, 4>, false, true>(g, w, codes, row_class, rows, y, nullptr, st)
+                          : launch_cfg<Cfg<4, 2, 1, 1, 2, 8, 4>, false, true>(g, w, codes, row_class, rows, y, nullptr, st);
+            if (multi)
+                return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 1, 8, 4>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st)
+                          : launch_cfg<Cfg<4, 2, 2, 1, 1, 8, 4>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st);
+            return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 1, 8, 4>, false>(g, w, codes, row_class, rows, y, nullptr, st)
+                      : launch_cfg<Cfg<4, 2, 2, 1, 1, 8, 4>, false>(g, w, codes, row_class, rows, y, nullptr, st);
         default:
             DGQ_CASE(4, 4, 2, 1, 2, 4, 4);  // 128 x 128, 8 waves of 32 x 64, two workgroups per CU
     }
