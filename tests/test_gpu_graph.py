@@ -1,0 +1,78 @@
+"""The hot calls only enqueue kernels (no allocation, no synchronisation, no memset
+nodes), so a caller may capture them in a HIP graph.  One layer plus one attention is
+captured once and replayed several times, with eager work and synchronisations between
+the replays; every replay must reproduce the eager results bit for bit."""
+import numpy as np
+import pytest
+
+import dgq_inputs as di
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgq():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2501_04304_amd as m
+    m.lib()
+    return m
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def test_captured_step_replays_like_eager(dgq):
+    import torch
+    run = di.linear_case(31, 2, 700, 320, 384)
+    cal = di.linear_case(31, 2, 700, 320, 384, calib=True)
+    att = di.attention_case(32, 2, 500, 4, 40, nk=77, d_ctx=64)
+    x = _dev(run["X"])
+    g = dgq.dgq_calibrate_groups(_dev(cal["X"]), 8, 64, 2)
+    w = dgq.dgq_pack_weight(g, _dev(run["W"]), None, 8)
+    M, O = x.shape[0], run["W"].shape[0]
+    codes = torch.empty(dgq.codes_shape(g, M), dtype=torch.int8, device="cuda")
+    cls = torch.empty(M, dtype=torch.uint8, device="cuda")
+    y = torch.empty((M, O), dtype=torch.float32, device="cuda")
+    q, k, v, kb = (_dev(att[n]) for n in ("Q", "K", "V", "key_bias"))
+    vhat = torch.empty_like(v)
+    out = torch.empty_like(q)
+    s = torch.empty(q.shape[0], dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(16, dgq.dgq_xattn_workspace_bytes(q.shape[0], q.shape[1], q.shape[2], q.shape[3], 77)),
+                     dtype=torch.uint8, device="cuda")
+
+    def step():
+        dgq.dgq_quantize_act(g, x, codes=codes, row_class=cls)
+        dgq.dgq_linear(g, w, codes, cls, y=y)
+        dgq.dgq_quantize_value(v, 8, v_hat=vhat)
+        dgq.dgq_xattn_logq(q, k, vhat, kb, 8, out=out, scale_out=s, workspace=ws)
+
+    step()  # eager: also the one-time kernel attributes, which are no stream work
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (codes, cls, y, vhat, out, s)]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+
+    for rep in range(4):
+        for t in (codes, cls, y, vhat, out, s):
+            t.zero_()                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((codes, cls, y, vhat, out, s), want):
+            assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
+        if rep == 1:                       # and an eager call in between
+            step()
+            torch.cuda.synchronize()
+    w.free()
+    g.free()
