@@ -429,8 +429,17 @@ def main():
                                                  a_["N"], a_["H"], a_["d"], a_["nk"], 8, ptr(a_["out"]),
                                                  ptr(a_["s"]), None, ptr(a_["ws"]),
                                                  C.c_size_t(a_["ws"].numel()), sp))
+            # the log quantizer without dynamic quantization: the scale is given (here: what the
+            # dynamic call just found), the kernel makes one pass over Q
+            s_own = torch.empty_like(a_["s"])
+            us_s = time_calls(L.dgq_xattn_logq_static, (ptr(a_["q"]), ptr(a_["k"]), ptr(a_["v"]), ptr(a_["kb"]),
+                                                        a_["B"], a_["N"], a_["H"], a_["d"], a_["nk"], 8,
+                                                        ptr(a_["s"]), ptr(a_["out"]), ptr(s_own), None, sp))
+            nominal = 2.0 * a_["B"] * a_["N"] * a_["H"] * a_["d"] * 4
             value_quant.append(dict(attention=a_["name"], v_bits=8, attn_bits=8,
-                                    us_quantize_value=round(us_v, 2), us_attention_on_v_hat=round(us_a, 2)))
+                                    us_quantize_value=round(us_v, 2), us_attention_on_v_hat=round(us_a, 2),
+                                    us_attention_given_scale=round(us_s, 2),
+                                    gbs_attention_given_scale=round(nominal / us_s / 1e3, 1)))
             del vhat
 
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------

@@ -293,6 +293,21 @@ const char *dgq_last_error(void);
 int dgq_version(void);
 
 /*
+ * The same attention with a GIVEN prompt scale: the log quantizer without dynamic
+ * quantization of the paper's ablation (Section 4.3), whose scale comes from calibration
+ * or from a running maximum over earlier denoising steps.  scale_in: fp32 [B].  With the
+ * scale known beforehand the two passes of dgq_xattn_logq collapse into one kernel and Q
+ * is read once; probabilities above the scale saturate at code 0.  scale_out: NULL, or
+ * fp32 [B] (not scale_in) receiving this call's own maximum, e.g. to update a running
+ * estimate.  No workspace.  Everything else as in dgq_xattn_logq; with scale_in equal to
+ * what dgq_xattn_logq reports, codes and product are the same bit for bit.
+ */
+int dgq_xattn_logq_static(const float *q, const float *k, const float *v,
+                          const float *key_bias, int32_t B, int32_t N, int32_t H, int32_t d,
+                          int32_t nk, int32_t attn_bits, const float *scale_in, float *out,
+                          float *scale_out, uint8_t *codes_dump, void *stream);
+
+/*
  * The quantized value tensor V^ of the attention product A^ V^ (Section 3.3).  Every
  * (prompt, head) slice V[b, :, h, :] goes through the linear quantizer of Section 3.1
  * with its own range:

@@ -233,7 +233,7 @@ def attn_probs(Q, K, key_bias=None):
     return A
 
 
-def xattn_logq(A, V, bits: int, want_ahat: bool = False):
+def xattn_logq(A, V, bits: int, want_ahat: bool = False, s_in=None):
     """A [B,H,N,nk] fp32, V [B,nk,H,d] -> dict(s, codes, margin, ahat, out [B,N,H,d])."""
     A = _f32(A)
     V = _f32(V)
@@ -244,9 +244,16 @@ def xattn_logq(A, V, bits: int, want_ahat: bool = False):
     margin = np.zeros((B, H, N, nk - 1), dtype=np.float32)
     ahat = np.zeros((B, H, N, nk), dtype=np.float64) if want_ahat else None
     out = np.zeros((B, N, H, d), dtype=np.float32)
-    lib().dgqo_xattn_logq(_p(A), _p(V), C.c_int32(B), C.c_int32(N), C.c_int32(H),
-                          C.c_int32(d), C.c_int32(nk), C.c_int32(bits), _p(s), _p(codes),
-                          _p(margin), _p(ahat), _p(out))
+    if s_in is None:
+        lib().dgqo_xattn_logq(_p(A), _p(V), C.c_int32(B), C.c_int32(N), C.c_int32(H),
+                              C.c_int32(d), C.c_int32(nk), C.c_int32(bits), _p(s), _p(codes),
+                              _p(margin), _p(ahat), _p(out))
+    else:
+        s_in = _f32(s_in)
+        assert s_in.shape == (B,)
+        lib().dgqo_xattn_logq_static(_p(A), _p(V), C.c_int32(B), C.c_int32(N), C.c_int32(H),
+                                     C.c_int32(d), C.c_int32(nk), C.c_int32(bits), _p(s_in), _p(s),
+                                     _p(codes), _p(margin), _p(ahat), _p(out))
     return dict(s=s, codes=codes, margin=margin, ahat=ahat, out=out)
 
 
@@ -262,8 +269,9 @@ def quantize_value(V, bits: int = 8):
     return dict(vhat=vhat, codes=codes, params=params)
 
 
-def xattn(Q, K, V, key_bias, bits: int, want_ahat: bool = False):
+def xattn(Q, K, V, key_bias, bits: int, want_ahat: bool = False, s_in=None):
+    """s_in [B]: a given (static) scale instead of the call's own maximum."""
     A = attn_probs(Q, K, key_bias)
-    r = xattn_logq(A, V, bits, want_ahat)
+    r = xattn_logq(A, V, bits, want_ahat, s_in=s_in)
     r["A"] = A
     return r

@@ -732,10 +732,10 @@ void dgqo_attn_probs(const float *Q, const float *K, const float *kb, int32_t B,
  *          to the nearest rounding boundary k + 1/2, k = 0 .. 2^bits - 2
  *   ahat   [B,H,N,nk]   (nullable) in double
  */
-void dgqo_xattn_logq(const float *A, const float *V, int32_t B, int32_t N,
-                     int32_t H, int32_t d, int32_t nk, int32_t bits,
-                     float *s_out, uint8_t *codes, float *margin, double *ahat,
-                     float *out)
+static void dgqo_xattn_logq_impl(const float *A, const float *V, int32_t B, int32_t N,
+                                 int32_t H, int32_t d, int32_t nk, int32_t bits,
+                                 const float *s_in, float *s_out, uint8_t *codes,
+                                 float *margin, double *ahat, float *out)
 {
     const int32_t qmax = (1 << bits) - 1;
     double *acc = (double *)malloc(sizeof(double) * (size_t)d);
@@ -747,7 +747,8 @@ void dgqo_xattn_logq(const float *A, const float *V, int32_t B, int32_t N,
                 for (int32_t j = 1; j < nk; ++j)
                     if (a[j] > s) s = a[j];
             }
-        s_out[b] = s;
+        s_out[b] = s;            /* this call's own maximum, whichever scale is used */
+        if (s_in) s = s_in[b];   /* static scale: given, e.g. a running max of earlier calls */
         for (int32_t h = 0; h < H; ++h)
             for (int32_t i = 0; i < N; ++i) {
                 const int64_t row = ((int64_t)b * H + h) * N + i;
@@ -788,6 +789,28 @@ void dgqo_xattn_logq(const float *A, const float *V, int32_t B, int32_t N,
             }
     }
     free(acc);
+}
+
+void dgqo_xattn_logq(const float *A, const float *V, int32_t B, int32_t N,
+                     int32_t H, int32_t d, int32_t nk, int32_t bits,
+                     float *s_out, uint8_t *codes, float *margin, double *ahat,
+                     float *out)
+{
+    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, NULL, s_out, codes, margin, ahat, out);
+}
+
+/*
+ * The log quantizer without dynamic quantization (the ablation of Section 4.3): the scale
+ * s[b] is GIVEN (calibrated, or a running maximum of earlier denoising steps) instead of
+ * being this call's maximum.  Probabilities above s saturate at code 0, i.e. at s.
+ * s_out still receives this call's own maximum (what a running estimate is updated with).
+ */
+void dgqo_xattn_logq_static(const float *A, const float *V, int32_t B, int32_t N,
+                            int32_t H, int32_t d, int32_t nk, int32_t bits,
+                            const float *s_in, float *s_out, uint8_t *codes, float *margin,
+                            double *ahat, float *out)
+{
+    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, s_in, s_out, codes, margin, ahat, out);
 }
 
 /* ------------------------------------------------------------------------- */

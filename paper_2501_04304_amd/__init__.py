@@ -70,6 +70,8 @@ def lib():
                                      vp, sz, vp]
         L.dgq_xattn_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.dgq_quantize_value.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+        L.dgq_xattn_logq_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
+                                            vp, vp]
         L.dgq_xattn_workspace_bytes.restype = sz
         L.dgq_last_error.restype = C.c_char_p
         L.dgq_version.restype = C.c_int
@@ -324,3 +326,24 @@ def dgq_quantize_value(v, v_bits: int = 8, v_hat=None, want_codes: bool = False,
                                     _ptr(codes) if codes is not None else None,
                                     _ptr(params) if params is not None else None, _stream(stream)))
     return v_hat, codes, params
+
+
+def dgq_xattn_logq_static(q, k, v, key_bias, attn_bits: int, scale_in, out=None, scale_out=None,
+                          codes_dump=None, stream=None):
+    """Attention with a given prompt scale (one pass).  Returns (out, scale_out or None)."""
+    import torch
+    _dev(q, torch.float32, "q")
+    _dev(k, torch.float32, "k")
+    _dev(v, torch.float32, "v")
+    _dev(scale_in, torch.float32, "scale_in")
+    B, N, H, d = q.shape
+    nk = k.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib().dgq_xattn_logq_static(_ptr(q), _ptr(k), _ptr(v),
+                                       _ptr(key_bias) if key_bias is not None else None, B, N, H, d,
+                                       nk, attn_bits, _ptr(scale_in), _ptr(out),
+                                       _ptr(scale_out) if scale_out is not None else None,
+                                       _ptr(codes_dump) if codes_dump is not None else None,
+                                       _stream(stream)))
+    return out, scale_out

@@ -746,7 +746,30 @@ int dgq_xattn_logq(const float *q, const float *k, const float *v, const float *
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace)))
         return fail(DGQ_EWORKSPACE, "dgq_xattn_logq: workspace missing, too small or misaligned");
     DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
-                         workspace, static_cast<hipStream_t>(stream)));
+                         workspace, nullptr, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+int dgq_xattn_logq_static(const float *q, const float *k, const float *v, const float *key_bias,
+                          int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t attn_bits,
+                          const float *scale_in, float *out, float *scale_out, uint8_t *codes_dump,
+                          void *stream) {
+    if (!q || !k || !v || !out || !scale_in)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq_static: null pointer");
+    if (B < 1 || N < 1 || H < 1) return fail(DGQ_EINVAL, "dgq_xattn_logq_static: empty tensor");
+    if (attn_bits != 4 && attn_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq_static: attn_bits must be 4 or 8");
+    if (nk < 2 || nk > 128 || d < 1 || d > 256)
+        return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_static: needs 2 <= nk <= 128 and 1 <= d <= 256");
+    if (B > 65535 || H > 65535)
+        return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_static: B or H above 65535");
+    if (scale_in == scale_out)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq_static: scale_in and scale_out must differ");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) ||
+        (key_bias && !aligned16(key_bias)))
+        return fail(DGQ_EALIGN, "dgq_xattn_logq_static: tensor not 16-byte aligned");
+    DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
+                         nullptr, scale_in, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 

@@ -116,7 +116,7 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
                         float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
-                        hipStream_t st);
+                        const float *scale_in, hipStream_t st);
 
 hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
                                  int32_t bits, float *vhat, uint8_t *codes, float *params,

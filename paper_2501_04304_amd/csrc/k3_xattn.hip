@@ -142,11 +142,15 @@ __device__ __host__ constexpr int key_of(int blk, int i, int hh) {
 }
 
 template <class CF, int PASS, bool DUMP>
-__global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
+__global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 2 : CF::WAVES_PER_SIMD) void k_xattn_mfma(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
     float qk_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
-    float *__restrict__ lse2, uint8_t *__restrict__ codes_dump) {
+    float *__restrict__ lse2, uint8_t *__restrict__ codes_dump,
+    const float *__restrict__ scale_in) {
+    // PASS 3: both passes in one, for a prompt scale that is GIVEN (scale_in): the soft-max
+    // statistics of a query block are taken and used at once, Q is read a single time, and
+    // `scale` (if not null) still collects this call's own maximum.
     constexpr int NKB = CF::NKB, KS = CF::KS, NKP = CF::NKP, DB = CF::DB, DP = CF::DP;
     constexpr int KROW = CF::KROW, VROW = CF::VROW;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -164,8 +168,8 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
 
     float s_b = 0.0f, s_eff = 1.0f, l2s = 0.0f;
     uint32_t pmask = 0xFFFFFFFFu;
-    if (PASS == 2) {
-        s_b = scale[b];
+    if (PASS >= 2) {
+        s_b = PASS == 3 ? scale_in[b] : scale[b];
         // no probability above zero outside the <start> column: only that column contributes
         s_eff = s_b > 0.0f ? s_b : 1.0f;
         pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;
@@ -191,7 +195,7 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             const int key = key_of(r >> 4, r & 15, half);
             biasv[idx] = key < nk ? (key_bias ? key_bias[key] * kLog2e : 0.0f) : -INFINITY;
         }
-        if (PASS == 2) {
+        if (PASS >= 2) {
             const float *vb = v + ((int64_t)b * nk * H + head) * d;
             for (int idx = tid; idx < NKP * (DP / 4); idx += kXThreads) {
                 const int j = idx / (DP / 4), t4 = (idx - j * (DP / 4)) * 4;
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             qh[s] = u32x4{p0.hi, p1.hi, p2.hi, p3.hi};
             ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
         }
-        const float lse_i = cur.lse;
+        float lse_i = cur.lse;
 
         // ---- S^T = K Q^T in log2 units --------------------------------------------------------
         v16f sm[NKB];
@@ -317,7 +321,8 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             cur = load_q(qn);
         }
 
-        if (PASS == 1) {
+        if (PASS == 1 || PASS == 3) {
+            if (PASS == 3) __builtin_amdgcn_sched_barrier(0);
             // ---- soft-max statistics of the lane's query ---------------------------------------
             float rest = -INFINITY;  // every key of this lane except register (0, 0)
 #pragma unroll
@@ -339,9 +344,13 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
             const float lse = m + __log2f(sum);
             if (valid) {
                 run_l2 = fmaxf(run_l2, m1 - lse);
-                if (hh == 0) lse2[((int64_t)b * H + head) * N + qi] = lse;
+                if (PASS == 1 && hh == 0) lse2[((int64_t)b * H + head) * N + qi] = lse;
             }
-            continue;
+            if (PASS == 1) continue;
+            lse_i = lse;
+            // keep the statistics and the code generation apart: interleaved, both hold
+            // their temporaries next to the 48 logits and the register file overflows
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // ---- pass 2: codes -> bf16 powers of two, packed as the next B operand --------------
@@ -447,7 +456,7 @@ __global__ __launch_bounds__(kXThreads, CF::WAVES_PER_SIMD) void k_xattn_mfma(
         }
     }
 
-    if (PASS == 1) {
+    if (PASS == 1 || (PASS == 3 && scale != nullptr)) {
         float amax = wave_max(run_l2);
         if (lane == 0) red[wave] = amax;
         __syncthreads();
@@ -466,7 +475,7 @@ template <class CF>
 hipError_t launch_mfma(const float *q, const float *k, const float *v, const float *key_bias,
                        int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
                        float *out, float *scale_out, uint8_t *codes_dump, float *lse2,
-                       hipStream_t st) {
+                       const float *scale_in, hipStream_t st) {
     auto k1 = k_xattn_mfma<CF, 1, false>;
     auto k2 = codes_dump ? k_xattn_mfma<CF, 2, true> : k_xattn_mfma<CF, 2, false>;
     hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k1), (int)CF::lds_pass1);
@@ -489,11 +498,21 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     const int32_t qpw = (int32_t)per_piece;
     const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B);
     const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
+    if (scale_in) {  // given scale: one kernel, Q read once
+        auto k3 = codes_dump ? k_xattn_mfma<CF, 3, true> : k_xattn_mfma<CF, 3, false>;
+        e = ensure_dynamic_lds(reinterpret_cast<const void *>(k3), (int)CF::lds_pass2);
+        if (e != hipSuccess) return e;
+        if (scale_out)
+            hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
+        hipLaunchKernelGGL(k3, grid, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d,
+                           nk, bits, qk_scale, qpw, out, scale_out, nullptr, codes_dump, scale_in);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
     hipLaunchKernelGGL(k1, grid, dim3(kXThreads), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump);
+                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump, nullptr);
     hipLaunchKernelGGL(k2, grid, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump);
+                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump, nullptr);
     return hipGetLastError();
 }
 
@@ -519,7 +538,7 @@ __global__ __launch_bounds__(256) void k_xattn(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t dpad, int32_t nk,
     int32_t bits, float inv_sqrt_d, float *__restrict__ out, float *__restrict__ scale,
-    uint8_t *__restrict__ codes_dump) {
+    uint8_t *__restrict__ codes_dump, const float *__restrict__ scale_in) {
     extern __shared__ float kv[];  // [NKP][dpad]
     __shared__ float red[4];
     const int32_t b = blockIdx.z, h = blockIdx.y;
@@ -589,7 +608,7 @@ __global__ __launch_bounds__(256) void k_xattn(
     }
 
     // ---- pass 2: codes and de-quantized probabilities --------------------------------
-    const float s = scale[b];
+    const float s = scale_in ? scale_in[b] : scale[b];  // given, or this call's maximum
     const float l2s = __log2f(s);
     const float lse2 = __log2f(sum);
     const float qmax = (float)((1 << bits) - 1);
@@ -690,7 +709,8 @@ __global__ __launch_bounds__(256) void k_quantize_value(
 template <int NKP>
 hipError_t launch_passes(const float *q, const float *k, const float *v, const float *key_bias,
                          int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
-                         float *out, float *scale_out, uint8_t *codes_dump, hipStream_t st) {
+                         float *out, float *scale_out, uint8_t *codes_dump,
+                         const float *scale_in, hipStream_t st) {
     const int32_t dpad = (d + 3) / 4 * 4;
     const size_t lds = sizeof(float) * (size_t)NKP * dpad;
     const float inv_sqrt_d = (float)(1.0 / sqrt((double)d));
@@ -704,11 +724,14 @@ hipError_t launch_passes(const float *q, const float *k, const float *v, const f
         if (e != hipSuccess) return e;
     }
     // scale_out accumulates a maximum: clear it with a fill kernel (capturable in a graph)
-    hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
-    hipLaunchKernelGGL(k1, grid, dim3(256), lds, st, q, k, v, key_bias, N, H, d, dpad, nk, bits,
-                       inv_sqrt_d, out, scale_out, codes_dump);
+    // the first pass collects this call's maximum (with a given scale only if it is asked for)
+    if (scale_out) {
+        hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
+        hipLaunchKernelGGL(k1, grid, dim3(256), lds, st, q, k, v, key_bias, N, H, d, dpad, nk, bits,
+                           inv_sqrt_d, out, scale_out, codes_dump, nullptr);
+    }
     hipLaunchKernelGGL(k2, grid, dim3(256), lds, st, q, k, v, key_bias, N, H, d, dpad, nk, bits,
-                       inv_sqrt_d, out, scale_out, codes_dump);
+                       inv_sqrt_d, out, scale_out, codes_dump, scale_in);
     return hipGetLastError();
 }
 
@@ -732,7 +755,7 @@ hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
                         float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
-                        hipStream_t st) {
+                        const float *scale_in, hipStream_t st) {
     if (mfma_shape(d, nk)) {
         float *lse2 = static_cast<float *>(workspace);
         const int ks = d <= 48 ? 3 : (d <= 64 ? 4 : 6);
@@ -740,7 +763,7 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
 #define DGQ_XATTN_CASE(NKB, KS)                                                              \
     if (nkb == NKB && ks == KS)                                                              \
         return launch_mfma<XCfg<NKB, KS>>(q, k, v, key_bias, B, N, H, d, nk, bits, out,       \
-                                          scale_out, codes_dump, lse2, st);
+                                          scale_out, codes_dump, lse2, scale_in, st);
         DGQ_XATTN_CASE(3, 3)
         DGQ_XATTN_CASE(3, 4)
         DGQ_XATTN_CASE(3, 6)
@@ -751,9 +774,9 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
     }
     if (nk <= 80)
         return launch_passes<80>(q, k, v, key_bias, B, N, H, d, nk, bits, out, scale_out,
-                                 codes_dump, st);
+                                 codes_dump, scale_in, st);
     return launch_passes<128>(q, k, v, key_bias, B, N, H, d, nk, bits, out, scale_out, codes_dump,
-                              st);
+                              scale_in, st);
 }
 
 }  // namespace dgq

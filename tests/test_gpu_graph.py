@@ -33,7 +33,9 @@ def test_captured_step_replays_like_eager(dgq):
     g = dgq.dgq_calibrate_groups(_dev(cal["X"]), 8, 64, 2)
     w = dgq.dgq_pack_weight(g, _dev(run["W"]), None, 8)
     M, O = x.shape[0], run["W"].shape[0]
-    codes = torch.empty(dgq.codes_shape(g, M), dtype=torch.int8, device="cuda")
+    # zeros, not empty: the rows of the last 32-row block beyond M are never written, and
+    # the comparison below is over the whole buffer
+    codes = torch.zeros(dgq.codes_shape(g, M), dtype=torch.int8, device="cuda")
     cls = torch.empty(M, dtype=torch.uint8, device="cuda")
     y = torch.empty((M, O), dtype=torch.float32, device="cuda")
     q, k, v, kb = (_dev(att[n]) for n in ("Q", "K", "V", "key_bias"))
@@ -69,8 +71,9 @@ def test_captured_step_replays_like_eager(dgq):
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((codes, cls, y, vhat, out, s), want):
-            assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
+        for name, got, ref in zip(("codes", "row_class", "y", "v_hat", "out", "scale"),
+                                  (codes, cls, y, vhat, out, s), want):
+            assert torch.equal(got, ref), "replay %d: %s differs from the eager result" % (rep, name)
         if rep == 1:                       # and an eager call in between
             step()
             torch.cuda.synchronize()

@@ -148,3 +148,40 @@ def test_scale_buffer_is_reset_between_calls(dgq, oracle):
         torch.cuda.synchronize()
         ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8)
         assert abs(s.item() - ref["s"][0]) <= S_RTOL * ref["s"][0]
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("B,N,H,d,nk", [(2, 300, 3, 40, 77), (1, 64, 2, 64, 77), (2, 70, 2, 37, 77),
+                                        (1, 40, 2, 40, 100), (3, 1, 1, 16, 2)])
+def test_given_scale_one_pass(dgq, oracle, B, N, H, d, nk, bits):
+    """The log quantizer without dynamic quantization (a given prompt scale): against the
+    oracle with the same scale; with the dynamic call's own scale it reproduces that call
+    bit for bit; it reports the call's own maximum all the same."""
+    import torch
+    from oracle.guard import DELTA, guarded_attention_case
+    c, _ = guarded_attention_case(700 + d + nk, B, N, H, d, nk=nk, bits_list=(bits,))
+    out_dyn, s_dyn, codes_dyn = _gpu(dgq, c, bits)
+    dev = [_dev(c[n]) for n in ("Q", "K", "V", "key_bias")]
+    codes = torch.full((B, H, N, nk - 1), 0xEE, dtype=torch.uint8, device="cuda")
+    s_own = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+    out, _ = dgq.dgq_xattn_logq_static(*dev, bits, _dev(s_dyn), scale_out=s_own, codes_dump=codes)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), codes_dyn)
+    assert np.array_equal(out.cpu().numpy(), out_dyn)
+    assert np.array_equal(s_own.cpu().numpy(), s_dyn)
+    # a scale from elsewhere (here: 0.6 and 1.7 times the maximum), with and without the
+    # request for the own maximum
+    for f in (0.6, 1.7):
+        s_in = (s_dyn * np.float32(f)).astype(np.float32)
+        ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], bits, s_in=s_in)
+        codes.fill_(0xEE)
+        out, _ = dgq.dgq_xattn_logq_static(*dev, bits, _dev(s_in), codes_dump=codes)
+        torch.cuda.synchronize()
+        safe = ref["margin"] >= DELTA
+        got = codes.cpu().numpy()
+        assert np.array_equal(got[safe], ref["codes"][safe])
+        assert np.abs(got.astype(int) - ref["codes"].astype(int)).max() <= 1
+        good = np.transpose(safe.all(-1), (0, 2, 1))  # [B, N, H]: rows without a marginal code
+        err = np.abs(out.cpu().numpy() - ref["out"])[good]
+        assert err.size and err.max() <= 1e-4 * np.abs(ref["out"]).max()
+        assert np.all(np.abs(ref["s"] - s_dyn) <= S_RTOL * s_dyn)

@@ -156,3 +156,32 @@ def test_redraw_changes_only_selected_queries():
     same = np.all(base["Q"] == c["Q"], axis=-1)
     assert not same[1, 3, 0] and same.sum() == same.size - 1
     assert np.array_equal(base["K"], c["K"]) and np.array_equal(base["V"], c["V"])
+
+
+def test_given_scale(oracle):
+    """The log quantizer without dynamic quantization: with the call's own maximum as the
+    given scale nothing changes; a scale 2^k times larger shifts every unclamped code by k
+    (log2 of a power of two is exact); probabilities above the scale saturate at the scale;
+    the call's own maximum is reported whatever scale is used."""
+    import dgq_inputs as di
+    c = di.attention_case(606, 2, 48, 2, 16, nk=20, d_ctx=32)
+    dyn = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8, want_ahat=True)
+    same = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8, s_in=dyn["s"])
+    assert np.array_equal(same["codes"], dyn["codes"]) and np.array_equal(same["out"], dyn["out"])
+    for k in (1, 3):
+        big = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8, s_in=dyn["s"] * np.float32(2 ** k))
+        want = np.minimum(dyn["codes"].astype(int) + k, 255)
+        assert np.array_equal(big["codes"].astype(int), want)
+        assert np.array_equal(big["s"], dyn["s"])
+    small = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8, s_in=dyn["s"] * np.float32(0.25),
+                         want_ahat=True)
+    assert np.array_equal(small["codes"].astype(int), np.maximum(dyn["codes"].astype(int) - 2, 0))
+    B = c["Q"].shape[0]
+    for b in range(B):
+        s_in = float(dyn["s"][b]) * 0.25
+        above = dyn["A"][b][..., 1:] > s_in
+        assert above.any()
+        assert np.all(small["codes"][b][above] == 0)
+        assert np.all(small["ahat"][b][..., 1:][above] == np.float32(s_in))
+        # the <start> column is never quantized
+        assert np.array_equal(small["ahat"][b][..., 0], dyn["A"][b][..., 0].astype(np.float64))
