@@ -252,6 +252,40 @@ int dgq_linear(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes
 int dgq_linear_geglu(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes,
                      const uint8_t *row_class, int64_t rows, float *y, void *stream);
 
+/*
+ * Two feed-forward layers chained without the fp32 activation between them: the gated
+ * layer's epilogue puts out[r,c] = a[r,c] * GELU(b[r,c]) (as in dgq_linear_geglu) straight
+ * through the FOLLOWING layer's activation quantizer (Section 3.1's linear quantizer with
+ * that layer's group-wise static (s_k, z_k), Section 3.3) and writes that layer's codes.
+ * The following layer must be grouped along the channel dimension only (one pixel class:
+ * dgq_calibrate_kmeans with the channel dimension, or dgq_calibrate_groups with
+ * n_pixel_classes = 1), so that a code depends on nothing but its own value and its
+ * channel's group, and must use 8-bit codes.
+ *
+ * dgq_pack_weight_gated_for (offline, blocking): as dgq_pack_weight for layer g, whose
+ * out_channels = 2 * (channels of g_next) rows of w are [value rows | gate rows]; the
+ * packed rows are reordered into g_next's permuted, padded K' order so that the epilogue's
+ * output columns are g_next's code positions, and the handle keeps a copy of g_next's
+ * per-chunk (z, 1/s) and padding mask (g_next may be freed afterwards).  The handle is
+ * accepted by dgq_linear_geglu_requant only.
+ *
+ * dgq_linear_geglu_requant (hot call; enqueues on `stream`, neither synchronises nor
+ * allocates):
+ *   codes, row_class: of layer g, as written by dgq_quantize_act
+ *   codes_next: dgq_codes_bytes(g_next, rows) bytes; receives exactly what
+ *               dgq_quantize_act(g_next, out) would write (stored code = q - 128, padding
+ *               positions 0, rows past `rows` in the last 16-row block untouched), up to
+ *               the rounding of out: a code whose pre-rounding value (out - z) / s lies
+ *               within the fp32 error of out of a half-integer may differ by one
+ *   row_class_next: u8 [rows], receives zeros (the single pixel class)
+ */
+int dgq_pack_weight_gated_for(const dgq_groups_t *g, const dgq_groups_t *g_next,
+                              const float *w, const float *bias, int32_t out_channels,
+                              int32_t w_bits, void *stream, dgq_weight_t **out);
+int dgq_linear_geglu_requant(const dgq_groups_t *g, const dgq_weight_t *w,
+                             const int8_t *codes, const uint8_t *row_class, int64_t rows,
+                             int8_t *codes_next, uint8_t *row_class_next, void *stream);
+
 size_t dgq_linear_workspace_bytes(const dgq_groups_t *g, const dgq_weight_t *w,
                                   int64_t rows);
 

@@ -62,6 +62,8 @@ def lib():
         L.dgq_quantize_act.argtypes = [vp, vp, i64, vp, vp, vp]
         L.dgq_linear.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
         L.dgq_linear_geglu.argtypes = [vp, vp, vp, vp, i64, vp, vp]
+        L.dgq_pack_weight_gated_for.argtypes = [vp, vp, vp, vp, i32, i32, vp, C.POINTER(vp)]
+        L.dgq_linear_geglu_requant.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp]
         L.dgq_codes_bytes.argtypes = [vp, i64]
         L.dgq_codes_bytes.restype = sz
         L.dgq_linear_workspace_bytes.argtypes = [vp, vp, i64]
@@ -203,6 +205,23 @@ def dgq_pack_weight(groups: Groups, w, bias, w_bits: int, stream=None) -> Weight
     return Weight(handle=h.value, groups=groups, out_channels=O, w_bits=w_bits)
 
 
+def dgq_pack_weight_gated_for(groups: Groups, next_groups: Groups, w, bias, w_bits: int,
+                              stream=None) -> Weight:
+    """Weights [value rows | gate rows] of a gated layer whose output is the input of the
+    layer `next_groups` describes; for dgq_linear_geglu_requant."""
+    import torch
+    _dev(w, torch.float32, "w")
+    if bias is not None:
+        _dev(bias, torch.float32, "bias")
+    O, ch = w.shape
+    if ch != groups.info.channels:
+        raise ValueError("w has %d input channels, the groups have %d" % (ch, groups.info.channels))
+    h = C.c_void_p()
+    _check(lib().dgq_pack_weight_gated_for(groups.handle, next_groups.handle, _ptr(w), _ptr(bias), O,
+                                           w_bits, _stream(stream), C.byref(h)))
+    return Weight(handle=h.value, groups=groups, out_channels=O, w_bits=w_bits)
+
+
 def codes_shape(groups: Groups, rows: int):
     """Shape of the block-tiled code buffer: [row blocks, chunks, 1024 bytes]."""
     n_chunks = groups.info.k_padded // DGQ_K_GRANULE
@@ -271,6 +290,31 @@ def dgq_linear_geglu(groups: Groups, weight: Weight, codes, row_class, y=None, s
     _check(lib().dgq_linear_geglu(groups.handle, weight.handle, _ptr(codes), _ptr(row_class),
                                   rows, _ptr(y), _stream(stream)))
     return y
+
+
+def dgq_linear_geglu_requant(groups: Groups, weight: Weight, codes, row_class, next_groups: Groups,
+                             codes_next=None, row_class_next=None, stream=None):
+    """Returns (codes_next, row_class_next): the following layer's codes of
+    value * GELU(gate), in the layout of dgq_quantize_act(next_groups, .)."""
+    import torch
+    _dev(codes, torch.int8, "codes")
+    _dev(row_class, torch.uint8, "row_class")
+    rows = row_class.numel()
+    if tuple(codes.shape) != codes_shape(groups, rows):
+        raise ValueError("codes / row_class have the wrong shape")
+    shape = codes_shape(next_groups, rows)
+    if codes_next is None:
+        codes_next = torch.empty(shape, dtype=torch.int8, device=codes.device)
+    if row_class_next is None:
+        row_class_next = torch.empty(rows, dtype=torch.uint8, device=codes.device)
+    _dev(codes_next, torch.int8, "codes_next")
+    _dev(row_class_next, torch.uint8, "row_class_next")
+    if tuple(codes_next.shape) != shape or row_class_next.numel() != rows:
+        raise ValueError("codes_next / row_class_next have the wrong shape")
+    _check(lib().dgq_linear_geglu_requant(groups.handle, weight.handle, _ptr(codes), _ptr(row_class),
+                                          rows, _ptr(codes_next), _ptr(row_class_next),
+                                          _stream(stream)))
+    return codes_next, row_class_next
 
 
 def dgq_xattn_workspace_bytes(B, N, H, d, nk) -> int:

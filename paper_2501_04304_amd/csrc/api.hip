@@ -267,6 +267,8 @@ void release(Weight *w) {
     (void)hipFree(w->d_wq);
     (void)hipFree(w->d_sw);
     (void)hipFree(w->d_zb);
+    (void)hipFree(w->d_rq_zi);
+    (void)hipFree(w->d_rq_keep);
     delete w;
 }
 
@@ -594,6 +596,73 @@ void dgq_groups_free(dgq_groups_t *h) {
     release(reinterpret_cast<Groups *>(h));
 }
 
+namespace {
+
+// Packs w for the layer described by g.  With `next` (a following layer with one pixel
+// class and 8-bit codes whose input is this layer's gated output) the packed rows are in
+// that layer's K' order -- value rows for positions 0 .. K'_next - 1, then the gate rows of
+// the same positions, all-zero rows at padding positions -- and the handle carries the
+// per-chunk (offset, 1 / step) and the padding mask of that layer's quantizer.
+int pack_weight(const char *who, const Groups *g, const Groups *next, const float *w,
+                const float *bias, int32_t out_channels, int32_t w_bits, hipStream_t st,
+                dgq_weight_t **out) {
+    Weight *wt = new (std::nothrow) Weight();
+    if (!wt) return fail(DGQ_EINVAL, std::string(who) + ": out of host memory");
+    wt->groups = g;
+    wt->O = next ? 2 * next->info.k_padded : out_channels;
+    wt->O_pad = (wt->O + kTileO - 1) / kTileO * kTileO;
+    wt->C = g->info.channels;
+    wt->Kp = g->info.k_padded;
+    wt->w_bits = w_bits;
+    (void)hipGetDevice(&wt->device);
+    DevBuf row_map;
+    hipError_t e = hipSuccess;
+    if (next) {
+        const int32_t kn = next->info.k_padded, half = out_channels / 2;
+        wt->next_channels = half;
+        wt->next_kp = kn;
+        std::vector<int32_t> map((size_t)2 * kn);
+        std::vector<uint8_t> keep((size_t)kn);
+        std::vector<float2> zi((size_t)next->n_chunks);
+        for (int32_t j = 0; j < kn; ++j) {
+            const int32_t c = next->perm[j];
+            map[j] = c;
+            map[(size_t)kn + j] = c < 0 ? -1 : half + c;
+            keep[j] = c < 0 ? 0 : 0xFF;
+        }
+        const int32_t NG = (int32_t)next->glen.size();
+        for (int32_t k = 0; k < NG; ++k)
+            for (int32_t ch = next->goff[k] / kGranule; ch < next->goff[k + 1] / kGranule; ++ch)
+                zi[ch] = make_float2(next->z[k], next->inv_s[k]);  // class row 0
+        e = row_map.alloc(map.size() * sizeof(int32_t));
+        if (e == hipSuccess)
+            e = hipMemcpy(row_map.p, map.data(), map.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&wt->d_rq_zi), zi.size() * sizeof(float2));
+        if (e == hipSuccess)
+            e = hipMemcpy(wt->d_rq_zi, zi.data(), zi.size() * sizeof(float2), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&wt->d_rq_keep), keep.size());
+        if (e == hipSuccess) e = hipMemcpy(wt->d_rq_keep, keep.data(), keep.size(), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&wt->d_wq), (size_t)wt->O_pad * wt->Kp);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&wt->d_sw), sizeof(float) * wt->O_pad);
+    if (e == hipSuccess)
+        e = hipMalloc(reinterpret_cast<void **>(&wt->d_zb), sizeof(float) * 2 * wt->O_pad);
+    if (e == hipSuccess)
+        e = launch_pack_weight(w, bias, wt->O, wt->O_pad, wt->C, wt->Kp, g->info.n_groups, w_bits,
+                               g->info.code_offset, g->d_perm, g->d_gchunk, g->d_s, g->d_z,
+                               g->n_tab, next ? row_map.as<int32_t>() : nullptr, wt->d_wq,
+                               wt->d_sw, wt->d_zb, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+        release(wt);
+        return hip_fail(e, who);
+    }
+    *out = reinterpret_cast<dgq_weight_t *>(wt);
+    return DGQ_OK;
+}
+
+}  // namespace
+
 int dgq_pack_weight(const dgq_groups_t *h, const float *w, const float *bias, int32_t out_channels,
                     int32_t w_bits, void *stream, dgq_weight_t **out) {
     if (!h || !w || !out) return fail(DGQ_EINVAL, "dgq_pack_weight: null pointer");
@@ -602,37 +671,40 @@ int dgq_pack_weight(const dgq_groups_t *h, const float *w, const float *bias, in
     if (w_bits != 4 && w_bits != 8) return fail(DGQ_EINVAL, "dgq_pack_weight: w_bits must be 4 or 8");
     if (!aligned16(w) || (bias && !aligned16(bias)))
         return fail(DGQ_EALIGN, "dgq_pack_weight: tensor not 16-byte aligned");
+    return pack_weight("dgq_pack_weight", reinterpret_cast<const Groups *>(h), nullptr, w, bias,
+                       out_channels, w_bits, static_cast<hipStream_t>(stream), out);
+}
+
+int dgq_pack_weight_gated_for(const dgq_groups_t *h, const dgq_groups_t *h_next, const float *w,
+                              const float *bias, int32_t out_channels, int32_t w_bits,
+                              void *stream, dgq_weight_t **out) {
+    if (!h || !h_next || !w || !out) return fail(DGQ_EINVAL, "dgq_pack_weight_gated_for: null pointer");
+    *out = nullptr;
+    if (out_channels < 2 || out_channels % 2)
+        return fail(DGQ_EINVAL, "dgq_pack_weight_gated_for: out_channels must be even (value and gate halves)");
+    if (w_bits != 4 && w_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_pack_weight_gated_for: w_bits must be 4 or 8");
+    if (!aligned16(w) || (bias && !aligned16(bias)))
+        return fail(DGQ_EALIGN, "dgq_pack_weight_gated_for: tensor not 16-byte aligned");
     const Groups *g = reinterpret_cast<const Groups *>(h);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    Weight *wt = new (std::nothrow) Weight();
-    if (!wt) return fail(DGQ_EINVAL, "dgq_pack_weight: out of host memory");
-    wt->groups = g;
-    wt->O = out_channels;
-    wt->O_pad = (out_channels + kTileO - 1) / kTileO * kTileO;
-    wt->C = g->info.channels;
-    wt->Kp = g->info.k_padded;
-    wt->w_bits = w_bits;
-    (void)hipGetDevice(&wt->device);
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&wt->d_wq), (size_t)wt->O_pad * wt->Kp);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&wt->d_sw), sizeof(float) * wt->O_pad);
-    if (e == hipSuccess)
-        e = hipMalloc(reinterpret_cast<void **>(&wt->d_zb), sizeof(float) * 2 * wt->O_pad);
-    if (e == hipSuccess)
-        e = launch_pack_weight(w, bias, wt->O, wt->O_pad, wt->C, wt->Kp, g->info.n_groups, w_bits,
-                               g->info.code_offset, g->d_perm, g->d_gchunk, g->d_s, g->d_z,
-                               g->n_tab, wt->d_wq, wt->d_sw, wt->d_zb, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) {
-        release(wt);
-        return hip_fail(e, "dgq_pack_weight");
-    }
-    *out = reinterpret_cast<dgq_weight_t *>(wt);
-    return DGQ_OK;
+    const Groups *next = reinterpret_cast<const Groups *>(h_next);
+    if (next->info.channels != out_channels / 2)
+        return fail(DGQ_ESHAPE, "dgq_pack_weight_gated_for: the following layer must take out_channels / 2 channels");
+    if (next->info.n_pixel_classes != 1 || next->info.act_bits != 8)
+        return fail(DGQ_EUNSUPPORTED,
+                    "dgq_pack_weight_gated_for: the following layer needs one pixel class (its "
+                    "quantizer must not depend on a row statistic) and 8-bit codes");
+    if (g->n_tab > 2)
+        return fail(DGQ_EUNSUPPORTED, "dgq_pack_weight_gated_for: this layer needs at most two pixel classes");
+    return pack_weight("dgq_pack_weight_gated_for", g, next, w, bias, out_channels, w_bits,
+                       static_cast<hipStream_t>(stream), out);
 }
 
 int dgq_weight_tables(const dgq_weight_t *h, int8_t *wq, float *sw) {
     if (!h) return fail(DGQ_EINVAL, "dgq_weight_tables: null handle");
     const Weight *w = reinterpret_cast<const Weight *>(h);
+    if (w->next_kp)
+        return fail(DGQ_EUNSUPPORTED, "dgq_weight_tables: rows of a weight packed for a following layer are not in the original order");
     if (sw) DGQ_HIP(hipMemcpy(sw, w->d_sw, sizeof(float) * w->O, hipMemcpyDeviceToHost));
     if (wq) {
         DevBuf tmp;
@@ -695,7 +767,9 @@ int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *code
         return fail(DGQ_EUNSUPPORTED, "dgq_linear: too many output tiles");
     if (g->n_tab > 2 && acc_dump)
         return fail(DGQ_EUNSUPPORTED, "dgq_linear: acc_dump needs at most two pixel classes");
-    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump, false,
+    if (w->next_kp)
+        return fail(DGQ_ESHAPE, "dgq_linear: weight was packed for dgq_linear_geglu_requant");
+    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump, 0, nullptr,
                           static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
@@ -709,6 +783,8 @@ int dgq_linear_geglu(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t
     const Weight *w = reinterpret_cast<const Weight *>(hw);
     if (w->groups != g)
         return fail(DGQ_ESHAPE, "dgq_linear_geglu: weight was packed for a different group handle");
+    if (w->next_kp)
+        return fail(DGQ_ESHAPE, "dgq_linear_geglu: weight was packed for dgq_linear_geglu_requant");
     if (w->O % 256 != 0)
         return fail(DGQ_EUNSUPPORTED,
                     "dgq_linear_geglu: out_channels must be a multiple of 256 (value and gate "
@@ -719,8 +795,29 @@ int dgq_linear_geglu(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t
         return fail(DGQ_EALIGN, "dgq_linear_geglu: tensor not 16-byte aligned");
     if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
         return fail(DGQ_EUNSUPPORTED, "dgq_linear_geglu: too many output tiles");
-    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, nullptr, true,
+    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, nullptr, 1, nullptr,
                           static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+int dgq_linear_geglu_requant(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *codes,
+                             const uint8_t *row_class, int64_t rows, int8_t *codes_next,
+                             uint8_t *row_class_next, void *stream) {
+    if (!h || !hw || !codes || !row_class || !codes_next || !row_class_next)
+        return fail(DGQ_EINVAL, "dgq_linear_geglu_requant: null pointer");
+    if (rows < 1) return fail(DGQ_EINVAL, "dgq_linear_geglu_requant: rows < 1");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    const Weight *w = reinterpret_cast<const Weight *>(hw);
+    if (w->groups != g)
+        return fail(DGQ_ESHAPE, "dgq_linear_geglu_requant: weight was packed for a different group handle");
+    if (!w->next_kp)
+        return fail(DGQ_ESHAPE, "dgq_linear_geglu_requant: weight was not packed by dgq_pack_weight_gated_for");
+    if (!aligned16(codes) || !aligned16(codes_next))
+        return fail(DGQ_EALIGN, "dgq_linear_geglu_requant: tensor not 16-byte aligned");
+    if ((rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear_geglu_requant: too many output tiles");
+    DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, reinterpret_cast<float *>(codes_next),
+                          nullptr, 2, row_class_next, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 

@@ -65,6 +65,12 @@ struct Weight {
     // [2][O_pad].  Two class rows: zb[p][o].  More than two classes (one channel group):
     // row 0 = sw[o] * sum_j wq[o,j], row 1 = bias[o]; zb[p][o] = zoff[p] * row 0 + row 1.
     float *d_zb = nullptr;
+    // Packed for a gated layer whose output feeds `next_channels` channels of a following
+    // layer directly: output rows are in that layer's K' order (value rows, then gate
+    // rows), and the two tables its quantizer needs travel with the weights.
+    int32_t next_channels = 0, next_kp = 0;
+    float2 *d_rq_zi = nullptr;     // [next_kp / 64] (offset, 1 / step) of each chunk
+    uint8_t *d_rq_keep = nullptr;  // [next_kp] 0xFF, or 0 at padding positions
     int device = 0;
 };
 
@@ -94,11 +100,14 @@ hipError_t launch_col_minmax_by_class(const float *x, int64_t rows, int32_t C,
                                       int32_t slabs, float *part, hipStream_t st);
 
 // Per-output-channel weight quantization into the K' layout plus the zero-point term.
+// row_map (optional, [O]): packed row o comes from row row_map[o] of w and bias, or is
+// all zero when that is negative.
 hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int32_t O_pad,
                               int32_t C, int32_t Kp, int32_t NG, int32_t w_bits,
                               int32_t code_offset, const int32_t *perm,
                               const int32_t *gchunk, const float *s, const float *z,
-                              int32_t n_classes, int8_t *wq, float *sw, float *zb, hipStream_t st);
+                              int32_t n_classes, const int32_t *row_map, int8_t *wq, float *sw,
+                              float *zb, hipStream_t st);
 
 // Inverse of the K' layout: wq_out [O][C] original order.
 hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t Kp,
@@ -107,11 +116,13 @@ hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t 
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
                                uint8_t *row_class, hipStream_t st);
 
-// geglu: y is [rows, O / 2] and receives value * GELU(gate) (first / second half of the
-// output channels); needs O % 256 == 0 and no accumulator dump.
+// geglu 1: y is [rows, O / 2] and receives value * GELU(gate) (first / second half of the
+// output channels); needs O % 128 == 0 and no accumulator dump.  geglu 2: the same value
+// goes through the following layer's quantizer; y is that layer's code buffer, rq_cls its
+// row classes, and w carries its tables.
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
-                         bool geglu, hipStream_t st);
+                         int geglu, uint8_t *rq_cls, hipStream_t st);
 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,

@@ -84,7 +84,8 @@ __global__ __launch_bounds__(256) void k_pack_weight(
     int32_t Kp, int32_t NG, int32_t w_bits, int32_t code_offset,
     const int32_t *__restrict__ perm, const int32_t *__restrict__ gchunk,
     const float *__restrict__ s, const float *__restrict__ z, int32_t n_classes,
-    int8_t *__restrict__ wq, float *__restrict__ sw, float *__restrict__ zb, int32_t O_pad) {
+    const int32_t *__restrict__ row_map, int8_t *__restrict__ wq, float *__restrict__ sw,
+    float *__restrict__ zb, int32_t O_pad) {
     extern __shared__ int32_t smem[];
     int32_t *gsum = smem;
     int32_t *chunk2grp = smem + NG;
@@ -96,7 +97,9 @@ __global__ __launch_bounds__(256) void k_pack_weight(
     auto at = [&](int32_t j) -> int8_t & {
         return wq[tiled64_offset(o, j >> 6, n_chunks, (j >> 4) & 3) + (j & 15)];
     };
-    if (o >= O) {  // padding rows: all-zero weights
+    // the row of w and bias behind packed row o: itself, or the one a row map names
+    const int32_t src = o >= O ? -1 : (row_map ? row_map[o] : o);
+    if (src < 0) {  // padding rows: all-zero weights
         for (int32_t j = tid; j < Kp; j += 256) at(j) = 0;
         if (tid == 0) {
             sw[o] = 0.0f;
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(
         gsum[g] = 0;
         for (int32_t ch = gchunk[g]; ch < gchunk[g + 1]; ++ch) chunk2grp[ch] = g;
     }
-    const float *wr = w + (int64_t)o * C;
+    const float *wr = w + (int64_t)src * C;
     float amax = 0.0f;
     for (int32_t c = tid; c < C; c += 256) {
         float a = fabsf(wr[c]);
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(
         // and the two class-independent rows are stored instead of one row per class
         if (tid == 0) {
             zb[o] = (float)((double)sc * (double)gsum[0]);
-            zb[O_pad + o] = bias ? bias[o] : 0.0f;
+            zb[O_pad + o] = bias ? bias[src] : 0.0f;
             sw[o] = sc;
         }
     } else if (tid < 2) {
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(256) void k_pack_weight(
             t += zo * (double)gsum[g];
         }
         double v = (double)sc * t;
-        if (bias) v += (double)bias[o];
+        if (bias) v += (double)bias[src];
         zb[p * O_pad + o] = (float)v;
         if (p == 0) sw[o] = sc;
     }
@@ -191,11 +194,12 @@ hipError_t launch_col_minmax_by_class(const float *x, int64_t rows, int32_t C, c
 hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int32_t O_pad,
                               int32_t C, int32_t Kp, int32_t NG, int32_t w_bits,
                               int32_t code_offset, const int32_t *perm, const int32_t *gchunk,
-                              const float *s, const float *z, int32_t n_classes, int8_t *wq,
-                              float *sw, float *zb, hipStream_t st) {
+                              const float *s, const float *z, int32_t n_classes,
+                              const int32_t *row_map, int8_t *wq, float *sw, float *zb,
+                              hipStream_t st) {
     const size_t lds = sizeof(int32_t) * (size_t)(NG + Kp / kGranule);
     hipLaunchKernelGGL(k_pack_weight, dim3(O_pad), dim3(256), lds, st, w, bias, O, C, Kp, NG,
-                       w_bits, code_offset, perm, gchunk, s, z, n_classes, wq, sw, zb, O_pad);
+                       w_bits, code_offset, perm, gchunk, s, z, n_classes, row_map, wq, sw, zb, O_pad);
     return hipGetLastError();
 }
 

@@ -126,19 +126,29 @@ struct Cfg {
 // y [rows, O/2] (the gated feed-forward of the transformer blocks), so the 2x wider
 // pre-activation never reaches memory.  Needs BO == 2 and O % (2 TO) == 0.
 //
+// GEGLU == 2 (gated + requantized): the tile's output channels are, in order, the K'
+// positions of the NEXT layer's channel groups (the weight rows were packed in that
+// order), that layer has one pixel class, and the epilogue puts value * GELU(gate) straight
+// through its quantizer: y is that layer's block-tiled 8-bit code buffer, rq_zi the
+// (offset, 1 / step) of each of its 64-position chunks, rq_keep one byte per position
+// (0xFF, or 0 for padding, whose stored code is 0), rq_cls its row classes (all 0).  The
+// fp32 activation between the two layers never reaches memory.
+//
 // MULTI: more than two pixel classes and ONE channel group (the pixel-dimension grouping
 // of Section 3.3).  The class of the row behind every accumulator register travels as a
 // 4-bit field; the single fold and the epilogue read that class's scale and offset from a
 // small LDS table, and the zero-point term is zoff[class] * (sw[o] * wsum[o]) + bias[o],
 // whose two class-independent rows arrive in place of zb[0] and zb[1].
-template <class CF, bool DUMP, bool GEGLU, bool MULTI>
+template <class CF, bool DUMP, int GEGLU, bool MULTI>
 __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int8_t *__restrict__ codes, const uint8_t *__restrict__ row_class,
     const int8_t *__restrict__ wq, const float *__restrict__ sw, const float *__restrict__ zb,
     const float *__restrict__ s_tab, const float *__restrict__ zoff_tab, int32_t P,
     const int32_t *__restrict__ gchunk, int64_t rows, int32_t O,
     int32_t O_pad, int32_t Kp, int32_t NG, int32_t tiles_r, int32_t tiles_o, int32_t per_xcd,
-    int32_t super_rows, float *__restrict__ y, int32_t *__restrict__ acc_dump) {
+    int32_t super_rows, float *__restrict__ y, int32_t *__restrict__ acc_dump,
+    const float2 *__restrict__ rq_zi, const uint8_t *__restrict__ rq_keep,
+    uint8_t *__restrict__ rq_cls) {
     constexpr int ABITS = CF::ABITS, BR = CF::BR, BO = CF::BO, STAGES = CF::STAGES;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -434,7 +444,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                 }
         }
         }
-        if constexpr (GEGLU) {
+        if constexpr (GEGLU != 0) {
             // block 0 holds the value, block 1 the gate of the same output channel:
             // out = value * gate * Phi(gate), written to y [rows, O / 2]
             const int32_t oh = O >> 1;
@@ -445,6 +455,43 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                 for (int i = 0; i < 16; ++i) {
                     facc[a][0][i] = facc[a][0][i] * gelu(facc[a][1][i]);
                 }
+            if constexpr (GEGLU == 2) {
+                // Quantize for the next layer (Section 3.1's linear quantizer with the
+                // chunk's static offset and step; same operations as the stand-alone
+                // quantizer) and store one byte per register.  Register i holds row
+                // 8 (i / 4) + 4 kh + i % 4 of the 32-row block: two 16-row code blocks,
+                // i / 8 apart; in its block the row is t = 8 (i / 4 % 2) + 4 kh + i % 4, whose
+                // slot swizzle is kh | 2 ((i / 2 ^ i / 4) % 2): one lane offset per value of
+                // the compile-time bit.
+                int8_t *cout = reinterpret_cast<int8_t *>(y);
+                const int32_t posw = (o0 >> 1) + wo * 32;  // first position of this wave
+                const int32_t nch2 = O >> 7, chunk = posw >> 6;
+                const float2 zi = rq_zi[chunk];
+                const uint32_t keep = rq_keep[posw + m32];
+                const uint32_t kq = (uint32_t)(((posw & 63) >> 4) + (m32 >> 4));
+                const uint32_t lane_off0 = (uint32_t)kh * 256u + (((kq ^ (uint32_t)kh)) << 4) + (uint32_t)(m32 & 15);
+                const uint32_t lane_off1 = (uint32_t)kh * 256u + (((kq ^ (uint32_t)kh ^ 2u)) << 4) + (uint32_t)(m32 & 15);
+#pragma unroll
+                for (int a = 0; a < BR; ++a) {
+                    const int64_t rb = (r0 + (wr * BR + a) * 32) >> 4;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float t = __fsub_rn(facc[a][0][i], zi.x);
+                        const float u = __fmul_rn(t, zi.y);
+                        const uint32_t q = (__builtin_amdgcn_cvt_pk_u8_f32(u, 0, 0u) ^ 0x80u) & keep;
+                        int8_t *blk = cout + (((rb + (i >> 3)) * nch2 + chunk) << 10) +
+                                      (8 * ((i >> 2) & 1) + (i & 3)) * 64;
+                        const uint32_t lo = (((i >> 1) ^ (i >> 2)) & 1) ? lane_off1 : lane_off0;
+                        if (!((past[a] >> i) & 1)) blk[lo] = (int8_t)q;
+                    }
+                }
+                // the column-0 tiles also write the next layer's row classes
+                if (o0 == 0 && wo == 0 && lane < 32 * BR) {
+                    const int64_t r = r0 + wr * BR * 32 + lane;
+                    if (r < rows) rq_cls[r] = 0;
+                }
+                return;
+            }
             if (r0 + CF::TR <= rows) {
                 const uint32_t lane_off = (uint32_t)(4 * kh * oh + m32) * 4u;
                 const int64_t row_bytes = (int64_t)oh * 4;
@@ -646,10 +693,10 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         run(std::false_type{});
 }
 
-template <class CF, bool DUMP, bool GEGLU = false, bool MULTI = false>
+template <class CF, bool DUMP, int GEGLU = 0, bool MULTI = false>
 hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
                       const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
-                      hipStream_t st) {
+                      hipStream_t st, uint8_t *rq_cls = nullptr) {
     const int32_t tiles_r = (int32_t)((rows + CF::TR - 1) / CF::TR);
     const int32_t tiles_o = (w.O + CF::TO - 1) / CF::TO;  // O_pad is a multiple of every TO
     const int64_t T = (int64_t)tiles_r * tiles_o;
@@ -657,8 +704,8 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     const dim3 grid((unsigned)(per_xcd * 8));
     size_t lds = (size_t)CF::STAGES * CF::STAGE_BYTES +
                  (MULTI ? 4 + 8 * (size_t)g.n_tab : 12 * (size_t)g.info.n_groups);
-    static_assert(!GEGLU || CF::BO == 2, "the gated epilogue pairs the two blocks of a wave");
-    static_assert(!(GEGLU && MULTI), "the gated epilogue is built for at most two pixel classes");
+    static_assert(GEGLU == 0 || CF::BO == 2, "the gated epilogue pairs the two blocks of a wave");
+    static_assert(!(GEGLU != 0 && MULTI), "the gated epilogue is built for at most two pixel classes");
     auto kern = k_linear<CF, DUMP, GEGLU, MULTI>;
     {
         hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kStageBudget);
@@ -680,7 +727,7 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
                        w.d_zb, g.d_s, g.d_zoff, g.n_tab, g.d_gchunk, rows, w.O, w.O_pad, w.Kp,
                        g.info.n_groups,
-                       tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump);
+                       tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump, w.d_rq_zi, w.d_rq_keep, rq_cls);
     return hipGetLastError();
 }
 
@@ -690,7 +737,7 @@ static int g_force_cfg = -1;  // tuning hook: environment variable DGQ_LINEAR_CF
 
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
-                         bool geglu, hipStream_t st) {
+                         int geglu, uint8_t *rq_cls, hipStream_t st) {
     static bool env_read = false;
     if (!env_read) {
         if (const char *e = getenv("DGQ_LINEAR_CFG")) g_force_cfg = atoi(e);
@@ -699,6 +746,7 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     const bool a8 = g.info.act_bits == 8;
     const bool multi = g.n_tab > 2;  // more than two pixel classes (one channel group)
     if (multi && (geglu || acc_dump || g.info.n_groups != 1)) return hipErrorInvalidValue;
+    if (geglu == 2 && (!w.d_rq_zi || !w.d_rq_keep || !rq_cls)) return hipErrorInvalidValue;
     if (acc_dump) {
         return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
                   : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
@@ -715,9 +763,12 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     if (g_force_cfg >= 0) cfg = g_force_cfg;
 #define DGQ_CASE(ID, ...)                                                                          \
     case ID:                                                                                       \
+        if (geglu == 2)                                                                            \
+            return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, 2>(g, w, codes, row_class, rows, y, nullptr, st, rq_cls) \
+                      : launch_cfg<Cfg<4, __VA_ARGS__>, false, 2>(g, w, codes, row_class, rows, y, nullptr, st, rq_cls); \
         if (geglu)                                                                                 \
-            return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, true>(g, w, codes, row_class, rows, y, nullptr, st) \
-                      : launch_cfg<Cfg<4, __VA_ARGS__>, false, true>(g, w, codes, row_class, rows, y, nullptr, st); \
+            return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st) \
+                      : launch_cfg<Cfg<4, __VA_ARGS__>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st); \
         if (multi)                                                                                 \
             return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st) \
                       : launch_cfg<Cfg<4, __VA_ARGS__>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st); \
@@ -728,9 +779,12 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         case 6:  // 64 x 64 behind an 8-stage ring: 4 waves of 32 x 32 (13-15 % faster on the
                  // 1232-row projections than 2 waves of 32 x 64); the gated epilogue needs
                  // two column blocks per wave and keeps the 2-wave shape
+            if (geglu == 2)
+                return a8 ? launch_cfg<Cfg<8, 2, 1, 1, 2, 8, 4>, false, 2>(g, w, codes, row_class, rows, y, nullptr, st, rq_cls)
+                          : launch_cfg<Cfg<4, 2, 1, 1, 2, 8, 4>, false, 2>(g, w, codes, row_class, rows, y, nullptr, st, rq_cls);
             if (geglu)
-                return a8 ? launch_cfg<Cfg<8, 2, 1, 1, 2, 8, 4>, false, true>(g, w, codes, row_class, rows, y, nullptr, st)
-                          : launch_cfg<Cfg<4, 2, 1, 1, 2, 8, 4>, false, true>(g, w, codes, row_class, rows, y, nullptr, st);
+                return a8 ? launch_cfg<Cfg<8, 2, 1, 1, 2, 8, 4>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st)
+                          : launch_cfg<Cfg<4, 2, 1, 1, 2, 8, 4>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st);
             if (multi)
                 return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 1, 8, 4>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st)
                           : launch_cfg<Cfg<4, 2, 2, 1, 1, 8, 4>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st);
