@@ -418,6 +418,47 @@ def main():
                 del codes, cls
             del xc, w
 
+    # ---------------- beyond the step: ff.in -> ff.out chained without the fp32 activation --
+    # The gated layer writes the following layer's codes (dgq_linear_geglu_requant) against
+    # the two calls it replaces: dgq_linear_geglu writing fp32 and dgq_quantize_act reading
+    # it back.  The following layer: 16 channel clusters, 8-bit codes, calibrated on the
+    # first 4096 rows of the gated layer's own output.
+    chain = []
+    if args.workload == "config5" and not args.step_only:
+        for ent in layers:
+            if not ent["name"].endswith("ff.in") or ent["O"] % 256:
+                continue
+            m = ent["modes"][(8, 8)]
+            M, oh = ent["M"], ent["O"] // 2
+            w = up(di.linear_case(ent["seed"], 1, 2, ent["C"], ent["O"])["W"])
+            h = torch.empty((M, oh), dtype=torch.float32, device=dev)
+            a_g = (C.c_void_p(m["g"].handle), C.c_void_p(m["wt"].handle), ptr(m["codes"]),
+                   ptr(m["cls"]), C.c_int64(M), ptr(h), sp)
+            us_g = time_calls(L.dgq_linear_geglu, a_g)
+            for next_grouping in ("16 channel clusters", "blocks of 128 channels"):
+                if next_grouping.startswith("16"):
+                    g2 = dgq.dgq_calibrate_kmeans(h[:4096], 8, 16, dgq.DIM_CHANNEL)
+                else:
+                    g2 = dgq.dgq_calibrate_groups(h[:4096], 8, 128, 1)
+                wf = dgq.dgq_pack_weight_gated_for(m["g"], g2, w, None, 8)
+                codes2 = torch.empty(dgq.codes_shape(g2, M), dtype=torch.int8, device=dev)
+                cls2 = torch.empty(M, dtype=torch.uint8, device=dev)
+                us_q = time_calls(L.dgq_quantize_act, (C.c_void_p(g2.handle), ptr(h), C.c_int64(M),
+                                                       ptr(codes2), ptr(cls2), sp))
+                us_c = time_calls(L.dgq_linear_geglu_requant,
+                                  (C.c_void_p(m["g"].handle), C.c_void_p(wf.handle), ptr(m["codes"]),
+                                   ptr(m["cls"]), C.c_int64(M), ptr(codes2), ptr(cls2), sp))
+                ops = 2.0 * M * ent["C"] * ent["O"]
+                chain.append(dict(layer=ent["name"], next_grouping=next_grouping, next_channels=oh,
+                                  next_k_padded=g2.info.k_padded,
+                                  us_geglu_fp32=round(us_g, 2), us_quantize_next=round(us_q, 2),
+                                  us_chained=round(us_c, 2), tops_chained=round(ops / us_c / 1e6, 1),
+                                  bytes_not_moved=int(2 * 4 * M * oh)))
+                wf.free()
+                g2.free()
+                del codes2, cls2
+            del w, h
+
     # ---------------- beyond the step: the attention product on the quantized value tensor ---
     value_quant = []
     if not args.step_only:
@@ -478,7 +519,7 @@ def main():
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
-                linear_geglu=fused, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, cpu_baseline=cpu)
+                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, cpu_baseline=cpu)
     print(json.dumps(line))
 
 

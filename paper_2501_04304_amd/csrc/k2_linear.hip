@@ -458,31 +458,48 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             if constexpr (GEGLU == 2) {
                 // Quantize for the next layer (Section 3.1's linear quantizer with the
                 // chunk's static offset and step; same operations as the stand-alone
-                // quantizer) and store one byte per register.  Register i holds row
-                // 8 (i / 4) + 4 kh + i % 4 of the 32-row block: two 16-row code blocks,
-                // i / 8 apart; in its block the row is t = 8 (i / 4 % 2) + 4 kh + i % 4, whose
-                // slot swizzle is kh | 2 ((i / 2 ^ i / 4) % 2): one lane offset per value of
-                // the compile-time bit.
+                // quantizer).  A lane holds one position (column) of 16 rows, the layout
+                // wants four consecutive positions of one row in a dword: the four codes of
+                // registers 4 g .. 4 g + 3 (rows 8 g + 4 kh + 0 .. 3) are packed into one
+                // dword and the 4 x 4 bytes are transposed across the four lanes of a quad,
+                // after which lane j of quad c holds row 8 g + 4 kh + j, positions 4 c .. 4 c + 3:
+                // one dword store per four registers.  In its 16-row code block that row is
+                // t = 8 (g % 2) + 4 kh + j with slot swizzle kh | 2 ((j / 2) ^ (g % 2)): one lane
+                // offset per value of the compile-time bit.
                 int8_t *cout = reinterpret_cast<int8_t *>(y);
                 const int32_t posw = (o0 >> 1) + wo * 32;  // first position of this wave
                 const int32_t nch2 = O >> 7, chunk = posw >> 6;
                 const float2 zi = rq_zi[chunk];
-                const uint32_t keep = rq_keep[posw + m32];
-                const uint32_t kq = (uint32_t)(((posw & 63) >> 4) + (m32 >> 4));
-                const uint32_t lane_off0 = (uint32_t)kh * 256u + (((kq ^ (uint32_t)kh)) << 4) + (uint32_t)(m32 & 15);
-                const uint32_t lane_off1 = (uint32_t)kh * 256u + (((kq ^ (uint32_t)kh ^ 2u)) << 4) + (uint32_t)(m32 & 15);
+                const uint32_t keep = rq_keep[posw + m32] ? 0xffffffffu : 0u;
+                const uint32_t j = (uint32_t)m32 & 3u, c = (uint32_t)m32 >> 2;
+                const uint32_t kq = (uint32_t)((posw & 63) >> 4) + (c >> 2);
+                const uint32_t row_part = (4u * (uint32_t)kh + j) * 64u + 4u * (c & 3u);
+                const uint32_t lane_off0 = row_part + ((kq ^ ((uint32_t)kh | ((j >> 1) << 1))) << 4);
+                const uint32_t lane_off1 = row_part + ((kq ^ ((uint32_t)kh | (((j >> 1) ^ 1u) << 1))) << 4);
+                const uint32_t sel = ((4u + j) << 8) | j;  // byte j of each of two sources
 #pragma unroll
                 for (int a = 0; a < BR; ++a) {
                     const int64_t rb = (r0 + (wr * BR + a) * 32) >> 4;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float t = __fsub_rn(facc[a][0][i], zi.x);
-                        const float u = __fmul_rn(t, zi.y);
-                        const uint32_t q = (__builtin_amdgcn_cvt_pk_u8_f32(u, 0, 0u) ^ 0x80u) & keep;
-                        int8_t *blk = cout + (((rb + (i >> 3)) * nch2 + chunk) << 10) +
-                                      (8 * ((i >> 2) & 1) + (i & 3)) * 64;
-                        const uint32_t lo = (((i >> 1) ^ (i >> 2)) & 1) ? lane_off1 : lane_off0;
-                        if (!((past[a] >> i) & 1)) blk[lo] = (int8_t)q;
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        uint32_t pk = 0;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const float t = __fsub_rn(facc[a][0][4 * g4 + k], zi.x);
+                            pk = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn(t, zi.y), k, pk);
+                        }
+                        pk = (pk ^ 0x80808080u) & keep;  // stored code = q - 128; padding stores 0
+                        const uint32_t q0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0x00, 0xf, 0xf, false);
+                        const uint32_t q1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0x55, 0xf, 0xf, false);
+                        const uint32_t q2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0xaa, 0xf, 0xf, false);
+                        const uint32_t q3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0xff, 0xf, 0xf, false);
+                        const uint32_t x01 = __builtin_amdgcn_perm(q1, q0, sel);  // bytes: q0.j, q1.j
+                        const uint32_t x23 = __builtin_amdgcn_perm(q3, q2, sel);  // bytes: q2.j, q3.j
+                        const uint32_t word = __builtin_amdgcn_perm(x23, x01, 0x05040100u);
+                        int8_t *blk = cout + (((rb + (g4 >> 1)) * nch2 + chunk) << 10) + (g4 & 1) * 512;
+                        const uint32_t lo = (g4 & 1) ? lane_off1 : lane_off0;
+                        if (!((past[a] >> (4 * g4 + (int)j)) & 1))
+                            *reinterpret_cast<uint32_t *>(blk + lo) = word;
                     }
                 }
                 // the column-0 tiles also write the next layer's row classes
