@@ -257,6 +257,27 @@ def xattn_logq(A, V, bits: int, want_ahat: bool = False, s_in=None):
     return dict(s=s, codes=codes, margin=margin, ahat=ahat, out=out)
 
 
+def selfattn(Q, K, V, bits: int, s_in, want_ahat: bool = False):
+    """Self-attention with every probability log2-quantized against the given scale
+    s_in [B].  Q [B,Nq,H,d] (any subset of the queries), K, V [B,nk,H,d] ->
+    dict(A, s (= max A per prompt), codes [B,H,Nq,nk], margin, ahat, out [B,Nq,H,d])."""
+    A = attn_probs(Q, K, None)
+    V = _f32(V)
+    B, H, N, nk = A.shape
+    d = V.shape[3]
+    s_in = _f32(s_in)
+    assert s_in.shape == (B,)
+    s = np.zeros(B, dtype=np.float32)
+    codes = np.zeros((B, H, N, nk), dtype=np.uint8)
+    margin = np.zeros((B, H, N, nk), dtype=np.float32)
+    ahat = np.zeros((B, H, N, nk), dtype=np.float64) if want_ahat else None
+    out = np.zeros((B, N, H, d), dtype=np.float32)
+    lib().dgqo_selfattn_logq(_p(A), _p(V), C.c_int32(B), C.c_int32(N), C.c_int32(H), C.c_int32(d),
+                             C.c_int32(nk), C.c_int32(bits), _p(s_in), _p(s), _p(codes), _p(margin),
+                             _p(ahat), _p(out))
+    return dict(A=A, s=s, codes=codes, margin=margin, ahat=ahat, out=out)
+
+
 def quantize_value(V, bits: int = 8):
     """V [B,nk,H,d] -> dict(vhat fp32 [B,nk,H,d], codes u8, params [B,H,2] = (s, z))."""
     V = _f32(V)

@@ -732,11 +732,15 @@ void dgqo_attn_probs(const float *Q, const float *K, const float *kb, int32_t B,
  *          to the nearest rounding boundary k + 1/2, k = 0 .. 2^bits - 2
  *   ahat   [B,H,N,nk]   (nullable) in double
  */
+/* first = 1: column 0 (the <start> token) bypasses the quantizer (cross-attention).
+ * first = 0: every column goes through it (self-attention); codes and margin then have
+ * nk columns instead of nk - 1. */
 static void dgqo_xattn_logq_impl(const float *A, const float *V, int32_t B, int32_t N,
                                  int32_t H, int32_t d, int32_t nk, int32_t bits,
-                                 const float *s_in, float *s_out, uint8_t *codes,
-                                 float *margin, double *ahat, float *out)
+                                 int32_t first, const float *s_in, float *s_out,
+                                 uint8_t *codes, float *margin, double *ahat, float *out)
 {
+    const int32_t nc = nk - first;
     const int32_t qmax = (1 << bits) - 1;
     double *acc = (double *)malloc(sizeof(double) * (size_t)d);
     for (int32_t b = 0; b < B; ++b) {
@@ -744,7 +748,7 @@ static void dgqo_xattn_logq_impl(const float *A, const float *V, int32_t B, int3
         for (int32_t h = 0; h < H; ++h)
             for (int32_t i = 0; i < N; ++i) {
                 const float *a = A + (((int64_t)b * H + h) * N + i) * nk;
-                for (int32_t j = 1; j < nk; ++j)
+                for (int32_t j = first; j < nk; ++j)
                     if (a[j] > s) s = a[j];
             }
         s_out[b] = s;            /* this call's own maximum, whichever scale is used */
@@ -754,9 +758,10 @@ static void dgqo_xattn_logq_impl(const float *A, const float *V, int32_t B, int3
                 const int64_t row = ((int64_t)b * H + h) * N + i;
                 const float *a = A + row * nk;
                 for (int32_t t = 0; t < d; ++t)
-                    acc[t] = (double)a[0] * (double)V[(((int64_t)b * nk + 0) * H + h) * d + t];
-                if (ahat) ahat[row * nk] = (double)a[0];
-                for (int32_t j = 1; j < nk; ++j) {
+                    acc[t] = first ? (double)a[0] * (double)V[(((int64_t)b * nk + 0) * H + h) * d + t]
+                                   : 0.0;
+                if (ahat && first) ahat[row * nk] = (double)a[0];
+                for (int32_t j = first; j < nk; ++j) {
                     int32_t q;
                     double mg;
                     if (a[j] > 0.0f && s > 0.0f) {
@@ -776,8 +781,8 @@ static void dgqo_xattn_logq_impl(const float *A, const float *V, int32_t B, int3
                         q = qmax;
                         mg = 1.0e30;
                     }
-                    codes[row * (nk - 1) + (j - 1)] = (uint8_t)q;
-                    if (margin) margin[row * (nk - 1) + (j - 1)] = (float)mg;
+                    codes[row * nc + (j - first)] = (uint8_t)q;
+                    if (margin) margin[row * nc + (j - first)] = (float)mg;
                     double p2 = ldexp(1.0, -q); /* exact power of two */
                     double ah = (double)s * p2;
                     if (ahat) ahat[row * nk + j] = ah;
@@ -796,7 +801,7 @@ void dgqo_xattn_logq(const float *A, const float *V, int32_t B, int32_t N,
                      float *s_out, uint8_t *codes, float *margin, double *ahat,
                      float *out)
 {
-    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, NULL, s_out, codes, margin, ahat, out);
+    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, 1, NULL, s_out, codes, margin, ahat, out);
 }
 
 /*
@@ -810,7 +815,23 @@ void dgqo_xattn_logq_static(const float *A, const float *V, int32_t B, int32_t N
                             const float *s_in, float *s_out, uint8_t *codes, float *margin,
                             double *ahat, float *out)
 {
-    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, s_in, s_out, codes, margin, ahat, out);
+    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, 1, s_in, s_out, codes, margin, ahat, out);
+}
+
+/*
+ * Self-attention (Section 3.3: the logarithmic quantizer is applied to self- and
+ * cross-attention alike; separating the <start> column and the dynamic scale are stated
+ * for cross-attention only): every probability goes through the log quantizer of
+ * Section 3.1 with a GIVEN scale s[b], A^q = clamp(rne(-log2(A / s)), 0, 2^b - 1),
+ * A^ = s 2^-A^q, out = A^ V.  A: [B,H,N,nk] (N queries, nk keys; nk = N in a layer, any
+ * subset of the queries for sampled checks); codes, margin: [B,H,N,nk].  s_out receives
+ * max A.
+ */
+void dgqo_selfattn_logq(const float *A, const float *V, int32_t B, int32_t N, int32_t H,
+                        int32_t d, int32_t nk, int32_t bits, const float *s_in, float *s_out,
+                        uint8_t *codes, float *margin, double *ahat, float *out)
+{
+    dgqo_xattn_logq_impl(A, V, B, N, H, d, nk, bits, 0, s_in, s_out, codes, margin, ahat, out);
 }
 
 /* ------------------------------------------------------------------------- */
