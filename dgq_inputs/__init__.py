@@ -100,6 +100,17 @@ def attention_case(seed: int, B: int, N: int, H: int, d: int,
 #   (name, M rows, B, N, C in, O out, group size G).
 # ----------------------------------------------------------------------------
 
+def selfattn_case(seed: int, B: int, N: int, H: int, d: int, sharp: float = 1.5):
+    """Self-attention inputs: Q, K, V ~ N(0, 1) [B,N,H,d] fp32 drawn in that order with
+    Generator(PCG64(seed)); Q is multiplied by `sharp`, so the logits q.k / sqrt(d) have
+    standard deviation `sharp` and a row's probabilities span many octaves."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    Q = (rng.standard_normal((B, N, H, d)) * sharp).astype(np.float32)
+    K = rng.standard_normal((B, N, H, d)).astype(np.float32)
+    V = rng.standard_normal((B, N, H, d)).astype(np.float32)
+    return dict(Q=Q, K=K, V=V)
+
+
 def _block_linears(prefix, B, N, C, G, d_ctx, nk=N_TEXT_KEYS):
     M = B * N
     Mk = B * nk

@@ -342,6 +342,30 @@ int dgq_xattn_logq_static(const float *q, const float *k, const float *v,
                           float *scale_out, uint8_t *codes_dump, void *stream);
 
 /*
+ * Self-attention with log2-quantized probabilities.  Section 3.3 applies the logarithmic
+ * quantizer of Section 3.1 to self- and cross-attention alike; separating the <start>
+ * column and the dynamic scale are stated for cross-attention only.  Here every
+ * probability is quantized and the scale is given:
+ *   L[b,h,i,j] = (q[b,i,h,:] . k[b,j,h,:]) / sqrt(d),  A = softmax_j(L) over all N keys
+ *   A^q = clamp(rne(-log2(A / s[b])), 0, 2^attn_bits - 1)   (A = 0: the top code)
+ *   out[b,i,h,:] = sum_j s[b] 2^-A^q[b,h,i,j] v[b,j,h,:]
+ *   q, k, v, out: fp32 [B, N, H, d] (device); v may be the V^ of dgq_quantize_value
+ *   scale_in:  fp32 [B], the given scale (1 for the plain log2 quantizer of a probability,
+ *              or a calibrated maximum); a value <= 0 gives out = 0
+ *   scale_out: NULL, or fp32 [B] receiving max A of this call
+ *   codes_dump: NULL, or u8 [B, H, N, N] receiving every code (debug / parity)
+ *   workspace: dgq_selfattn_workspace_bytes(B, N, H, d) bytes, 16-byte aligned; holds K
+ *              and V^T in the matrix cores' operand pieces, rewritten by every call
+ * d % 8 == 0 and d <= 64 (DGQ_EUNSUPPORTED otherwise; the workspace size reads 0).
+ * attn_bits in {4, 8}.  Enqueues on `stream`; does not synchronise or allocate.
+ */
+size_t dgq_selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d);
+int dgq_selfattn_logq(const float *q, const float *k, const float *v, int32_t B, int32_t N,
+                      int32_t H, int32_t d, int32_t attn_bits, const float *scale_in,
+                      float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/*
  * The quantized value tensor V^ of the attention product A^ V^ (Section 3.3).  Every
  * (prompt, head) slice V[b, :, h, :] goes through the linear quantizer of Section 3.1
  * with its own range:

@@ -75,6 +75,9 @@ def lib():
         L.dgq_xattn_logq_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
                                             vp, vp]
         L.dgq_xattn_workspace_bytes.restype = sz
+        L.dgq_selfattn_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.dgq_selfattn_workspace_bytes.restype = sz
+        L.dgq_selfattn_logq.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.dgq_last_error.restype = C.c_char_p
         L.dgq_version.restype = C.c_int
         _lib = L
@@ -354,6 +357,38 @@ def dgq_xattn_logq(q, k, v, key_bias, attn_bits: int, out=None, scale_out=None, 
                                 attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
                                 _ptr(workspace), wbytes, _stream(stream)))
     return out, scale_out
+
+
+def dgq_selfattn_workspace_bytes(B, N, H, d) -> int:
+    return int(lib().dgq_selfattn_workspace_bytes(B, N, H, d))
+
+
+def dgq_selfattn_logq(q, k, v, attn_bits: int, scale_in, out=None, scale_out=None, codes_dump=None,
+                      workspace=None, stream=None):
+    """q, k, v fp32 [B,N,H,d], scale_in fp32 [B] -> out fp32 [B,N,H,d].  scale_out [B] and
+    codes_dump u8 [B,H,N,N] are filled if given."""
+    import torch
+    for t, name in ((q, "q"), (k, "k"), (v, "v"), (scale_in, "scale_in")):
+        _dev(t, torch.float32, name)
+    B, N, H, d = q.shape
+    if tuple(k.shape) != (B, N, H, d) or tuple(v.shape) != (B, N, H, d) or scale_in.numel() != B:
+        raise ValueError("q, k, v must share one shape [B,N,H,d] and scale_in have B entries")
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out, torch.float32, "out")
+    if scale_out is not None:
+        _dev(scale_out, torch.float32, "scale_out")
+    if codes_dump is not None:
+        _dev(codes_dump, torch.uint8, "codes_dump")
+        if tuple(codes_dump.shape) != (B, H, N, N):
+            raise ValueError("codes_dump must be [B,H,N,N]")
+    need = dgq_selfattn_workspace_bytes(B, N, H, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(lib().dgq_selfattn_logq(_ptr(q), _ptr(k), _ptr(v), B, N, H, d, attn_bits, _ptr(scale_in),
+                                   _ptr(out), _ptr(scale_out), _ptr(codes_dump), _ptr(workspace),
+                                   workspace.numel(), _stream(stream)))
+    return out
 
 
 def dgq_quantize_value(v, v_bits: int = 8, v_hat=None, want_codes: bool = False,

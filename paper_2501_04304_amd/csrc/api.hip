@@ -870,6 +870,33 @@ int dgq_xattn_logq_static(const float *q, const float *k, const float *v, const 
     return DGQ_OK;
 }
 
+size_t dgq_selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d) {
+    if (B < 1 || N < 1 || H < 1) return 0;
+    return selfattn_workspace_bytes(B, N, H, d);
+}
+
+int dgq_selfattn_logq(const float *q, const float *k, const float *v, int32_t B, int32_t N, int32_t H,
+                      int32_t d, int32_t attn_bits, const float *scale_in, float *out,
+                      float *scale_out, uint8_t *codes_dump, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+    if (!q || !k || !v || !scale_in || !out)
+        return fail(DGQ_EINVAL, "dgq_selfattn_logq: null pointer");
+    if (B < 1 || N < 1 || H < 1 || d < 1) return fail(DGQ_EINVAL, "dgq_selfattn_logq: empty shape");
+    if (attn_bits != 4 && attn_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_selfattn_logq: attn_bits must be 4 or 8");
+    if (d % 8 != 0 || d > 64)
+        return fail(DGQ_EUNSUPPORTED, "dgq_selfattn_logq: head dimension must be a multiple of 8, at most 64");
+    if ((int64_t)B * H > (1 << 20) || N > (1 << 20))
+        return fail(DGQ_EUNSUPPORTED, "dgq_selfattn_logq: too many (prompt, head) pairs or tokens");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(workspace))
+        return fail(DGQ_EALIGN, "dgq_selfattn_logq: tensor not 16-byte aligned");
+    if (!workspace || workspace_bytes < selfattn_workspace_bytes(B, N, H, d))
+        return fail(DGQ_ESHAPE, "dgq_selfattn_logq: workspace smaller than dgq_selfattn_workspace_bytes");
+    DGQ_HIP(launch_selfattn(q, k, v, B, N, H, d, attn_bits, scale_in, out, scale_out, codes_dump,
+                            workspace, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
 int dgq_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d, int32_t v_bits,
                        float *v_hat, uint8_t *codes, float *params, void *stream) {
     if (!v || !v_hat) return fail(DGQ_EINVAL, "dgq_quantize_value: null pointer");

@@ -519,6 +519,289 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
 bool mfma_shape(int32_t d, int32_t nk) { return (d % 8) == 0 && d <= 96 && nk + 2 <= 128; }
 
 // ======================================================================================
+// Self-attention: every key quantized, given scale, keys streamed in tiles of 32
+// ======================================================================================
+// Section 3.3 applies the log quantizer to self-attention too; there is no <start> column
+// and the scale s_b is given.  The number of keys equals the number of queries (4096 on
+// the 64 x 64 latent), so K and V^T cannot live in LDS as in the kernels above.  A first
+// kernel writes them once per (prompt, head) in exactly the pieces the matrix cores take:
+//   Kh, Kl [tile][32 keys][DK halves]      fp16 hi / lo of K log2(e) / sqrt(d)
+//   Vh, Vl [tile][DV dims][32 key slots]   bf16 hi / lo of s_b V^T, the key slots of a tile
+//                                          in the order the accumulator registers of S^T
+//                                          hold them (see k_xattn_mfma)
+// The second kernel gives each wavefront 32 queries (their fp16 pieces stay in registers)
+// and sweeps the key tiles twice, reading the fragments straight from memory (they are
+// shared by every wavefront of the (prompt, head) pair and stay in L2): sweep A takes the
+// running maximum and sum of 2^(S - max) for lse2, sweep B recomputes S^T bit-identically,
+// forms the codes from log2 s + lse2 - S as above and accumulates Out^T = V^T P^T.  A code
+// depends on the row's full sum, so one sweep cannot do both.  No LDS, no barrier.
+template <int KS_>
+struct SCfg {
+    static constexpr int KS = KS_;
+    static constexpr int DK = 16 * KS;        // halves per key row
+    static constexpr int DB = (KS + 1) / 2;   // 32-wide blocks of output dims
+    static constexpr int DV = 32 * DB;
+    static constexpr size_t k_tile = 32 * DK;  // elements per tile and piece
+    static constexpr size_t v_tile = DV * 32;
+};
+
+// slot of key j (0..31) of a tile in the V^T rows: inside each 16-key step the lower lane
+// half takes keys 0..3 and 8..11, the upper half keys 4..7 and 12..15
+__device__ __host__ constexpr int v_slot(int j) {
+    return 16 * (j >> 4) + 8 * ((j >> 2) & 1) + (j & 3) + 4 * ((j >> 3) & 1);
+}
+
+template <class CF>
+__global__ __launch_bounds__(256) void k_selfattn_prep(
+    const float *__restrict__ k, const float *__restrict__ v, int32_t nk, int32_t H, int32_t d,
+    float qk_scale, const float *__restrict__ scale_in, int32_t n_tiles, uint16_t *__restrict__ kh,
+    uint16_t *__restrict__ kl, uint16_t *__restrict__ vh, uint16_t *__restrict__ vl) {
+    constexpr int KS = CF::KS, DK = CF::DK, DV = CF::DV;
+    const int32_t tile = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int64_t hs = (int64_t)H * d;
+    const int64_t bh = (int64_t)b * H + head;
+    const float s_b = scale_in[b];
+    const float s_eff = s_b > 0.0f ? s_b : 1.0f;
+    const float *kb = k + ((int64_t)b * nk * H + head) * d;
+    const float *vb = v + ((int64_t)b * nk * H + head) * d;
+    uint16_t *khp = kh + (bh * n_tiles + tile) * CF::k_tile;
+    uint16_t *klp = kl + (bh * n_tiles + tile) * CF::k_tile;
+    uint16_t *vhp = vh + (bh * n_tiles + tile) * CF::v_tile;
+    uint16_t *vlp = vl + (bh * n_tiles + tile) * CF::v_tile;
+    for (int idx = tid; idx < 32 * KS * 4; idx += 256) {
+        const int j = idx / (KS * 4), t4 = (idx - j * (KS * 4)) * 4;
+        const int32_t key = 32 * tile + j;
+        float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (key < nk && t4 < d) x = *reinterpret_cast<const float4 *>(kb + (int64_t)key * hs + t4);
+        const HiLo p0 = split_h2(x.x * qk_scale, x.y * qk_scale);
+        const HiLo p1 = split_h2(x.z * qk_scale, x.w * qk_scale);
+        *reinterpret_cast<u32x2 *>(khp + j * DK + t4) = u32x2{p0.hi, p1.hi};
+        *reinterpret_cast<u32x2 *>(klp + j * DK + t4) = u32x2{p0.lo, p1.lo};
+    }
+    for (int idx = tid; idx < 32 * (DV / 4); idx += 256) {
+        const int j = idx / (DV / 4), t4 = (idx - j * (DV / 4)) * 4;
+        const int32_t key = 32 * tile + j;
+        float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (key < nk && t4 < d) x = *reinterpret_cast<const float4 *>(vb + (int64_t)key * hs + t4);
+        const float xe[4] = {x.x * s_eff, x.y * s_eff, x.z * s_eff, x.w * s_eff};
+        const int slot = v_slot(j);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t hb = bf16_rne_bits(xe[e]);
+            const uint32_t lb = bf16_rne_bits(xe[e] - __uint_as_float(hb));
+            vhp[(t4 + e) * 32 + slot] = (uint16_t)(hb >> 16);
+            vlp[(t4 + e) * 32 + slot] = (uint16_t)(lb >> 16);
+        }
+    }
+}
+
+template <class CF, bool DUMP>
+__global__ __launch_bounds__(256, 2) void k_selfattn(
+    const float *__restrict__ q, int32_t BH, int32_t N, int32_t H, int32_t d, int32_t bits,
+    int32_t n_tiles, int32_t q_tiles, const uint16_t *__restrict__ kh,
+    const uint16_t *__restrict__ kl, const uint16_t *__restrict__ vh,
+    const uint16_t *__restrict__ vl, const float *__restrict__ scale_in, float *__restrict__ out,
+    float *__restrict__ scale_out, uint8_t *__restrict__ codes_dump) {
+    constexpr int KS = CF::KS, DK = CF::DK, DB = CF::DB;
+    // Workgroup w runs on XCD w % 8: give every XCD whole (prompt, head) pairs, so that the
+    // pair's K and V^T pieces (2 MB at 4096 keys) are fetched into one L2 only.
+    const int32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int32_t bh = (slot / q_tiles) * 8 + xcd;
+    if (bh >= BH) return;
+    const int32_t b = bh / H, head = bh - b * H;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int32_t q0 = ((slot % q_tiles) * 4 + wave) * 32;
+    if (q0 >= N) return;  // wave-uniform; the kernel has no barrier
+    const int n = lane & 31, hh = lane >> 5;
+    const int32_t nk = N;
+    const int32_t qi = q0 + n;
+    const bool valid = qi < N;
+    const int64_t hs = (int64_t)H * d;
+
+    const float s_b = scale_in[b];
+    const float s_eff = s_b > 0.0f ? s_b : 1.0f;
+    const uint32_t pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;  // scale 0: every product is 0
+    const float l2s = __log2f(s_eff);
+
+    // ---- the lane's query slices as fp16 pieces: dims 16 s + 8 hh .. + 7 -------------------
+    u32x4 qh[KS], ql[KS];
+    {
+        const float *p = q + ((int64_t)b * N * H + head) * d + (int64_t)(valid ? qi : N - 1) * hs + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            float4 a = {0.0f, 0.0f, 0.0f, 0.0f}, c = a;
+            if (16 * s + 8 * hh < d) {
+                a = *reinterpret_cast<const float4 *>(p + 16 * s);
+                c = *reinterpret_cast<const float4 *>(p + 16 * s + 4);
+            }
+            const HiLo p0 = split_h2(a.x, a.y), p1 = split_h2(a.z, a.w);
+            const HiLo p2 = split_h2(c.x, c.y), p3 = split_h2(c.z, c.w);
+            qh[s] = u32x4{p0.hi, p1.hi, p2.hi, p3.hi};
+            ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
+        }
+    }
+    const uint16_t *khb = kh + (int64_t)bh * n_tiles * CF::k_tile + n * DK + 8 * hh;
+    const uint16_t *klb = kl + (int64_t)bh * n_tiles * CF::k_tile + n * DK + 8 * hh;
+    const uint16_t *vhb = vh + (int64_t)bh * n_tiles * CF::v_tile + n * 32 + 8 * hh;
+    const uint16_t *vlb = vl + (int64_t)bh * n_tiles * CF::v_tile + n * 32 + 8 * hh;
+
+    // S^T of key tile kt for the wave's 32 queries, in log2 units; padding keys -inf
+    auto s_tile = [&](int32_t kt, v16f &sm) {
+        u32x4 fh[KS], fl[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            fh[s] = *reinterpret_cast<const u32x4 *>(khb + (int64_t)kt * CF::k_tile + 16 * s);
+            fl[s] = *reinterpret_cast<const u32x4 *>(klb + (int64_t)kt * CF::k_tile + 16 * s);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sm[i] = 0.0f;
+        if (32 * kt + 32 > nk) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (32 * kt + key_of(0, i, hh) >= nk) sm[i] = -INFINITY;
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const v8h bqh = __builtin_bit_cast(v8h, qh[s]);
+            const v8h bql = __builtin_bit_cast(v8h, ql[s]);
+            const v8h akh = __builtin_bit_cast(v8h, fh[s]);
+            const v8h akl = __builtin_bit_cast(v8h, fl[s]);
+            sm = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bqh, sm, 0, 0, 0);
+            sm = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bql, sm, 0, 0, 0);
+            sm = __builtin_amdgcn_mfma_f32_32x32x16_f16(akl, bqh, sm, 0, 0, 0);
+        }
+    };
+
+    // ---- sweep A: lse2 of the lane's query (each lane half sees half of the keys) -------
+    float m = -INFINITY, l = 0.0f;
+    for (int32_t kt = 0; kt < n_tiles; ++kt) {
+        v16f sm;
+        s_tile(kt, sm);
+        float tm = sm[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) tm = fmaxf(tm, sm[i]);
+        const float mn = fmaxf(m, tm);
+        const float ms = mn == -INFINITY ? 0.0f : mn;
+        float add = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) add += __builtin_amdgcn_exp2f(sm[i] - ms);
+        l = l * __builtin_amdgcn_exp2f(m - ms) + add;
+        m = mn;
+    }
+    float lse;
+    {
+        const float mo = __shfl_xor(m, 32, kWave), lo = __shfl_xor(l, 32, kWave);
+        const float m2 = fmaxf(m, mo);  // finite: key 0 exists
+        const float l2 = l * __builtin_amdgcn_exp2f(m - m2) + lo * __builtin_amdgcn_exp2f(mo - m2);
+        lse = m2 + __log2f(l2);
+        if (scale_out) {
+            // the row's largest probability; probabilities order like their bit patterns
+            float amax = valid ? m2 - lse : -INFINITY;
+            amax = wave_max(amax);
+            if (lane == 0)
+                atomicMax(reinterpret_cast<unsigned int *>(scale_out + b),
+                          __float_as_uint(__builtin_amdgcn_exp2f(amax)));
+        }
+    }
+
+    // ---- sweep B: codes and Out^T = V^T P^T -------------------------------------------------
+    const float c0 = l2s + lse;
+    const float thr = l2s + 150.0f;
+    constexpr int32_t kMagic = 0x4B400000;  // bit pattern of 12582912.0f
+    const int32_t cq = (1 << bits) - 1;
+    const int32_t ce = cq < 127 ? cq : 127;  // 2^-127 and below leave the product as zero
+    uint8_t *cd = nullptr;
+    if (DUMP) cd = codes_dump + ((int64_t)bh * N + (valid ? qi : 0)) * (int64_t)nk;
+    v16f o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
+    for (int32_t kt = 0; kt < n_tiles; ++kt) {
+        v16f sm;
+        s_tile(kt, sm);
+        // V^T fragments of this tile: issued before the code arithmetic that hides them
+        u32x4 fvh[DB][2], fvl[DB][2];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                fvh[db][u] = *reinterpret_cast<const u32x4 *>(vhb + (int64_t)kt * CF::v_tile + db * 32 * 32 + 16 * u);
+                fvl[db][u] = *reinterpret_cast<const u32x4 *>(vlb + (int64_t)kt * CF::v_tile + db * 32 * 32 + 16 * u);
+            }
+        uint32_t pk[8];
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            int32_t e[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                float t = c0 - sm[i + u];
+                t = t > thr ? 300.0f : t;  // a probability that is zero in fp32: top code
+                const int32_t r = __float_as_int(t + 12582912.0f);
+                if (DUMP) {
+                    const int32_t key = 32 * kt + key_of(0, i + u, hh);
+                    const int32_t c = clamp_i32(r, kMagic, kMagic + cq) - kMagic;
+                    if (valid && key < nk) cd[key] = (uint8_t)c;
+                }
+                e[u] = (kMagic + 127) - clamp_i32(r, kMagic, kMagic + ce);
+            }
+            pk[i >> 1] = ((uint32_t)(e[0] | (e[1] << 16)) << 7) & pmask;
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const u32x4 pb = {pk[4 * u + 0], pk[4 * u + 1], pk[4 * u + 2], pk[4 * u + 3]};
+            const v8bf bp = __builtin_bit_cast(v8bf, pb);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fvh[db][u]), bp, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fvl[db][u]), bp, o[db], 0, 0, 0);
+            }
+        }
+    }
+    if (valid) {
+        float *orow = out + ((int64_t)b * N * H + head) * d + (int64_t)qi * hs;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int dim = 32 * db + 8 * a + 4 * hh;
+                if (dim < d) {
+                    const float4 t = {o[db][4 * a + 0], o[db][4 * a + 1], o[db][4 * a + 2], o[db][4 * a + 3]};
+                    *reinterpret_cast<float4 *>(orow + dim) = t;
+                }
+            }
+    }
+}
+
+template <class CF>
+hipError_t launch_selfattn_cfg(const float *q, const float *k, const float *v, int32_t B, int32_t N,
+                               int32_t H, int32_t d, int32_t bits, const float *scale_in, float *out,
+                               float *scale_out, uint8_t *codes_dump, void *workspace,
+                               hipStream_t st) {
+    const int32_t n_tiles = (N + 31) / 32, BH = B * H;
+    uint16_t *kh = static_cast<uint16_t *>(workspace);
+    uint16_t *kl = kh + (size_t)BH * n_tiles * CF::k_tile;
+    uint16_t *vh = kl + (size_t)BH * n_tiles * CF::k_tile;
+    uint16_t *vl = vh + (size_t)BH * n_tiles * CF::v_tile;
+    const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
+    if (scale_out) hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
+    hipLaunchKernelGGL(k_selfattn_prep<CF>, dim3(n_tiles, H, B), dim3(256), 0, st, k, v, N, H, d,
+                       qk_scale, scale_in, n_tiles, kh, kl, vh, vl);
+    const int32_t q_tiles = (N + 127) / 128;
+    const int64_t groups = ((int64_t)BH + 7) / 8;
+    const dim3 grid((unsigned)(groups * q_tiles * 8));
+    if (codes_dump)
+        hipLaunchKernelGGL((k_selfattn<CF, true>), grid, dim3(256), 0, st, q, BH, N, H, d, bits, n_tiles,
+                           q_tiles, kh, kl, vh, vl, scale_in, out, scale_out, codes_dump);
+    else
+        hipLaunchKernelGGL((k_selfattn<CF, false>), grid, dim3(256), 0, st, q, BH, N, H, d, bits, n_tiles,
+                           q_tiles, kh, kl, vh, vl, scale_in, out, scale_out, codes_dump);
+    return hipGetLastError();
+}
+
+// ======================================================================================
 // Plain fp32 path (any head dim up to 256, any nk up to 128)
 // ======================================================================================
 
@@ -777,6 +1060,27 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
                                  codes_dump, scale_in, st);
     return launch_passes<128>(q, k, v, key_bias, B, N, H, d, nk, bits, out, scale_out, codes_dump,
                               scale_in, st);
+}
+
+// K and V^T of every (prompt, head) pair in the matrix cores' pieces (see k_selfattn_prep).
+static int selfattn_ks(int32_t d) { return d <= 16 ? 1 : (d <= 32 ? 2 : (d <= 48 ? 3 : 4)); }
+
+size_t selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d) {
+    if (d % 8 != 0 || d > 64 || d < 8) return 0;
+    const size_t ks = (size_t)selfattn_ks(d), dk = 16 * ks, dv = 32 * ((ks + 1) / 2);
+    const size_t n_tiles = ((size_t)N + 31) / 32;
+    return (size_t)B * H * n_tiles * (32 * dk + dv * 32) * 2 * sizeof(uint16_t);
+}
+
+hipError_t launch_selfattn(const float *q, const float *k, const float *v, int32_t B, int32_t N,
+                           int32_t H, int32_t d, int32_t bits, const float *scale_in, float *out,
+                           float *scale_out, uint8_t *codes_dump, void *workspace, hipStream_t st) {
+    switch (selfattn_ks(d)) {
+        case 1: return launch_selfattn_cfg<SCfg<1>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+        case 2: return launch_selfattn_cfg<SCfg<2>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+        case 3: return launch_selfattn_cfg<SCfg<3>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+        default: return launch_selfattn_cfg<SCfg<4>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+    }
 }
 
 }  // namespace dgq
