@@ -523,40 +523,58 @@ bool mfma_shape(int32_t d, int32_t nk) { return (d % 8) == 0 && d <= 96 && nk + 
 // ======================================================================================
 // Section 3.3 applies the log quantizer to self-attention too; there is no <start> column
 // and the scale s_b is given.  The number of keys equals the number of queries (4096 on
-// the 64 x 64 latent), so K and V^T cannot live in LDS as in the kernels above.  A first
-// kernel writes them once per (prompt, head) in exactly the pieces the matrix cores take:
-//   Kh, Kl [tile][32 keys][DK halves]      fp16 hi / lo of K log2(e) / sqrt(d)
-//   Vh, Vl [tile][DV dims][32 key slots]   bf16 hi / lo of s_b V^T, the key slots of a tile
-//                                          in the order the accumulator registers of S^T
-//                                          hold them (see k_xattn_mfma)
-// The second kernel gives each wavefront 32 queries (their fp16 pieces stay in registers)
-// and sweeps the key tiles twice, reading the fragments straight from memory (they are
-// shared by every wavefront of the (prompt, head) pair and stay in L2): sweep A takes the
-// running maximum and sum of 2^(S - max) for lse2, sweep B recomputes S^T bit-identically,
-// forms the codes from log2 s + lse2 - S as above and accumulates Out^T = V^T P^T.  A code
-// depends on the row's full sum, so one sweep cannot do both.  No LDS, no barrier.
+// the 64 x 64 latent), so K and V^T cannot live in LDS whole as in the kernels above.  A
+// first kernel writes them once per (prompt, head), in tiles of 32 keys, as the very bytes
+// LDS will hold:
+//   [Kh | Kl]  32 keys x 128 B   fp16 hi / lo of K log2(e) / sqrt(d) (64 dims, zero-padded)
+//   [Vh | Vl]  DV dims x 64 B    bf16 hi / lo of s_b V^T, the 32 key slots of a tile in the
+//                                order the accumulator registers of S^T hold them
+// with the 16-byte slots of every row XOR-permuted by row bits, so that the 16-byte fragment
+// reads of 32 consecutive rows spread over all banks.  The second kernel gives each of its
+// eight wavefronts 32 queries (their fp16 pieces stay in registers) and sweeps the key tiles
+// twice through a three-stage LDS ring filled by direct-to-LDS loads of 1 KiB (the tile
+// image is copied verbatim): sweep A takes the running maximum and sum of 2^(S - max) for
+// lse2, sweep B recomputes S^T bit-identically, forms the codes from log2 s + lse2 - S as
+// above and accumulates Out^T = V^T P^T.  A code depends on the row's full sum, so one
+// sweep cannot do both.  (Read straight from memory by every wavefront, the fragments cost
+// 24 KB of cache traffic per wavefront and tile pair and the texture path, not the matrix
+// cores, set the pace: 5.8 ms on 16 x 10 x 4096 x 64.)
 template <int KS_>
 struct SCfg {
     static constexpr int KS = KS_;
-    static constexpr int DK = 16 * KS;        // halves per key row
     static constexpr int DB = (KS + 1) / 2;   // 32-wide blocks of output dims
     static constexpr int DV = 32 * DB;
-    static constexpr size_t k_tile = 32 * DK;  // elements per tile and piece
-    static constexpr size_t v_tile = DV * 32;
+    static constexpr int K_BYTES = 2 * 32 * 128;   // hi + lo
+    static constexpr int V_BYTES = 2 * DV * 64;    // hi + lo
+    static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
+    static constexpr int K_CHUNKS = K_BYTES / 1024, TILE_CHUNKS = TILE_BYTES / 1024;
+    static constexpr int STAGES = 3;
 };
+constexpr int kSWaves = 8;  // wavefronts per workgroup: 256 queries share every tile
 
 // slot of key j (0..31) of a tile in the V^T rows: inside each 16-key step the lower lane
 // half takes keys 0..3 and 8..11, the upper half keys 4..7 and 12..15
 __device__ __host__ constexpr int v_slot(int j) {
     return 16 * (j >> 4) + 8 * ((j >> 2) & 1) + (j & 3) + 4 * ((j >> 3) & 1);
 }
+// byte offsets inside a tile image: 16-byte slot c of K row j (8 slots) / of V^T row t (4 slots)
+__device__ __host__ constexpr int k_row_slot(int j, int c) { return j * 128 + ((c ^ (j & 7)) << 4); }
+__device__ __host__ constexpr int v_row_slot(int t, int c) { return t * 64 + ((c ^ ((t >> 1) & 3)) << 4); }
+
+#define DGQ_X_LDS_DMA16(sbase, voff, l0)                                              \
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"      \
+                 :                                                                    \
+                 : "v"(voff), "s"(sbase), "s"(l0)                                     \
+                 : "memory", "m0")
+#define DGQ_X_WAIT_VMCNT(N) \
+    __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
 template <class CF>
 __global__ __launch_bounds__(256) void k_selfattn_prep(
     const float *__restrict__ k, const float *__restrict__ v, int32_t nk, int32_t H, int32_t d,
-    float qk_scale, const float *__restrict__ scale_in, int32_t n_tiles, uint16_t *__restrict__ kh,
-    uint16_t *__restrict__ kl, uint16_t *__restrict__ vh, uint16_t *__restrict__ vl) {
-    constexpr int KS = CF::KS, DK = CF::DK, DV = CF::DV;
+    float qk_scale, const float *__restrict__ scale_in, int32_t n_tiles,
+    uint8_t *__restrict__ ws) {
+    constexpr int DV = CF::DV;
     const int32_t tile = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x;
     const int64_t hs = (int64_t)H * d;
@@ -565,19 +583,19 @@ __global__ __launch_bounds__(256) void k_selfattn_prep(
     const float s_eff = s_b > 0.0f ? s_b : 1.0f;
     const float *kb = k + ((int64_t)b * nk * H + head) * d;
     const float *vb = v + ((int64_t)b * nk * H + head) * d;
-    uint16_t *khp = kh + (bh * n_tiles + tile) * CF::k_tile;
-    uint16_t *klp = kl + (bh * n_tiles + tile) * CF::k_tile;
-    uint16_t *vhp = vh + (bh * n_tiles + tile) * CF::v_tile;
-    uint16_t *vlp = vl + (bh * n_tiles + tile) * CF::v_tile;
-    for (int idx = tid; idx < 32 * KS * 4; idx += 256) {
-        const int j = idx / (KS * 4), t4 = (idx - j * (KS * 4)) * 4;
+    uint8_t *img = ws + (bh * n_tiles + tile) * CF::TILE_BYTES;
+    uint8_t *khp = img, *klp = img + 32 * 128;
+    uint8_t *vhp = img + CF::K_BYTES, *vlp = vhp + DV * 64;
+    for (int idx = tid; idx < 32 * 16; idx += 256) {  // 32 keys x 64 dims in fours
+        const int j = idx >> 4, t4 = (idx & 15) * 4;
         const int32_t key = 32 * tile + j;
         float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
         if (key < nk && t4 < d) x = *reinterpret_cast<const float4 *>(kb + (int64_t)key * hs + t4);
         const HiLo p0 = split_h2(x.x * qk_scale, x.y * qk_scale);
         const HiLo p1 = split_h2(x.z * qk_scale, x.w * qk_scale);
-        *reinterpret_cast<u32x2 *>(khp + j * DK + t4) = u32x2{p0.hi, p1.hi};
-        *reinterpret_cast<u32x2 *>(klp + j * DK + t4) = u32x2{p0.lo, p1.lo};
+        const int off = k_row_slot(j, t4 >> 3) + (t4 & 7) * 2;
+        *reinterpret_cast<u32x2 *>(khp + off) = u32x2{p0.hi, p1.hi};
+        *reinterpret_cast<u32x2 *>(klp + off) = u32x2{p0.lo, p1.lo};
     }
     for (int idx = tid; idx < 32 * (DV / 4); idx += 256) {
         const int j = idx / (DV / 4), t4 = (idx - j * (DV / 4)) * 4;
@@ -590,34 +608,34 @@ __global__ __launch_bounds__(256) void k_selfattn_prep(
         for (int e = 0; e < 4; ++e) {
             const uint32_t hb = bf16_rne_bits(xe[e]);
             const uint32_t lb = bf16_rne_bits(xe[e] - __uint_as_float(hb));
-            vhp[(t4 + e) * 32 + slot] = (uint16_t)(hb >> 16);
-            vlp[(t4 + e) * 32 + slot] = (uint16_t)(lb >> 16);
+            const int off = v_row_slot(t4 + e, slot >> 3) + (slot & 7) * 2;
+            *reinterpret_cast<uint16_t *>(vhp + off) = (uint16_t)(hb >> 16);
+            *reinterpret_cast<uint16_t *>(vlp + off) = (uint16_t)(lb >> 16);
         }
     }
 }
 
 template <class CF, bool DUMP>
-__global__ __launch_bounds__(256, 2) void k_selfattn(
+__global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
     const float *__restrict__ q, int32_t BH, int32_t N, int32_t H, int32_t d, int32_t bits,
-    int32_t n_tiles, int32_t q_tiles, const uint16_t *__restrict__ kh,
-    const uint16_t *__restrict__ kl, const uint16_t *__restrict__ vh,
-    const uint16_t *__restrict__ vl, const float *__restrict__ scale_in, float *__restrict__ out,
-    float *__restrict__ scale_out, uint8_t *__restrict__ codes_dump) {
-    constexpr int KS = CF::KS, DK = CF::DK, DB = CF::DB;
+    int32_t n_tiles, int32_t q_tiles, const uint8_t *__restrict__ ws,
+    const float *__restrict__ scale_in, float *__restrict__ out, float *__restrict__ scale_out,
+    uint8_t *__restrict__ codes_dump) {
+    constexpr int KS = CF::KS, DB = CF::DB, DV = CF::DV, STAGES = CF::STAGES;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t ring[];
     // Workgroup w runs on XCD w % 8: give every XCD whole (prompt, head) pairs, so that the
-    // pair's K and V^T pieces (2 MB at 4096 keys) are fetched into one L2 only.
+    // pair's tile images (2 MB at 4096 keys) are fetched into one L2 only.
     const int32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int32_t bh = (slot / q_tiles) * 8 + xcd;
-    if (bh >= BH) return;
+    if (bh >= BH) return;  // the whole workgroup
     const int32_t b = bh / H, head = bh - b * H;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int32_t q0 = ((slot % q_tiles) * 4 + wave) * 32;
-    if (q0 >= N) return;  // wave-uniform; the kernel has no barrier
+    const int32_t q0 = ((slot % q_tiles) * kSWaves + wave) * 32;
     const int n = lane & 31, hh = lane >> 5;
     const int32_t nk = N;
     const int32_t qi = q0 + n;
-    const bool valid = qi < N;
+    const bool valid = qi < N;  // a wave past the end still walks the ring with the others
     const int64_t hs = (int64_t)H * d;
 
     const float s_b = scale_in[b];
@@ -642,18 +660,47 @@ __global__ __launch_bounds__(256, 2) void k_selfattn(
             ql[s] = u32x4{p0.lo, p1.lo, p2.lo, p3.lo};
         }
     }
-    const uint16_t *khb = kh + (int64_t)bh * n_tiles * CF::k_tile + n * DK + 8 * hh;
-    const uint16_t *klb = kl + (int64_t)bh * n_tiles * CF::k_tile + n * DK + 8 * hh;
-    const uint16_t *vhb = vh + (int64_t)bh * n_tiles * CF::v_tile + n * 32 + 8 * hh;
-    const uint16_t *vlb = vl + (int64_t)bh * n_tiles * CF::v_tile + n * 32 + 8 * hh;
 
-    // S^T of key tile kt for the wave's 32 queries, in log2 units; padding keys -inf
+    // ---- the ring: tile kt lives in stage kt % STAGES; wave w copies 1 KiB chunk w of the
+    // K part and, in sweep B, chunk K_CHUNKS + w of the V part (clamped to the last chunk,
+    // which is then copied twice: same bytes, same place)
+    const uint8_t *img0 = ws + (int64_t)bh * n_tiles * CF::TILE_BYTES;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
+    const uint32_t ring0 = (uint32_t)reinterpret_cast<uintptr_t>(
+        (const __attribute__((address_space(3))) uint8_t *)ring);
+    const int vchunk = CF::K_CHUNKS + wave < CF::TILE_CHUNKS ? CF::K_CHUNKS + wave : CF::TILE_CHUNKS - 1;
+    auto issue = [&](const bool with_v, int32_t kt) __attribute__((always_inline)) {
+        const uint8_t *src = img0 + (int64_t)kt * CF::TILE_BYTES;
+        const uint32_t dst = ring0 + (uint32_t)(kt % STAGES) * CF::TILE_BYTES;
+        DGQ_X_LDS_DMA16(src + wave * 1024, lane16, dst + (uint32_t)wave * 1024u);
+        if (with_v) DGQ_X_LDS_DMA16(src + vchunk * 1024, lane16, dst + (uint32_t)vchunk * 1024u);
+    };
+    // One step of a sweep: tile kt has landed for every wave, and the stage the tile after
+    // next goes to is no longer read by anyone.
+    auto advance = [&](const bool with_v, int32_t kt) __attribute__((always_inline)) {
+        asm volatile("" ::: "memory");
+        // the code dump's stores share the counter and need not return in order with loads
+        if (DUMP || kt + 1 >= n_tiles)
+            DGQ_X_WAIT_VMCNT(0);
+        else if (with_v)
+            DGQ_X_WAIT_VMCNT(2);
+        else
+            DGQ_X_WAIT_VMCNT(1);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (kt + 2 < n_tiles) issue(with_v, kt + 2);
+    };
+
+    const int k_off = k_row_slot(n, hh);   // slot 2 s + hh: the step enters as an XOR of 2 s
+    // S^T of the tile in `stage` for the wave's 32 queries, in log2 units; padding keys -inf
     auto s_tile = [&](int32_t kt, v16f &sm) {
+        const uint8_t *st = ring + (kt % STAGES) * CF::TILE_BYTES;
         u32x4 fh[KS], fl[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            fh[s] = *reinterpret_cast<const u32x4 *>(khb + (int64_t)kt * CF::k_tile + 16 * s);
-            fl[s] = *reinterpret_cast<const u32x4 *>(klb + (int64_t)kt * CF::k_tile + 16 * s);
+            const int off = k_off ^ (s << 5);
+            fh[s] = *reinterpret_cast<const u32x4 *>(st + off);
+            fl[s] = *reinterpret_cast<const u32x4 *>(st + 32 * 128 + off);
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) sm[i] = 0.0f;
@@ -676,7 +723,10 @@ __global__ __launch_bounds__(256, 2) void k_selfattn(
 
     // ---- sweep A: lse2 of the lane's query (each lane half sees half of the keys) -------
     float m = -INFINITY, l = 0.0f;
+    issue(false, 0);
+    if (n_tiles > 1) issue(false, 1);
     for (int32_t kt = 0; kt < n_tiles; ++kt) {
+        advance(false, kt);
         v16f sm;
         s_tile(kt, sm);
         float tm = sm[0];
@@ -700,7 +750,7 @@ __global__ __launch_bounds__(256, 2) void k_selfattn(
             // the row's largest probability; probabilities order like their bit patterns
             float amax = valid ? m2 - lse : -INFINITY;
             amax = wave_max(amax);
-            if (lane == 0)
+            if (lane == 0 && q0 < N)
                 atomicMax(reinterpret_cast<unsigned int *>(scale_out + b),
                           __float_as_uint(__builtin_amdgcn_exp2f(amax)));
         }
@@ -719,17 +769,25 @@ __global__ __launch_bounds__(256, 2) void k_selfattn(
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
+    const int v_off = v_row_slot(n, hh);  // slot 2 u + hh: the step enters as an XOR of 2 u
+    __builtin_amdgcn_s_barrier();  // every wave has left sweep A's last stage
+    asm volatile("" ::: "memory");
+    issue(true, 0);
+    if (n_tiles > 1) issue(true, 1);
     for (int32_t kt = 0; kt < n_tiles; ++kt) {
+        advance(true, kt);
         v16f sm;
         s_tile(kt, sm);
-        // V^T fragments of this tile: issued before the code arithmetic that hides them
+        const uint8_t *st = ring + (kt % STAGES) * CF::TILE_BYTES + CF::K_BYTES;
+        // V^T fragments of this tile: read before the code arithmetic that hides them
         u32x4 fvh[DB][2], fvl[DB][2];
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                fvh[db][u] = *reinterpret_cast<const u32x4 *>(vhb + (int64_t)kt * CF::v_tile + db * 32 * 32 + 16 * u);
-                fvl[db][u] = *reinterpret_cast<const u32x4 *>(vlb + (int64_t)kt * CF::v_tile + db * 32 * 32 + 16 * u);
+                const int off = db * 32 * 64 + (v_off ^ (u << 5));
+                fvh[db][u] = *reinterpret_cast<const u32x4 *>(st + off);
+                fvl[db][u] = *reinterpret_cast<const u32x4 *>(st + DV * 64 + off);
             }
         uint32_t pk[8];
 #pragma unroll
@@ -781,23 +839,21 @@ hipError_t launch_selfattn_cfg(const float *q, const float *k, const float *v, i
                                float *scale_out, uint8_t *codes_dump, void *workspace,
                                hipStream_t st) {
     const int32_t n_tiles = (N + 31) / 32, BH = B * H;
-    uint16_t *kh = static_cast<uint16_t *>(workspace);
-    uint16_t *kl = kh + (size_t)BH * n_tiles * CF::k_tile;
-    uint16_t *vh = kl + (size_t)BH * n_tiles * CF::k_tile;
-    uint16_t *vl = vh + (size_t)BH * n_tiles * CF::v_tile;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
     const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
     if (scale_out) hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
     hipLaunchKernelGGL(k_selfattn_prep<CF>, dim3(n_tiles, H, B), dim3(256), 0, st, k, v, N, H, d,
-                       qk_scale, scale_in, n_tiles, kh, kl, vh, vl);
-    const int32_t q_tiles = (N + 127) / 128;
+                       qk_scale, scale_in, n_tiles, ws);
+    const int32_t q_tiles = (N + 32 * kSWaves - 1) / (32 * kSWaves);
     const int64_t groups = ((int64_t)BH + 7) / 8;
     const dim3 grid((unsigned)(groups * q_tiles * 8));
+    const size_t lds = (size_t)CF::STAGES * CF::TILE_BYTES;
     if (codes_dump)
-        hipLaunchKernelGGL((k_selfattn<CF, true>), grid, dim3(256), 0, st, q, BH, N, H, d, bits, n_tiles,
-                           q_tiles, kh, kl, vh, vl, scale_in, out, scale_out, codes_dump);
+        hipLaunchKernelGGL((k_selfattn<CF, true>), grid, dim3(64 * kSWaves), lds, st, q, BH, N, H, d, bits,
+                           n_tiles, q_tiles, ws, scale_in, out, scale_out, codes_dump);
     else
-        hipLaunchKernelGGL((k_selfattn<CF, false>), grid, dim3(256), 0, st, q, BH, N, H, d, bits, n_tiles,
-                           q_tiles, kh, kl, vh, vl, scale_in, out, scale_out, codes_dump);
+        hipLaunchKernelGGL((k_selfattn<CF, false>), grid, dim3(64 * kSWaves), lds, st, q, BH, N, H, d, bits,
+                           n_tiles, q_tiles, ws, scale_in, out, scale_out, codes_dump);
     return hipGetLastError();
 }
 
@@ -1067,9 +1123,9 @@ static int selfattn_ks(int32_t d) { return d <= 16 ? 1 : (d <= 32 ? 2 : (d <= 48
 
 size_t selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d) {
     if (d % 8 != 0 || d > 64 || d < 8) return 0;
-    const size_t ks = (size_t)selfattn_ks(d), dk = 16 * ks, dv = 32 * ((ks + 1) / 2);
+    const size_t dv = 32 * (((size_t)selfattn_ks(d) + 1) / 2);
     const size_t n_tiles = ((size_t)N + 31) / 32;
-    return (size_t)B * H * n_tiles * (32 * dk + dv * 32) * 2 * sizeof(uint16_t);
+    return (size_t)B * H * n_tiles * (2 * 32 * 128 + 2 * dv * 64);  // one tile image per 32 keys
 }
 
 hipError_t launch_selfattn(const float *q, const float *k, const float *v, int32_t B, int32_t N,
