@@ -483,6 +483,30 @@ def main():
                                     gbs_attention_given_scale=round(nominal / us_s / 1e3, 1)))
             del vhat
 
+    # ---------------- beyond the step: self-attention with log2-quantized probabilities ------
+    # The 4096-token self-attention of the 64 x 64 latent at the sweep's batch (16 prompts x 10
+    # heads of 64) with 8-bit codes against the scale 1.  Flops: the method's two products,
+    # 4 N^2 d per (prompt, head); the kernel issues four times that on the matrix cores (the
+    # logits twice, each as three fp16 products, and P^ V as two bf16 products).
+    self_attn = []
+    if args.workload == "config5" and not args.step_only:
+        for (B_, N_, H_, d_) in ((16, 4096, 10, 64), (16, 1024, 20, 64)):
+            c_ = di.selfattn_case(77, 1, N_, H_, d_)
+            qs, ks, vs = (up(c_[n]).expand(B_, N_, H_, d_).contiguous() for n in ("Q", "K", "V"))
+            outs = torch.empty_like(qs)
+            ones = torch.ones(B_, dtype=torch.float32, device=dev)
+            wss = torch.empty(int(L.dgq_selfattn_workspace_bytes(B_, N_, H_, d_)), dtype=torch.uint8, device=dev)
+            us = time_calls(L.dgq_selfattn_logq, (ptr(qs), ptr(ks), ptr(vs), B_, N_, H_, d_, 8, ptr(ones),
+                                                  ptr(outs), None, None, ptr(wss), C.c_size_t(wss.numel()), sp),
+                            n_rep=5)
+            flops = 4.0 * B_ * H_ * N_ * N_ * d_
+            self_attn.append(dict(B=B_, N=N_, H=H_, d=d_, attn_bits=8, us=round(us, 1),
+                                  tflops_method=round(flops / us / 1e6, 1),
+                                  tflops_issued=round(4 * flops / us / 1e6, 1),
+                                  frac_f16_mfma_peak_issued=round(4 * flops / us / 1e6 / 2500.0, 4),
+                                  workspace_bytes=int(wss.numel())))
+            del qs, ks, vs, outs, wss
+
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -519,7 +543,7 @@ def main():
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
-                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, cpu_baseline=cpu)
+                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, self_attention=self_attn, cpu_baseline=cpu)
     print(json.dumps(line))
 
 
