@@ -260,7 +260,7 @@ int dgq_linear_geglu(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t 
  * The following layer must be grouped along the channel dimension only (one pixel class:
  * dgq_calibrate_kmeans with the channel dimension, or dgq_calibrate_groups with
  * n_pixel_classes = 1), so that a code depends on nothing but its own value and its
- * channel's group, and must use 8-bit codes.
+ * channel's group; its codes may be 8 or 4 bits wide.
  *
  * dgq_pack_weight_gated_for (offline, blocking): as dgq_pack_weight for layer g, whose
  * out_channels = 2 * (channels of g_next) rows of w are [value rows | gate rows]; the
@@ -273,8 +273,9 @@ int dgq_linear_geglu(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t 
  * allocates):
  *   codes, row_class: of layer g, as written by dgq_quantize_act
  *   codes_next: dgq_codes_bytes(g_next, rows) bytes; receives exactly what
- *               dgq_quantize_act(g_next, out) would write (stored code = q - 128, padding
- *               positions 0, rows past `rows` in the last 16-row block untouched), up to
+ *               dgq_quantize_act(g_next, out) would write (8-bit: stored code = q - 128;
+ *               4-bit: packed nibbles; padding positions 0; rows past `rows` in the last
+ *               row block untouched), up to
  *               the rounding of out: a code whose pre-rounding value (out - z) / s lies
  *               within the fp32 error of out of a half-integer may differ by one
  *   row_class_next: u8 [rows], receives zeros (the single pixel class)

@@ -621,6 +621,7 @@ int pack_weight(const char *who, const Groups *g, const Groups *next, const floa
         const int32_t kn = next->info.k_padded, half = out_channels / 2;
         wt->next_channels = half;
         wt->next_kp = kn;
+        wt->next_bits = next->info.act_bits;
         std::vector<int32_t> map((size_t)2 * kn);
         std::vector<uint8_t> keep((size_t)kn);
         std::vector<float2> zi((size_t)next->n_chunks);
@@ -690,10 +691,10 @@ int dgq_pack_weight_gated_for(const dgq_groups_t *h, const dgq_groups_t *h_next,
     const Groups *next = reinterpret_cast<const Groups *>(h_next);
     if (next->info.channels != out_channels / 2)
         return fail(DGQ_ESHAPE, "dgq_pack_weight_gated_for: the following layer must take out_channels / 2 channels");
-    if (next->info.n_pixel_classes != 1 || next->info.act_bits != 8)
+    if (next->info.n_pixel_classes != 1)
         return fail(DGQ_EUNSUPPORTED,
                     "dgq_pack_weight_gated_for: the following layer needs one pixel class (its "
-                    "quantizer must not depend on a row statistic) and 8-bit codes");
+                    "quantizer must not depend on a row statistic)");
     if (g->n_tab > 2)
         return fail(DGQ_EUNSUPPORTED, "dgq_pack_weight_gated_for: this layer needs at most two pixel classes");
     return pack_weight("dgq_pack_weight_gated_for", g, next, w, bias, out_channels, w_bits,

@@ -68,7 +68,7 @@ struct Weight {
     // Packed for a gated layer whose output feeds `next_channels` channels of a following
     // layer directly: output rows are in that layer's K' order (value rows, then gate
     // rows), and the two tables its quantizer needs travel with the weights.
-    int32_t next_channels = 0, next_kp = 0;
+    int32_t next_channels = 0, next_kp = 0, next_bits = 8;
     float2 *d_rq_zi = nullptr;     // [next_kp / 64] (offset, 1 / step) of each chunk
     uint8_t *d_rq_keep = nullptr;  // [next_kp] 0xFF, or 0 at padding positions
     int device = 0;

@@ -129,7 +129,7 @@ struct Cfg {
 // GEGLU == 2 (gated + requantized): the tile's output channels are, in order, the K'
 // positions of the NEXT layer's channel groups (the weight rows were packed in that
 // order), that layer has one pixel class, and the epilogue puts value * GELU(gate) straight
-// through its quantizer: y is that layer's block-tiled 8-bit code buffer, rq_zi the
+// through its quantizer: y is that layer's block-tiled code buffer (rq_bits wide), rq_zi the
 // (offset, 1 / step) of each of its 64-position chunks, rq_keep one byte per position
 // (0xFF, or 0 for padding, whose stored code is 0), rq_cls its row classes (all 0).  The
 // fp32 activation between the two layers never reaches memory.
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     int32_t O_pad, int32_t Kp, int32_t NG, int32_t tiles_r, int32_t tiles_o, int32_t per_xcd,
     int32_t super_rows, float *__restrict__ y, int32_t *__restrict__ acc_dump,
     const float2 *__restrict__ rq_zi, const uint8_t *__restrict__ rq_keep,
-    uint8_t *__restrict__ rq_cls) {
+    uint8_t *__restrict__ rq_cls, int32_t rq_bits) {
     constexpr int ABITS = CF::ABITS, BR = CF::BR, BO = CF::BO, STAGES = CF::STAGES;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -477,6 +477,43 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                 const uint32_t lane_off0 = row_part + ((kq ^ ((uint32_t)kh | ((j >> 1) << 1))) << 4);
                 const uint32_t lane_off1 = row_part + ((kq ^ ((uint32_t)kh | (((j >> 1) ^ 1u) << 1))) << 4);
                 const uint32_t sel = ((4u + j) << 8) | j;  // byte j of each of two sources
+                // 4-bit codes for the next layer: blocks of 32 rows x 32 bytes, a dword holds
+                // 8 positions (byte i: position i in the low, i + 4 in the high nibble).  After
+                // the same transpose the even quad of a pair holds the low nibbles, the odd
+                // quad (four lanes up) the high ones; the even quads store.  Row t = 8 g + 4 kh + j
+                // of the block has slot swizzle g % 2.
+                if (rq_bits == 4) {
+                    const uint32_t eb = (uint32_t)((posw & 63) >> 3) + (c >> 1);  // 8-position block in the chunk
+                    const uint32_t row4 = (4u * (uint32_t)kh + j) * 32u + 4u * (eb & 3u);
+                    const uint32_t l4_0 = row4 + ((eb >> 2) << 4), l4_1 = row4 + (((eb >> 2) ^ 1u) << 4);
+#pragma unroll
+                    for (int a = 0; a < BR; ++a) {
+                        const int64_t rb = (r0 + (wr * BR + a) * 32) >> 5;
+                        int8_t *blk = cout + ((rb * nch2 + chunk) << 10);
+#pragma unroll
+                        for (int g4 = 0; g4 < 4; ++g4) {
+                            uint32_t pk = 0;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const float t = __fsub_rn(facc[a][0][4 * g4 + k], zi.x);
+                                const float u = __builtin_amdgcn_fmed3f(__fmul_rn(t, zi.y), 0.0f, 15.0f);
+                                pk = __builtin_amdgcn_cvt_pk_u8_f32(u, k, pk);
+                            }
+                            pk &= keep;
+                            const uint32_t q0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0x00, 0xf, 0xf, false);
+                            const uint32_t q1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0x55, 0xf, 0xf, false);
+                            const uint32_t q2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0xaa, 0xf, 0xf, false);
+                            const uint32_t q3 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)pk, 0xff, 0xf, 0xf, false);
+                            const uint32_t x01 = __builtin_amdgcn_perm(q1, q0, sel);
+                            const uint32_t x23 = __builtin_amdgcn_perm(q3, q2, sel);
+                            const uint32_t low = __builtin_amdgcn_perm(x23, x01, 0x05040100u);
+                            const uint32_t high = (uint32_t)__shfl_down((int)low, 4, 64);
+                            const uint32_t lo = ((g4 & 1) ? l4_1 : l4_0) + 256u * g4;
+                            if (!(c & 1u) && !((past[a] >> (4 * g4 + (int)j)) & 1))
+                                *reinterpret_cast<uint32_t *>(blk + lo) = low | (high << 4);
+                        }
+                    }
+                } else
 #pragma unroll
                 for (int a = 0; a < BR; ++a) {
                     const int64_t rb = (r0 + (wr * BR + a) * 32) >> 4;
@@ -744,7 +781,8 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
                        w.d_zb, g.d_s, g.d_zoff, g.n_tab, g.d_gchunk, rows, w.O, w.O_pad, w.Kp,
                        g.info.n_groups,
-                       tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump, w.d_rq_zi, w.d_rq_keep, rq_cls);
+                       tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump, w.d_rq_zi, w.d_rq_keep, rq_cls,
+                       w.next_bits);
     return hipGetLastError();
 }
 

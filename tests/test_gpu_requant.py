@@ -51,7 +51,8 @@ def _oracle_h(oracle, og1, X, W, bias):
     return oy, oracle.geglu(oy)
 
 
-def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=None, cal_rows=256):
+def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=None, cal_rows=256,
+         next_bits=8):
     """Layer 1: C1 -> 2 C2 (hybrid grid, two pixel classes, act_bits codes); layer 2 takes
     the C2 gated channels with 8-bit codes and channel groups only."""
     import torch
@@ -72,11 +73,11 @@ def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=No
     crow = np.sort(rng.choice(rows, min(cal_rows, rows), replace=False))
     _, hcal = _oracle_h(oracle, og1, cal["X"][crow], W, bias)
     if next_kind == "kmeans":
-        og2 = oracle.calibrate_kmeans(hcal, 8, K, 0)
-        g2 = dgq.dgq_calibrate_kmeans(_dev(hcal), 8, K, dgq.DIM_CHANNEL)
+        og2 = oracle.calibrate_kmeans(hcal, next_bits, K, 0)
+        g2 = dgq.dgq_calibrate_kmeans(_dev(hcal), next_bits, K, dgq.DIM_CHANNEL)
     else:
-        og2 = oracle.calibrate(hcal, 8, 64, 1)
-        g2 = dgq.dgq_calibrate_groups(_dev(hcal), 8, 64, 1)
+        og2 = oracle.calibrate(hcal, next_bits, 64, 1)
+        g2 = dgq.dgq_calibrate_groups(_dev(hcal), next_bits, 64, 1)
     assert g2.info.n_pixel_classes == 1 and g2.info.k_padded == og2.Kp
     t2 = g2.tables()
     assert np.array_equal(t2["perm"], og2.perm)
@@ -102,9 +103,9 @@ def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=No
     # oracle chain on the selected rows
     oy, h = _oracle_h(oracle, og1, X[sel], W, bias)
     oq2 = oracle.quantize_act(og2, h)
-    q_gpu = codes_to_q(codes2.cpu().numpy(), 8, og2.Kp, rows)[sel].astype(np.int64)
+    q_gpu = codes_to_q(codes2.cpu().numpy(), next_bits, og2.Kp, rows)[sel].astype(np.int64)
     real = og2.perm >= 0
-    assert np.all(q_gpu[:, ~real] == 128)           # stored 0 at padding positions
+    assert np.all(q_gpu[:, ~real] == (128 if next_bits == 8 else 0))   # stored 0 at padding positions
     q_ref = oq2["q"][:, real].astype(np.int64)
     q_got = q_gpu[:, real]
     # distance of each decision from a rounding boundary, in steps, from the oracle's h
@@ -121,13 +122,13 @@ def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=No
     allow_h = 1e-5 * np.abs(oy).max() * (np.abs(_gelu64(b)) + 1.13 * np.abs(a)) \
         + 2e-6 * np.abs(h) + 5e-7 * np.abs(a).max() * np.abs(b).max()
     allow_u = allow_h[:, ch] / s
-    inside = (u > -0.5) & (u < 255.5)                # outside, both sides saturate
+    inside = (u > -0.5) & (u < (1 << next_bits) - 0.5)   # outside, both sides saturate
     decided = (margin >= allow_u) | ~inside
     diff = q_got != q_ref
     assert not (diff & decided).any(), "%d decided codes differ" % int((diff & decided).sum())
     assert np.abs(q_got - q_ref).max() <= 1
     assert diff.mean() < 2e-3, "too many codes differ: %.2e" % diff.mean()
-    assert np.unique(q_ref).size > 30  # not a trivial case
+    assert np.unique(q_ref).size > (30 if next_bits == 8 else 8)  # not a trivial case
     for hnd in (wt_f, wt, g1, g2):
         hnd.free()
     return float(decided.mean()), float(diff.mean())
@@ -151,6 +152,24 @@ def test_small_and_ragged(dgq, oracle, B, N, C1, C2, G, ab, next_kind):
     assert decided > 0.9
 
 
+@pytest.mark.parametrize("next_kind", ["kmeans", "blocks"])
+@pytest.mark.parametrize("B,N,C1,C2,G,ab", [
+    (2, 150, 328, 256, 64, 8),
+    (2, 1111, 200, 640, 64, 4),
+    (2, 2500, 136, 896, 64, 8),
+])
+def test_four_bit_codes_for_the_following_layer(dgq, oracle, B, N, C1, C2, G, ab, next_kind):
+    M = B * N
+    sample = None
+    if M > 1000:
+        rng = np.random.default_rng(C2 + 1)
+        sample = np.unique(np.concatenate([rng.choice(M, 40, replace=False),
+                                           [0, 31, 32, 63, 64, 127, 128, M - 130, M - 33, M - 32, M - 1]]))
+    decided, _ = _run(dgq, oracle, B, N, C1, C2, G, ab, 950 + C1 + C2, next_kind, sample=sample,
+                      next_bits=4)
+    assert decided > 0.99
+
+
 def test_config5_feed_forward_sampled(dgq, oracle):
     """ff.in -> ff.out of the SDXL-scale sweep at full size (16384 x 1280 -> 2 x 5120 ->
     codes of the 5120-channel layer), sampled rows."""
@@ -168,9 +187,8 @@ def test_argument_errors(dgq):
     h = _dev(np.random.default_rng(0).standard_normal((64, 256)).astype(np.float32))
     g2 = dgq.dgq_calibrate_kmeans(h, 8, 4, dgq.DIM_CHANNEL)
     g2p = dgq.dgq_calibrate_kmeans(h, 8, 4, dgq.DIM_PIXEL)       # needs a row statistic
-    g2a4 = dgq.dgq_calibrate_kmeans(h, 4, 4, dgq.DIM_CHANNEL)    # 4-bit codes
     w = _dev(run["W"])
-    for bad in (g2p, g2a4):
+    for bad in (g2p,):
         with pytest.raises(dgq.DgqError) as e:
             dgq.dgq_pack_weight_gated_for(g1, bad, w, None, 8)
         assert e.value.code == -4
@@ -191,5 +209,5 @@ def test_argument_errors(dgq):
     assert e.value.code == -3
     import torch
     torch.cuda.synchronize()
-    for hnd in (wf, wp, g1, g2, g2p, g2a4):
+    for hnd in (wf, wp, g1, g2, g2p):
         hnd.free()
