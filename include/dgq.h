@@ -357,7 +357,7 @@ int dgq_xattn_logq_static(const float *q, const float *k, const float *v,
  *   codes_dump: NULL, or u8 [B, H, N, N] receiving every code (debug / parity)
  *   workspace: dgq_selfattn_workspace_bytes(B, N, H, d) bytes, 16-byte aligned; holds K
  *              and V^T in the matrix cores' operand pieces, rewritten by every call
- * d % 8 == 0 and d <= 64 (DGQ_EUNSUPPORTED otherwise; the workspace size reads 0).
+ * d % 8 == 0 and d <= 160 (DGQ_EUNSUPPORTED otherwise; the workspace size reads 0).
  * attn_bits in {4, 8}.  Enqueues on `stream`; does not synchronise or allocate.
  */
 size_t dgq_selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d);

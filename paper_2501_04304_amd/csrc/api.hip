@@ -885,8 +885,8 @@ int dgq_selfattn_logq(const float *q, const float *k, const float *v, int32_t B,
     if (B < 1 || N < 1 || H < 1 || d < 1) return fail(DGQ_EINVAL, "dgq_selfattn_logq: empty shape");
     if (attn_bits != 4 && attn_bits != 8)
         return fail(DGQ_EINVAL, "dgq_selfattn_logq: attn_bits must be 4 or 8");
-    if (d % 8 != 0 || d > 64)
-        return fail(DGQ_EUNSUPPORTED, "dgq_selfattn_logq: head dimension must be a multiple of 8, at most 64");
+    if (d % 8 != 0 || d > 160)
+        return fail(DGQ_EUNSUPPORTED, "dgq_selfattn_logq: head dimension must be a multiple of 8, at most 160");
     if ((int64_t)B * H > (1 << 20) || N > (1 << 20))
         return fail(DGQ_EUNSUPPORTED, "dgq_selfattn_logq: too many (prompt, head) pairs or tokens");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(workspace))

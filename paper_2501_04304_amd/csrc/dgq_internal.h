@@ -134,7 +134,7 @@ hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t 
                                  hipStream_t st);
 
 // Self-attention with every probability log2-quantized against the given scale; needs
-// d % 8 == 0, 8 <= d <= 64 and a workspace of selfattn_workspace_bytes.
+// d % 8 == 0, 8 <= d <= 160 and a workspace of selfattn_workspace_bytes.
 hipError_t launch_selfattn(const float *q, const float *k, const float *v, int32_t B, int32_t N,
                            int32_t H, int32_t d, int32_t bits, const float *scale_in, float *out,
                            float *scale_out, uint8_t *codes_dump, void *workspace, hipStream_t st);

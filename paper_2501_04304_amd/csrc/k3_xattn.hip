@@ -526,7 +526,8 @@ bool mfma_shape(int32_t d, int32_t nk) { return (d % 8) == 0 && d <= 96 && nk + 
 // the 64 x 64 latent), so K and V^T cannot live in LDS whole as in the kernels above.  A
 // first kernel writes them once per (prompt, head), in tiles of 32 keys, as the very bytes
 // LDS will hold:
-//   [Kh | Kl]  32 keys x 128 B   fp16 hi / lo of K log2(e) / sqrt(d) (64 dims, zero-padded)
+//   [Kh | Kl]  32 keys x PITCH   fp16 hi / lo of K log2(e) / sqrt(d) (64, 128 or 192 dims,
+//                                zero-padded)
 //   [Vh | Vl]  DV dims x 64 B    bf16 hi / lo of s_b V^T, the 32 key slots of a tile in the
 //                                order the accumulator registers of S^T hold them
 // with the 16-byte slots of every row XOR-permuted by row bits, so that the 16-byte fragment
@@ -544,11 +545,17 @@ struct SCfg {
     static constexpr int KS = KS_;
     static constexpr int DB = (KS + 1) / 2;   // 32-wide blocks of output dims
     static constexpr int DV = 32 * DB;
-    static constexpr int K_BYTES = 2 * 32 * 128;   // hi + lo
+    static constexpr int PITCH = 128 * ((KS + 3) / 4);  // bytes per K row: whole groups of 8 slots
+    static constexpr int K_BYTES = 2 * 32 * PITCH;      // hi + lo
     static constexpr int V_BYTES = 2 * DV * 64;    // hi + lo
     static constexpr int TILE_BYTES = K_BYTES + V_BYTES;
     static constexpr int K_CHUNKS = K_BYTES / 1024, TILE_CHUNKS = TILE_BYTES / 1024;
     static constexpr int STAGES = 3;
+    // direct-to-LDS loads per wave and tile (8 waves): sweep A copies the K part, sweep B all
+    static constexpr int LA = K_CHUNKS / 8, LB = (TILE_CHUNKS + 7) / 8;
+    // wavefronts per SIMD the registers are budgeted for: the query pieces and the output
+    // blocks of a wide head take most of the file
+    static constexpr int OCC = KS <= 4 ? 2 : 1;
 };
 constexpr int kSWaves = 8;  // wavefronts per workgroup: 256 queries share every tile
 
@@ -557,8 +564,9 @@ constexpr int kSWaves = 8;  // wavefronts per workgroup: 256 queries share every
 __device__ __host__ constexpr int v_slot(int j) {
     return 16 * (j >> 4) + 8 * ((j >> 2) & 1) + (j & 3) + 4 * ((j >> 3) & 1);
 }
-// byte offsets inside a tile image: 16-byte slot c of K row j (8 slots) / of V^T row t (4 slots)
-__device__ __host__ constexpr int k_row_slot(int j, int c) { return j * 128 + ((c ^ (j & 7)) << 4); }
+// byte offsets inside a tile image: 16-byte slot c of K row j (the XOR stays inside a group
+// of 8 slots) / of V^T row t (4 slots)
+__device__ __host__ constexpr int k_row_slot(int pitch, int j, int c) { return j * pitch + ((c ^ (j & 7)) << 4); }
 __device__ __host__ constexpr int v_row_slot(int t, int c) { return t * 64 + ((c ^ ((t >> 1) & 3)) << 4); }
 
 #define DGQ_X_LDS_DMA16(sbase, voff, l0)                                              \
@@ -584,16 +592,17 @@ __global__ __launch_bounds__(256) void k_selfattn_prep(
     const float *kb = k + ((int64_t)b * nk * H + head) * d;
     const float *vb = v + ((int64_t)b * nk * H + head) * d;
     uint8_t *img = ws + (bh * n_tiles + tile) * CF::TILE_BYTES;
-    uint8_t *khp = img, *klp = img + 32 * 128;
+    uint8_t *khp = img, *klp = img + 32 * CF::PITCH;
     uint8_t *vhp = img + CF::K_BYTES, *vlp = vhp + DV * 64;
-    for (int idx = tid; idx < 32 * 16; idx += 256) {  // 32 keys x 64 dims in fours
-        const int j = idx >> 4, t4 = (idx & 15) * 4;
+    constexpr int QUADS = CF::PITCH / 8;  // fours of dims per K row
+    for (int idx = tid; idx < 32 * QUADS; idx += 256) {
+        const int j = idx / QUADS, t4 = (idx - j * QUADS) * 4;
         const int32_t key = 32 * tile + j;
         float4 x = {0.0f, 0.0f, 0.0f, 0.0f};
         if (key < nk && t4 < d) x = *reinterpret_cast<const float4 *>(kb + (int64_t)key * hs + t4);
         const HiLo p0 = split_h2(x.x * qk_scale, x.y * qk_scale);
         const HiLo p1 = split_h2(x.z * qk_scale, x.w * qk_scale);
-        const int off = k_row_slot(j, t4 >> 3) + (t4 & 7) * 2;
+        const int off = k_row_slot(CF::PITCH, j, t4 >> 3) + (t4 & 7) * 2;
         *reinterpret_cast<u32x2 *>(khp + off) = u32x2{p0.hi, p1.hi};
         *reinterpret_cast<u32x2 *>(klp + off) = u32x2{p0.lo, p1.lo};
     }
@@ -616,7 +625,7 @@ __global__ __launch_bounds__(256) void k_selfattn_prep(
 }
 
 template <class CF, bool DUMP>
-__global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
+__global__ __launch_bounds__(64 * kSWaves, CF::OCC) void k_selfattn(
     const float *__restrict__ q, int32_t BH, int32_t N, int32_t H, int32_t d, int32_t bits,
     int32_t n_tiles, int32_t q_tiles, const uint8_t *__restrict__ ws,
     const float *__restrict__ scale_in, float *__restrict__ out, float *__restrict__ scale_out,
@@ -662,18 +671,22 @@ __global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
     }
 
     // ---- the ring: tile kt lives in stage kt % STAGES; wave w copies 1 KiB chunk w of the
-    // K part and, in sweep B, chunk K_CHUNKS + w of the V part (clamped to the last chunk,
-    // which is then copied twice: same bytes, same place)
+    // image, w + 8, ... (sweep A: the K part only; past the last chunk a wave copies the last
+    // one again: same bytes, same place)
     const uint8_t *img0 = ws + (int64_t)bh * n_tiles * CF::TILE_BYTES;
     const uint32_t lane16 = (uint32_t)lane * 16u;
     const uint32_t ring0 = (uint32_t)reinterpret_cast<uintptr_t>(
         (const __attribute__((address_space(3))) uint8_t *)ring);
-    const int vchunk = CF::K_CHUNKS + wave < CF::TILE_CHUNKS ? CF::K_CHUNKS + wave : CF::TILE_CHUNKS - 1;
     auto issue = [&](const bool with_v, int32_t kt) __attribute__((always_inline)) {
         const uint8_t *src = img0 + (int64_t)kt * CF::TILE_BYTES;
         const uint32_t dst = ring0 + (uint32_t)(kt % STAGES) * CF::TILE_BYTES;
-        DGQ_X_LDS_DMA16(src + wave * 1024, lane16, dst + (uint32_t)wave * 1024u);
-        if (with_v) DGQ_X_LDS_DMA16(src + vchunk * 1024, lane16, dst + (uint32_t)vchunk * 1024u);
+#pragma unroll
+        for (int j = 0; j < CF::LB; ++j) {
+            if (!with_v && j >= CF::LA) break;
+            int c = wave + kSWaves * j;
+            c = c < CF::TILE_CHUNKS ? c : CF::TILE_CHUNKS - 1;
+            DGQ_X_LDS_DMA16(src + c * 1024, lane16, dst + (uint32_t)c * 1024u);
+        }
     };
     // One step of a sweep: tile kt has landed for every wave, and the stage the tile after
     // next goes to is no longer read by anyone.
@@ -683,25 +696,30 @@ __global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
         if (DUMP || kt + 1 >= n_tiles)
             DGQ_X_WAIT_VMCNT(0);
         else if (with_v)
-            DGQ_X_WAIT_VMCNT(2);
+            DGQ_X_WAIT_VMCNT(CF::LB);
         else
-            DGQ_X_WAIT_VMCNT(1);
+            DGQ_X_WAIT_VMCNT(CF::LA);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (kt + 2 < n_tiles) issue(with_v, kt + 2);
     };
 
-    const int k_off = k_row_slot(n, hh);   // slot 2 s + hh: the step enters as an XOR of 2 s
+    // slot 2 s + hh: s % 4 enters as an XOR (bits 1..2 of the slot), s / 4 as a group of 8 slots
+    const int k_off = k_row_slot(CF::PITCH, n, hh);
     // S^T of the tile in `stage` for the wave's 32 queries, in log2 units; padding keys -inf
     auto s_tile = [&](int32_t kt, v16f &sm) {
         const uint8_t *st = ring + (kt % STAGES) * CF::TILE_BYTES;
-        u32x4 fh[KS], fl[KS];
+        // all fragments of a narrow head are read up front; a wide head (whose query pieces
+        // and output blocks fill the register file) reads them one step ahead of their MFMAs
+        constexpr int NF = KS <= 4 ? KS : 2;
+        u32x4 fh[NF], fl[NF];
+        auto frag = [&](int s) __attribute__((always_inline)) {
+            const int off = (k_off ^ ((s & 3) << 5)) + 128 * (s >> 2);
+            fh[s % NF] = *reinterpret_cast<const u32x4 *>(st + off);
+            fl[s % NF] = *reinterpret_cast<const u32x4 *>(st + 32 * CF::PITCH + off);
+        };
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int off = k_off ^ (s << 5);
-            fh[s] = *reinterpret_cast<const u32x4 *>(st + off);
-            fl[s] = *reinterpret_cast<const u32x4 *>(st + 32 * 128 + off);
-        }
+        for (int s = 0; s < (KS <= 4 ? KS : 1); ++s) frag(s);
 #pragma unroll
         for (int i = 0; i < 16; ++i) sm[i] = 0.0f;
         if (32 * kt + 32 > nk) {
@@ -711,10 +729,11 @@ __global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
         }
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
+            if (KS > 4 && s + 1 < KS) frag(s + 1);
             const v8h bqh = __builtin_bit_cast(v8h, qh[s]);
             const v8h bql = __builtin_bit_cast(v8h, ql[s]);
-            const v8h akh = __builtin_bit_cast(v8h, fh[s]);
-            const v8h akl = __builtin_bit_cast(v8h, fl[s]);
+            const v8h akh = __builtin_bit_cast(v8h, fh[s % NF]);
+            const v8h akl = __builtin_bit_cast(v8h, fl[s % NF]);
             sm = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bqh, sm, 0, 0, 0);
             sm = __builtin_amdgcn_mfma_f32_32x32x16_f16(akh, bql, sm, 0, 0, 0);
             sm = __builtin_amdgcn_mfma_f32_32x32x16_f16(akl, bqh, sm, 0, 0, 0);
@@ -779,16 +798,21 @@ __global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
         v16f sm;
         s_tile(kt, sm);
         const uint8_t *st = ring + (kt % STAGES) * CF::TILE_BYTES + CF::K_BYTES;
-        // V^T fragments of this tile: read before the code arithmetic that hides them
-        u32x4 fvh[DB][2], fvl[DB][2];
+        // V^T fragments of this tile.  Narrow heads: all read before the code arithmetic that
+        // hides them; wide heads: each right before its MFMAs (registers)
+        constexpr bool V_AHEAD = DB <= 2;
+        auto v_frag = [&](int db, int u, u32x4 &h, u32x4 &l) __attribute__((always_inline)) {
+            const int off = db * 32 * 64 + (v_off ^ (u << 5));
+            h = *reinterpret_cast<const u32x4 *>(st + off);
+            l = *reinterpret_cast<const u32x4 *>(st + DV * 64 + off);
+        };
+        u32x4 fvh[V_AHEAD ? DB : 1][2], fvl[V_AHEAD ? DB : 1][2];
+        if (V_AHEAD) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int off = db * 32 * 64 + (v_off ^ (u << 5));
-                fvh[db][u] = *reinterpret_cast<const u32x4 *>(st + off);
-                fvl[db][u] = *reinterpret_cast<const u32x4 *>(st + DV * 64 + off);
-            }
+                for (int u = 0; u < 2; ++u) v_frag(db, u, fvh[V_AHEAD ? db : 0][u], fvl[V_AHEAD ? db : 0][u]);
+        }
         uint32_t pk[8];
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
@@ -813,8 +837,15 @@ __global__ __launch_bounds__(64 * kSWaves, 2) void k_selfattn(
             const v8bf bp = __builtin_bit_cast(v8bf, pb);
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fvh[db][u]), bp, o[db], 0, 0, 0);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, fvl[db][u]), bp, o[db], 0, 0, 0);
+                u32x4 h, l;
+                if (V_AHEAD) {
+                    h = fvh[V_AHEAD ? db : 0][u];
+                    l = fvl[V_AHEAD ? db : 0][u];
+                } else {
+                    v_frag(db, u, h, l);
+                }
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, h), bp, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, l), bp, o[db], 0, 0, 0);
             }
         }
     }
@@ -848,6 +879,11 @@ hipError_t launch_selfattn_cfg(const float *q, const float *k, const float *v, i
     const int64_t groups = ((int64_t)BH + 7) / 8;
     const dim3 grid((unsigned)(groups * q_tiles * 8));
     const size_t lds = (size_t)CF::STAGES * CF::TILE_BYTES;
+    {
+        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k_selfattn<CF, true>), (int)lds);
+        if (e == hipSuccess) e = ensure_dynamic_lds(reinterpret_cast<const void *>(k_selfattn<CF, false>), (int)lds);
+        if (e != hipSuccess) return e;
+    }
     if (codes_dump)
         hipLaunchKernelGGL((k_selfattn<CF, true>), grid, dim3(64 * kSWaves), lds, st, q, BH, N, H, d, bits,
                            n_tiles, q_tiles, ws, scale_in, out, scale_out, codes_dump);
@@ -1119,13 +1155,15 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
 }
 
 // K and V^T of every (prompt, head) pair in the matrix cores' pieces (see k_selfattn_prep).
-static int selfattn_ks(int32_t d) { return d <= 16 ? 1 : (d <= 32 ? 2 : (d <= 48 ? 3 : 4)); }
+static int selfattn_ks(int32_t d) {
+    return d <= 16 ? 1 : (d <= 32 ? 2 : (d <= 48 ? 3 : (d <= 64 ? 4 : (d <= 80 ? 5 : 10))));
+}
 
 size_t selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d) {
-    if (d % 8 != 0 || d > 64 || d < 8) return 0;
-    const size_t dv = 32 * (((size_t)selfattn_ks(d) + 1) / 2);
+    if (d % 8 != 0 || d > 160 || d < 8) return 0;
+    const size_t ks = (size_t)selfattn_ks(d), dv = 32 * ((ks + 1) / 2), pitch = 128 * ((ks + 3) / 4);
     const size_t n_tiles = ((size_t)N + 31) / 32;
-    return (size_t)B * H * n_tiles * (2 * 32 * 128 + 2 * dv * 64);  // one tile image per 32 keys
+    return (size_t)B * H * n_tiles * (2 * 32 * pitch + 2 * dv * 64);  // one tile image per 32 keys
 }
 
 hipError_t launch_selfattn(const float *q, const float *k, const float *v, int32_t B, int32_t N,
@@ -1135,7 +1173,9 @@ hipError_t launch_selfattn(const float *q, const float *k, const float *v, int32
         case 1: return launch_selfattn_cfg<SCfg<1>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
         case 2: return launch_selfattn_cfg<SCfg<2>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
         case 3: return launch_selfattn_cfg<SCfg<3>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
-        default: return launch_selfattn_cfg<SCfg<4>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+        case 4: return launch_selfattn_cfg<SCfg<4>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+        case 5: return launch_selfattn_cfg<SCfg<5>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
+        default: return launch_selfattn_cfg<SCfg<10>>(q, k, v, B, N, H, d, bits, scale_in, out, scale_out, codes_dump, workspace, st);
     }
 }
 

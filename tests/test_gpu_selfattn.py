@@ -67,6 +67,10 @@ def _check(dgq, oracle, c, bits, s_in, sel=None, min_good=0.2):
     (2, 300, 2, 16),
     (1, 5, 2, 32),      # fewer keys than one lane half holds
     (1, 1, 1, 8),       # a single token: A = 1
+    (1, 100, 2, 80),    # the 32 x 32 level's head width: five 16-dim steps, 256-byte key rows
+    (1, 70, 2, 72),     # the same kernel with a padded last step
+    (2, 90, 1, 160),    # the 16 x 16 and 8 x 8 levels' head width: ten steps, 384-byte key rows
+    (1, 40, 1, 104),    # and a width in between (runs as ten steps)
 ])
 def test_small_shapes(dgq, oracle, B, N, H, d, bits):
     c = di.selfattn_case(40 + N + d, B, N, H, d)
@@ -119,11 +123,12 @@ def test_argument_errors(dgq):
     with pytest.raises(dgq.DgqError) as e:
         dgq.dgq_selfattn_logq(q, q, q, 5, s)
     assert e.value.code == -1
-    q72 = torch.zeros((1, 8, 1, 72), dtype=torch.float32, device="cuda")
-    with pytest.raises(dgq.DgqError) as e:
-        dgq.dgq_selfattn_logq(q72, q72, q72, 8, s)
-    assert e.value.code == -4
+    for dbad in (168, 20):                                 # too wide; not a multiple of 8
+        qb = torch.zeros((1, 8, 1, dbad), dtype=torch.float32, device="cuda")
+        with pytest.raises(dgq.DgqError) as e:
+            dgq.dgq_selfattn_logq(qb, qb, qb, 8, s)
+        assert e.value.code == -4
     with pytest.raises(dgq.DgqError) as e:                 # workspace too small
         dgq.dgq_selfattn_logq(q, q, q, 8, s, workspace=torch.empty(64, dtype=torch.uint8, device="cuda"))
     assert e.value.code == -3
-    assert dgq.dgq_selfattn_workspace_bytes(1, 8, 1, 72) == 0
+    assert dgq.dgq_selfattn_workspace_bytes(1, 8, 1, 168) == 0
