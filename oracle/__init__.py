@@ -117,6 +117,37 @@ def calibrate(x, act_bits: int, G: int, P: int = 2, granule: int = GRANULE) -> G
                   taus=np.array([tau.value], dtype=np.float32))
 
 
+def im2col3x3(x, B: int, H: int, W: int):
+    """The 3 x 3 neighbourhoods of a [B*H*W, C] activation map (pixels row-major, one row
+    per pixel) as rows of 9 C values: tap t = 3 (dy + 1) + (dx + 1) holds the channels of
+    pixel (h + dy, w + dx), zeros outside the image (stride 1, zero padding 1)."""
+    x = np.asarray(x)
+    Cc = x.shape[1]
+    img = x.reshape(B, H, W, Cc)
+    pad = np.zeros((B, H + 2, W + 2, Cc), dtype=x.dtype)
+    pad[:, 1:H + 1, 1:W + 1] = img
+    taps = [pad[:, 1 + dy:1 + dy + H, 1 + dx:1 + dx + W] for dy in (-1, 0, 1) for dx in (-1, 0, 1)]
+    return np.concatenate(taps, axis=-1).reshape(B * H * W, 9 * Cc)
+
+
+def groups_for_conv3x3(g: Groups) -> Groups:
+    """The group tables of a 3 x 3 convolution over an input grouped by g (one pixel class):
+    the unfolded input has 9 C channels, tap t's copy of channel c being channel t C + c, and
+    every tap keeps the channel groups, scales and offsets of g."""
+    assert g.P == 1
+    T = 9
+    perm = np.concatenate([np.where(g.perm >= 0, g.perm + t * g.C, -1) for t in range(T)]).astype(np.int32)
+    goff = np.concatenate([g.goff[:-1] + t * g.Kp for t in range(T)] + [[T * g.Kp]]).astype(np.int32)
+    return Groups(C=T * g.C, act_bits=g.act_bits, G=g.G, P=1, NG=T * g.NG, Kp=T * g.Kp,
+                  n_outlier_channels=T * g.n_outlier_channels, n_regular_groups=T * g.n_regular_groups,
+                  dstar=g.dstar, n_class1_rows=0, perm=perm, goff=goff,
+                  glen=np.tile(g.glen, T).astype(np.int32), tau_pix=g.tau_pix,
+                  s=np.ascontiguousarray(np.tile(g.s, (1, T))), z=np.ascontiguousarray(np.tile(g.z, (1, T))),
+                  inv_s=np.ascontiguousarray(np.tile(g.inv_s, (1, T))),
+                  D_channel=g.D_channel, D_pixel=g.D_pixel, cal_row_class=g.cal_row_class,
+                  taus=g.taus, mode=g.mode)
+
+
 def k_means(v, K: int):
     """Exact 1-D K-means.  Returns (k, bounds [k+1], taus [k-1], order)."""
     v = _f32(v)
