@@ -146,6 +146,32 @@ int dgq_calibrate_kmeans(const float *x_cal, int64_t rows, int32_t channels,
                          int32_t act_bits, int32_t n_clusters, int32_t dimension,
                          void *stream, dgq_groups_t **out);
 
+/*
+ * 3 x 3 convolution (stride 1, zero padding 1) through the same quantizer and contraction:
+ * the paper quantizes every layer of the U-Net with the activation quantizer of Section 3.3,
+ * convolutions included.  With the activation map x [B*H*W, C] (one row per pixel, pixels
+ * row-major) quantized once by dgq_quantize_act(g, x), the convolution is the linear layer
+ *   y[r, o] = sum_t sum_c x^[r_t, c] w[o, t, c],  t = 3 (dy + 1) + (dx + 1),
+ *   r_t = the pixel (h + dy, w + dx) of the same image, x^ = 0 outside it,
+ * over 9 C "channels" (tap t's copy of channel c is channel t C + c).
+ *
+ * dgq_groups_for_conv3x3 (offline): the group tables of that layer -- g's permutation,
+ * groups, scales and offsets replicated for the nine taps (channels = 9 C, k_padded = 9 K',
+ * n_groups = 9 NG).  g must have one pixel class (DGQ_EUNSUPPORTED otherwise).  Pass the
+ * new handle to dgq_pack_weight with w fp32 [O, 9 C] (tap-major rows [o][dy][dx][c]) and to
+ * dgq_linear; free it with dgq_groups_free.
+ *
+ * dgq_conv3x3_codes (hot call; enqueues on `stream`, neither synchronises nor allocates):
+ * unfolds the CODES of the map: codes9 (dgq_codes_bytes(g9, B*H*W) bytes) receives, for
+ * every pixel and tap, the code row of the neighbouring pixel, and outside the image the
+ * code of the value 0 (what quantizing the zero-padded, unfolded activations would give).
+ *   codes: as written by dgq_quantize_act(g, x) for rows = B*H*W
+ * The row classes written by dgq_quantize_act (all 0) serve the convolution's dgq_linear too.
+ */
+int dgq_groups_for_conv3x3(const dgq_groups_t *g, dgq_groups_t **out);
+int dgq_conv3x3_codes(const dgq_groups_t *g9, const int8_t *codes, int32_t B, int32_t H,
+                      int32_t W, int8_t *codes9, void *stream);
+
 /* Host copy of the n_pixel_classes - 1 ascending row-range thresholds (taus: host). */
 int dgq_groups_thresholds(const dgq_groups_t *g, float *taus);
 

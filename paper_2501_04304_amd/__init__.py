@@ -64,6 +64,8 @@ def lib():
         L.dgq_linear_geglu.argtypes = [vp, vp, vp, vp, i64, vp, vp]
         L.dgq_pack_weight_gated_for.argtypes = [vp, vp, vp, vp, i32, i32, vp, C.POINTER(vp)]
         L.dgq_linear_geglu_requant.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp]
+        L.dgq_groups_for_conv3x3.argtypes = [vp, C.POINTER(vp)]
+        L.dgq_conv3x3_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.dgq_codes_bytes.argtypes = [vp, i64]
         L.dgq_codes_bytes.restype = sz
         L.dgq_linear_workspace_bytes.argtypes = [vp, vp, i64]
@@ -192,6 +194,34 @@ def dgq_calibrate_kmeans(x_cal, act_bits: int, n_clusters: int, dimension: int =
     info = GroupsInfo()
     _check(lib().dgq_groups_info(h, C.byref(info)))
     return Groups(handle=h.value, info=info)
+
+
+def dgq_groups_for_conv3x3(groups: Groups) -> Groups:
+    """The group tables of the 3 x 3 convolution over a map grouped by `groups` (one pixel
+    class): nine replicated taps, 9 C channels."""
+    h = C.c_void_p()
+    _check(lib().dgq_groups_for_conv3x3(groups.handle, C.byref(h)))
+    info = GroupsInfo()
+    _check(lib().dgq_groups_info(h, C.byref(info)))
+    return Groups(handle=h.value, info=info)
+
+
+def dgq_conv3x3_codes(groups9: Groups, codes, B: int, H: int, W: int, codes9=None, stream=None):
+    """codes of the [B*H*W, C] map (dgq_quantize_act) -> the unfolded codes of its 3 x 3
+    convolution, int8 in the layout of codes_shape(groups9, B*H*W)."""
+    import torch
+    _dev(codes, torch.int8, "codes")
+    rows = B * H * W
+    shape = codes_shape(groups9, rows)
+    if codes.numel() * 9 != shape[0] * shape[1] * shape[2]:
+        raise ValueError("codes do not belong to a [B*H*W, C] map of this layer")
+    if codes9 is None:
+        codes9 = torch.empty(shape, dtype=torch.int8, device=codes.device)
+    _dev(codes9, torch.int8, "codes9")
+    if tuple(codes9.shape) != shape:
+        raise ValueError("codes9 has the wrong shape")
+    _check(lib().dgq_conv3x3_codes(groups9.handle, _ptr(codes), B, H, W, _ptr(codes9), _stream(stream)))
+    return codes9
 
 
 def dgq_pack_weight(groups: Groups, w, bias, w_bits: int, stream=None) -> Weight:

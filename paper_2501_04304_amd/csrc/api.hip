@@ -259,6 +259,7 @@ void release(Groups *g) {
     (void)hipFree(g->d_zoff);
     (void)hipFree(g->d_taus);
     (void)hipFree(g->d_gchunk);
+    (void)hipFree(g->d_fill);
     delete g;
 }
 
@@ -567,6 +568,92 @@ int dgq_calibrate_kmeans(const float *x_cal, int64_t rows, int32_t channels, int
         return rc;
     }
     *out = reinterpret_cast<dgq_groups_t *>(g);
+    return DGQ_OK;
+}
+
+int dgq_groups_for_conv3x3(const dgq_groups_t *h, dgq_groups_t **out) {
+    if (!h || !out) return fail(DGQ_EINVAL, "dgq_groups_for_conv3x3: null pointer");
+    *out = nullptr;
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    if (g->info.n_pixel_classes != 1 || g->conv_taps)
+        return fail(DGQ_EUNSUPPORTED,
+                    "dgq_groups_for_conv3x3: needs a layer with one pixel class (the scale of a "
+                    "tap's partial sum would otherwise follow the neighbouring pixel's class)");
+    constexpr int32_t T = 9;
+    const int32_t C = g->info.channels, Kp = g->info.k_padded, NG = g->info.n_groups;
+    if ((int64_t)T * Kp > (1 << 24)) return fail(DGQ_EUNSUPPORTED, "dgq_groups_for_conv3x3: too many channels");
+    Groups *g9 = new (std::nothrow) Groups();
+    if (!g9) return fail(DGQ_EINVAL, "dgq_groups_for_conv3x3: out of host memory");
+    g9->n_tab = 2;
+    g9->taus.assign(1, INFINITY);
+    g9->conv_taps = T;
+    g9->base_kp = Kp;
+    for (int32_t t = 0; t < T; ++t) {
+        for (int32_t j = 0; j < Kp; ++j) g9->perm.push_back(g->perm[j] < 0 ? -1 : t * C + g->perm[j]);
+        for (int32_t k = 0; k < NG; ++k) {
+            g9->goff.push_back(t * Kp + g->goff[k]);
+            g9->glen.push_back(g->glen[k]);
+        }
+    }
+    g9->goff.push_back(T * Kp);
+    g9->s.resize((size_t)2 * T * NG);
+    g9->z.resize((size_t)2 * T * NG);
+    g9->inv_s.resize((size_t)2 * T * NG);
+    for (int p = 0; p < 2; ++p)
+        for (int32_t t = 0; t < T; ++t)
+            for (int32_t k = 0; k < NG; ++k) {
+                const size_t to = (size_t)p * T * NG + (size_t)t * NG + k, from = (size_t)p * NG + k;
+                g9->s[to] = g->s[from];
+                g9->z[to] = g->z[from];
+                g9->inv_s[to] = g->inv_s[from];
+            }
+    g9->info = g->info;
+    g9->info.channels = T * C;
+    g9->info.n_groups = T * NG;
+    g9->info.k_padded = T * Kp;
+    g9->info.n_outlier_channels = T * g->info.n_outlier_channels;
+    g9->info.n_regular_groups = T * g->info.n_regular_groups;
+    // the code of the value 0 at every position of one tap: the quantizer's own operations
+    // (fl(fl(0 - z) * (1/s)), round to nearest even, clamp), then the stored form
+    const int bits = g->info.act_bits;
+    const float qmax = (float)((1 << bits) - 1);
+    std::vector<uint8_t> q0((size_t)Kp, 0), fill((size_t)(bits == 8 ? Kp : Kp / 2), 0);
+    for (int32_t k = 0; k < NG; ++k) {
+        const float t0 = 0.0f - g->z[k];
+        float u = nearbyintf(t0 * g->inv_s[k]);
+        u = u < 0.0f ? 0.0f : (u > qmax ? qmax : u);
+        if (!(u == u)) u = 0.0f;
+        for (int32_t j = g->goff[k]; j < g->goff[k + 1]; ++j)
+            if (g->perm[j] >= 0) q0[j] = (uint8_t)u;
+    }
+    if (bits == 8) {
+        for (int32_t j = 0; j < Kp; ++j) fill[j] = g->perm[j] >= 0 ? (uint8_t)(q0[j] ^ 0x80) : 0;
+    } else {
+        for (int32_t e = 0; e < Kp / 8; ++e)
+            for (int b = 0; b < 4; ++b) fill[4 * e + b] = (uint8_t)(q0[8 * e + b] | (q0[8 * e + 4 + b] << 4));
+    }
+    int rc = upload(&g9->d_fill, fill);
+    if (rc == DGQ_OK) rc = upload_tables(g9);
+    if (rc != DGQ_OK) {
+        release(g9);
+        return rc;
+    }
+    *out = reinterpret_cast<dgq_groups_t *>(g9);
+    return DGQ_OK;
+}
+
+int dgq_conv3x3_codes(const dgq_groups_t *h9, const int8_t *codes, int32_t B, int32_t H, int32_t W,
+                      int8_t *codes9, void *stream) {
+    if (!h9 || !codes || !codes9) return fail(DGQ_EINVAL, "dgq_conv3x3_codes: null pointer");
+    if (B < 1 || H < 1 || W < 1) return fail(DGQ_EINVAL, "dgq_conv3x3_codes: empty shape");
+    const Groups *g9 = reinterpret_cast<const Groups *>(h9);
+    if (g9->conv_taps != 9)
+        return fail(DGQ_ESHAPE, "dgq_conv3x3_codes: the handle does not come from dgq_groups_for_conv3x3");
+    if (!aligned16(codes) || !aligned16(codes9))
+        return fail(DGQ_EALIGN, "dgq_conv3x3_codes: tensor not 16-byte aligned");
+    if ((int64_t)B * H * W > ((int64_t)1 << 31))
+        return fail(DGQ_EUNSUPPORTED, "dgq_conv3x3_codes: too many pixels");
+    DGQ_HIP(launch_conv3x3_codes(*g9, codes, B, H, W, codes9, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 

@@ -54,6 +54,11 @@ struct Groups {
     float *d_zoff = nullptr;       // [n_tab][NG]  z + code_offset * s
     float *d_taus = nullptr;       // [n_tab - 1]
     int32_t *d_gchunk = nullptr;   // [NG+1] first chunk of each group
+    // Tables of a 3 x 3 convolution (nine replicated taps of a base layer with base_kp
+    // positions): d_fill is one tap's code row of the value 0 in position order, as stored
+    // (8 bit: q - 128 per position; 4 bit: packed nibbles; padding positions 0).
+    int32_t conv_taps = 0, base_kp = 0;
+    uint8_t *d_fill = nullptr;
     int device = 0;
 };
 
@@ -123,6 +128,11 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
                          int geglu, uint8_t *rq_cls, hipStream_t st);
+
+// Unfolds the codes of a [B, H, W] activation map into the code buffer of its 3 x 3
+// convolution (nine taps, the code of zero outside the image).
+hipError_t launch_conv3x3_codes(const Groups &g9, const int8_t *codes, int32_t B, int32_t H,
+                                int32_t W, int8_t *codes9, hipStream_t st);
 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,

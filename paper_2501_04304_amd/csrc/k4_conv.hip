@@ -1,0 +1,78 @@
+// 3 x 3 convolution (stride 1, zero padding 1) through the grouped contraction: the paper
+// quantizes every layer of the U-Net, convolutions included, with the activation quantizer
+// of Section 3.3.  The activation map is quantized ONCE per pixel (k_quantize_act, codes
+// [pixels, K']); this kernel unfolds the CODES, not the activations: the code row of output
+// pixel (b, h, w) is the concatenation over the nine taps t = 3 (dy + 1) + (dx + 1) of the code
+// row of pixel (b, h + dy, w + dx), and of the code of the value 0 where that pixel lies
+// outside the image.  The result is the code buffer of a layer with 9 K' positions (group
+// tables replicated per tap), which the contraction kernel takes as it is.  Needs one pixel
+// class: with several, the scale of a tap's partial sum would follow the neighbour's class,
+// not the output row's.
+//
+// Both buffers are block-tiled (1 KiB = one 64-position chunk of 16 rows of 64 B, or of 32
+// rows of 32 B of packed 4-bit codes; 16-byte slots XOR-permuted by row bits).  One thread
+// moves one 16-byte slot; consecutive threads write one block contiguously.
+#include "dgq_internal.h"
+
+namespace dgq {
+
+namespace {
+
+template <int BITS>
+__global__ __launch_bounds__(256) void k_conv3x3_codes(
+    const int8_t *__restrict__ codes, const uint8_t *__restrict__ fill, int32_t B, int32_t H,
+    int32_t W, int32_t n_chunks, int8_t *__restrict__ out) {
+    constexpr int SLOTS = BITS == 8 ? 4 : 2;        // 16-byte slots per row and chunk
+    constexpr int ROWS = BITS == 8 ? 16 : 32;       // rows per block
+    constexpr int ROW_BYTES = 16 * SLOTS;
+    const int64_t rows = (int64_t)B * H * W;
+    const int64_t n_blocks = (rows + ROWS - 1) / ROWS;
+    const int64_t total = n_blocks * 9 * n_chunks * 64;  // 64 slots per 1 KiB block
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * 256) {
+        const int sl = (int)(idx & 63);              // slot of the destination block, memory order
+        const int64_t blk = idx >> 6;
+        const int32_t c9 = (int32_t)(blk % (9 * n_chunks));
+        const int64_t rb = blk / (9 * n_chunks);
+        const int t = c9 / n_chunks, ch = c9 - t * n_chunks;
+        const int tr = sl / SLOTS;                   // row in the block
+        const int stored = sl % SLOTS;               // stored slot = logical slot ^ swizzle(row)
+        const int kq = stored ^ (BITS == 8 ? swz64(tr) : swz32(tr));
+        const int64_t r = rb * ROWS + tr;
+        if (r >= rows) continue;                     // rows past the end are never read as results
+        const int32_t w = (int32_t)(r % W);
+        const int32_t h = (int32_t)((r / W) % H);
+        const int dy = t / 3 - 1, dx = t % 3 - 1;
+        uint4 v;
+        if ((uint32_t)(h + dy) < (uint32_t)H && (uint32_t)(w + dx) < (uint32_t)W) {
+            const int64_t rs = r + (int64_t)dy * W + dx;   // same image: no carry into b
+            const int64_t off = BITS == 8 ? tiled64_offset(rs, ch, n_chunks, kq)
+                                          : tiled32_offset(rs, ch, n_chunks, kq);
+            v = *reinterpret_cast<const uint4 *>(codes + off);
+        } else {
+            v = *reinterpret_cast<const uint4 *>(fill + (int64_t)ch * ROW_BYTES + kq * 16);
+        }
+        *reinterpret_cast<uint4 *>(out + (blk << 10) + sl * 16) = v;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_conv3x3_codes(const Groups &g9, const int8_t *codes, int32_t B, int32_t H,
+                                int32_t W, int8_t *codes9, hipStream_t st) {
+    const int32_t n_chunks = g9.base_kp / kGranule;
+    const int64_t rows = (int64_t)B * H * W;
+    const int64_t rpb = g9.info.act_bits == 8 ? 16 : 32;
+    const int64_t total = (rows + rpb - 1) / rpb * 9 * n_chunks * 64;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;  // grid-stride beyond 64 workgroups per CU
+    if (g9.info.act_bits == 8)
+        hipLaunchKernelGGL(k_conv3x3_codes<8>, dim3((unsigned)blocks), dim3(256), 0, st, codes, g9.d_fill, B, H,
+                           W, n_chunks, codes9);
+    else
+        hipLaunchKernelGGL(k_conv3x3_codes<4>, dim3((unsigned)blocks), dim3(256), 0, st, codes, g9.d_fill, B, H,
+                           W, n_chunks, codes9);
+    return hipGetLastError();
+}
+
+}  // namespace dgq

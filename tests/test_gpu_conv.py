@@ -1,0 +1,119 @@
+"""GPU parity of the 3 x 3 convolution path (dgq_groups_for_conv3x3, dgq_conv3x3_codes, then
+the ordinary dgq_pack_weight / dgq_linear) against the CPU oracle: the unfolded codes
+bit-exact against the oracle's quantizer applied to the zero-padded, unfolded activations;
+the accumulators bit-exact; the result within 1e-4 * max|ref|."""
+import numpy as np
+import pytest
+
+import dgq_inputs as di
+from support import assert_close_fp32, codes_to_q
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgq():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2501_04304_amd as m
+    m.lib()
+    return m
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _run(dgq, oracle, B, H, W, C, O, act_bits, kind, seed, sample=None, check_acc=False):
+    import torch
+    rows = B * H * W
+    run = di.linear_case(seed, B, H * W, C, 8)
+    cal = di.linear_case(seed, B, H * W, C, 8, calib=True)
+    X = run["X"]
+    rng = np.random.default_rng(seed)
+    Wt = (rng.standard_normal((O, 9 * C)) * 0.02).astype(np.float32)      # [o][dy][dx][c]
+    bias = rng.standard_normal(O).astype(np.float32)
+    if kind == "kmeans":
+        og = oracle.calibrate_kmeans(cal["X"], act_bits, 8, 0)
+        g = dgq.dgq_calibrate_kmeans(_dev(cal["X"]), act_bits, 8, dgq.DIM_CHANNEL)
+    else:
+        og = oracle.calibrate(cal["X"], act_bits, 64, 1)
+        g = dgq.dgq_calibrate_groups(_dev(cal["X"]), act_bits, 64, 1)
+    og9 = oracle.groups_for_conv3x3(og)
+    g9 = dgq.dgq_groups_for_conv3x3(g)
+    inf = g9.info
+    assert (inf.channels, inf.k_padded, inf.n_groups, inf.n_pixel_classes) == (9 * C, og9.Kp, og9.NG, 1)
+    t9 = g9.tables()
+    assert np.array_equal(t9["perm"], og9.perm) and np.array_equal(t9["goff"], og9.goff)
+    assert np.array_equal(t9["glen"], og9.glen)
+    assert np.array_equal(t9["s"][:1].view(np.uint32), og9.s[:1].view(np.uint32))
+    assert np.array_equal(t9["z"][:1].view(np.uint32), og9.z[:1].view(np.uint32))
+
+    codes, cls = dgq.dgq_quantize_act(g, _dev(X))
+    codes9 = torch.full(dgq.codes_shape(g9, rows), 0x33, dtype=torch.int8, device="cuda")
+    dgq.dgq_conv3x3_codes(g9, codes, B, H, W, codes9=codes9)
+    wt = dgq.dgq_pack_weight(g9, _dev(Wt), _dev(bias), 8)
+    y = dgq.dgq_linear(g9, wt, codes9, cls)
+    torch.cuda.synchronize()
+    assert int(cls.max()) == 0
+
+    sel = np.arange(rows) if sample is None else np.asarray(sample)
+    X9 = oracle.im2col3x3(X, B, H, W)[sel]
+    oq = oracle.quantize_act(og9, X9)
+    q_gpu = codes_to_q(codes9.cpu().numpy(), act_bits, og9.Kp, rows)[sel]
+    real = og9.perm >= 0
+    assert np.array_equal(q_gpu[:, real], oq["q"][:, real])
+    assert np.all(q_gpu[:, ~real] == (128 if act_bits == 8 else 0))
+    owq, osw = oracle.quantize_weight(Wt, 8)
+    oy, oacc = oracle.linear(og9, oq["q"], oq["cls"], owq, osw, bias, want_acc=check_acc)
+    assert_close_fp32(y.cpu().numpy()[sel], oy, "y")
+    if check_acc:
+        dump = torch.full((rows, O, og9.NG), -7, dtype=torch.int32, device="cuda")
+        dgq.dgq_linear(g9, wt, codes9, cls, acc_dump=dump)
+        torch.cuda.synchronize()
+        assert np.array_equal(dump.cpu().numpy()[sel], oacc)
+    for hnd in (wt, g9, g):
+        hnd.free()
+
+
+@pytest.mark.parametrize("kind", ["kmeans", "blocks"])
+@pytest.mark.parametrize("act_bits", [8, 4])
+@pytest.mark.parametrize("B,H,W,C,O", [
+    (2, 9, 7, 72, 40),      # pixels not a multiple of the 16 / 32-row code blocks
+    (1, 16, 16, 128, 128),
+    (3, 5, 3, 40, 24),      # images smaller than a code block: neighbours cross block borders
+    (1, 1, 1, 64, 8),       # a single pixel: eight taps of padding
+])
+def test_small_maps(dgq, oracle, B, H, W, C, O, act_bits, kind):
+    _run(dgq, oracle, B, H, W, C, O, act_bits, kind, 300 + H * W + C, check_acc=(H * W <= 256))
+
+
+def test_resnet_block_shape_sampled(dgq, oracle):
+    """A 3 x 3 convolution of the U-Net at the 32 x 32 level (2 x 32 x 32 pixels, 640 -> 640
+    channels), sampled pixels: corners, borders and interior."""
+    B, H, W, C, O = 2, 32, 32, 640, 640
+    rng = np.random.default_rng(4)
+    rows = B * H * W
+    sample = np.unique(np.concatenate([rng.choice(rows, 12, replace=False),
+                                       [0, W - 1, W, H * W - 1, H * W, rows - W, rows - 1]]))
+    _run(dgq, oracle, B, H, W, C, O, 8, "kmeans", 77, sample=sample)
+
+
+def test_argument_errors(dgq):
+    x = _dev(di.linear_case(1, 1, 64, 64, 8)["X"])
+    g2 = dgq.dgq_calibrate_groups(x, 8, 64, 2)                  # two pixel classes
+    with pytest.raises(dgq.DgqError) as e:
+        dgq.dgq_groups_for_conv3x3(g2)
+    assert e.value.code == -4
+    g1 = dgq.dgq_calibrate_groups(x, 8, 64, 1)
+    codes, _ = dgq.dgq_quantize_act(g1, x)
+    with pytest.raises(dgq.DgqError) as e:                      # not a convolution handle
+        dgq._check(dgq.lib().dgq_conv3x3_codes(g1.handle, codes.data_ptr(), 1, 8, 8, codes.data_ptr(), None))
+    assert e.value.code == -3
+    g9 = dgq.dgq_groups_for_conv3x3(g1)
+    with pytest.raises(dgq.DgqError) as e:                      # nested unfolding
+        dgq.dgq_groups_for_conv3x3(g9)
+    assert e.value.code == -4
+    for hnd in (g9, g1, g2):
+        hnd.free()
