@@ -507,6 +507,39 @@ def main():
                                   workspace_bytes=int(wss.numel())))
             del qs, ks, vs, outs, wss
 
+    # ---------------- beyond the step: 3 x 3 convolutions of the U-Net's residual blocks -----
+    # 16 maps of 64 x 64 x 640 and of 32 x 32 x 1280, A8W8, channel groups of 128 and one pixel
+    # class (16 free-size clusters would pad every cluster of every tap to 64 positions): quantize once
+    # per pixel, unfold the codes (dgq_conv3x3_codes), contract over 9 K' positions.
+    conv = []
+    if args.workload == "config5" and not args.step_only:
+        for (B_, H_, W_, C_) in ((16, 64, 64, 640), (16, 32, 32, 1280)):
+            M_ = B_ * H_ * W_
+            cs = di.linear_case(91, 1, H_ * W_, C_, 8)
+            xs = up(cs["X"]).repeat(B_, 1)
+            g1 = dgq.dgq_calibrate_groups(xs[:H_ * W_], 8, 128, 1)
+            g9 = dgq.dgq_groups_for_conv3x3(g1)
+            w9 = torch.randn((C_, 9 * C_), dtype=torch.float32, device=dev) * 0.02
+            wt9 = dgq.dgq_pack_weight(g9, w9, None, 8)
+            c1 = torch.empty(dgq.codes_shape(g1, M_), dtype=torch.int8, device=dev)
+            cl1 = torch.empty(M_, dtype=torch.uint8, device=dev)
+            c9 = torch.empty(dgq.codes_shape(g9, M_), dtype=torch.int8, device=dev)
+            y9 = torch.empty((M_, C_), dtype=torch.float32, device=dev)
+            us_q = time_calls(L.dgq_quantize_act, (C.c_void_p(g1.handle), ptr(xs), C.c_int64(M_), ptr(c1), ptr(cl1), sp))
+            us_u = time_calls(L.dgq_conv3x3_codes, (C.c_void_p(g9.handle), ptr(c1), B_, H_, W_, ptr(c9), sp))
+            us_l = time_calls(L.dgq_linear, (C.c_void_p(g9.handle), C.c_void_p(wt9.handle), ptr(c9), ptr(cl1),
+                                             C.c_int64(M_), ptr(y9), None, None, C.c_size_t(0), sp))
+            ops = 2.0 * M_ * 9 * C_ * C_
+            conv.append(dict(B=B_, H=H_, W=W_, C=C_, O=C_, k_padded=g9.info.k_padded,
+                             us_quantize=round(us_q, 2), us_unfold_codes=round(us_u, 2),
+                             gbs_unfold=round((c1.numel() + c9.numel()) / us_u / 1e3, 1),
+                             us_linear=round(us_l, 2), tops_linear=round(ops / us_l / 1e6, 1),
+                             tops_whole=round(ops / (us_q + us_u + us_l) / 1e6, 1)))
+            wt9.free()
+            g9.free()
+            g1.free()
+            del xs, w9, c1, cl1, c9, y9
+
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -543,7 +576,7 @@ def main():
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
-                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, self_attention=self_attn, cpu_baseline=cpu)
+                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, self_attention=self_attn, conv3x3=conv, cpu_baseline=cpu)
     print(json.dumps(line))
 
 
