@@ -50,6 +50,9 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_pack_weight_gated_for(None, None, None, None, 512, 8, None, None) == -1
     assert lib.dgq_xattn_logq_static(None, None, None, None, 1, 1, 1, 8, 77, 8, None, None, None, None, None) == -1
     assert lib.dgq_quantize_value(None, 1, 77, 1, 8, 8, None, None, None, None) == -1
+    assert lib.dgq_selfattn_logq(None, None, None, 1, 8, 1, 8, 8, None, None, None, None, None, 0, None) == -1
+    assert lib.dgq_groups_for_conv3x3(None, None) == -1
+    assert lib.dgq_conv3x3_codes(None, None, 1, 4, 4, None, None) == -1
     h = C.c_void_p()
     assert lib.dgq_calibrate_groups(None, 4, 64, 8, 64, 2, None, C.byref(h)) == -1
     buf = (C.c_float * 64)()
@@ -75,7 +78,8 @@ def test_binding_names_match_the_abi():
     for s in ("dgq_calibrate_groups", "dgq_calibrate_kmeans", "dgq_pack_weight",
               "dgq_quantize_act", "dgq_linear", "dgq_linear_geglu", "dgq_xattn_logq", "dgq_xattn_workspace_bytes",
               "dgq_pack_weight_gated_for", "dgq_linear_geglu_requant", "dgq_quantize_value",
-              "dgq_xattn_logq_static"):
+              "dgq_xattn_logq_static", "dgq_selfattn_logq", "dgq_selfattn_workspace_bytes",
+              "dgq_groups_for_conv3x3", "dgq_conv3x3_codes"):
         assert callable(getattr(dgq, s))
 
 
