@@ -820,7 +820,9 @@ __global__ __launch_bounds__(64 * kSWaves, CF::OCC) void k_selfattn(
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 float t = c0 - sm[i + u];
-                t = t > thr ? 300.0f : t;  // a probability that is zero in fp32: top code
+                // a probability that is zero in fp32 takes the top code; the product does not
+                // need the rule (every code above 126 gives a zero weight anyway)
+                if (DUMP) t = t > thr ? 300.0f : t;
                 const int32_t r = __float_as_int(t + 12582912.0f);
                 if (DUMP) {
                     const int32_t key = 32 * kt + key_of(0, i + u, hh);
