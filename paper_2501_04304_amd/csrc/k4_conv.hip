@@ -10,49 +10,51 @@
 // not the output row's.
 //
 // Both buffers are block-tiled (1 KiB = one 64-position chunk of 16 rows of 64 B, or of 32
-// rows of 32 B of packed 4-bit codes; 16-byte slots XOR-permuted by row bits).  One thread
-// moves one 16-byte slot; consecutive threads write one block contiguously.
+// rows of 32 B of packed 4-bit codes; 16-byte slots XOR-permuted by row bits).
 #include "dgq_internal.h"
 
 namespace dgq {
 
 namespace {
 
+// One workgroup per destination row block (16 or 32 pixels): lane (tid % 64) owns one
+// 16-byte slot of every block of that row block, wave (tid / 64) takes every fourth chunk.
+// Everything that needs a division (the pixel's place in its image) is done once per thread;
+// the loops over taps and chunks only add strides, and a wave writes 1 KiB at a time.
 template <int BITS>
 __global__ __launch_bounds__(256) void k_conv3x3_codes(
-    const int8_t *__restrict__ codes, const uint8_t *__restrict__ fill, int32_t B, int32_t H,
+    const int8_t *__restrict__ codes, const uint8_t *__restrict__ fill, int64_t rows, int32_t H,
     int32_t W, int32_t n_chunks, int8_t *__restrict__ out) {
     constexpr int SLOTS = BITS == 8 ? 4 : 2;        // 16-byte slots per row and chunk
     constexpr int ROWS = BITS == 8 ? 16 : 32;       // rows per block
     constexpr int ROW_BYTES = 16 * SLOTS;
-    const int64_t rows = (int64_t)B * H * W;
-    const int64_t n_blocks = (rows + ROWS - 1) / ROWS;
-    const int64_t total = n_blocks * 9 * n_chunks * 64;  // 64 slots per 1 KiB block
-    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * 256) {
-        const int sl = (int)(idx & 63);              // slot of the destination block, memory order
-        const int64_t blk = idx >> 6;
-        const int32_t c9 = (int32_t)(blk % (9 * n_chunks));
-        const int64_t rb = blk / (9 * n_chunks);
-        const int t = c9 / n_chunks, ch = c9 - t * n_chunks;
-        const int tr = sl / SLOTS;                   // row in the block
-        const int stored = sl % SLOTS;               // stored slot = logical slot ^ swizzle(row)
-        const int kq = stored ^ (BITS == 8 ? swz64(tr) : swz32(tr));
-        const int64_t r = rb * ROWS + tr;
-        if (r >= rows) continue;                     // rows past the end are never read as results
-        const int32_t w = (int32_t)(r % W);
-        const int32_t h = (int32_t)((r / W) % H);
+    const int64_t rb = blockIdx.x;
+    const int sl = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int tr = sl / SLOTS;                       // row in the block
+    const int stored = sl % SLOTS;                   // stored slot = logical slot ^ swizzle(row)
+    const int kq = stored ^ (BITS == 8 ? swz64(tr) : swz32(tr));
+    const int64_t r = rb * ROWS + tr;
+    if (r >= rows) return;                           // rows past the end are never read as results
+    const int32_t w = (int32_t)(r % W);
+    const int32_t h = (int32_t)((r / W) % H);
+    int8_t *dst = out + ((rb * 9 * n_chunks) << 10) + sl * 16;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
         const int dy = t / 3 - 1, dx = t % 3 - 1;
-        uint4 v;
-        if ((uint32_t)(h + dy) < (uint32_t)H && (uint32_t)(w + dx) < (uint32_t)W) {
-            const int64_t rs = r + (int64_t)dy * W + dx;   // same image: no carry into b
-            const int64_t off = BITS == 8 ? tiled64_offset(rs, ch, n_chunks, kq)
-                                          : tiled32_offset(rs, ch, n_chunks, kq);
-            v = *reinterpret_cast<const uint4 *>(codes + off);
+        const bool inside = (uint32_t)(h + dy) < (uint32_t)H && (uint32_t)(w + dx) < (uint32_t)W;
+        const int64_t rs = r + (int64_t)dy * W + dx;   // same image: no carry into the batch index
+        const int8_t *src;
+        int32_t stride;
+        if (inside) {
+            src = codes + (BITS == 8 ? tiled64_offset(rs, 0, n_chunks, kq) : tiled32_offset(rs, 0, n_chunks, kq));
+            stride = 1024;
         } else {
-            v = *reinterpret_cast<const uint4 *>(fill + (int64_t)ch * ROW_BYTES + kq * 16);
+            src = reinterpret_cast<const int8_t *>(fill) + kq * 16;
+            stride = ROW_BYTES;
         }
-        *reinterpret_cast<uint4 *>(out + (blk << 10) + sl * 16) = v;
+        for (int32_t ch = q; ch < n_chunks; ch += 4)
+            *reinterpret_cast<uint4 *>(dst + ((int64_t)(t * n_chunks + ch) << 10)) =
+                *reinterpret_cast<const uint4 *>(src + (int64_t)ch * stride);
     }
 }
 
@@ -63,15 +65,13 @@ hipError_t launch_conv3x3_codes(const Groups &g9, const int8_t *codes, int32_t B
     const int32_t n_chunks = g9.base_kp / kGranule;
     const int64_t rows = (int64_t)B * H * W;
     const int64_t rpb = g9.info.act_bits == 8 ? 16 : 32;
-    const int64_t total = (rows + rpb - 1) / rpb * 9 * n_chunks * 64;
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 256 * 64) blocks = 256 * 64;  // grid-stride beyond 64 workgroups per CU
+    const int64_t blocks = (rows + rpb - 1) / rpb;
     if (g9.info.act_bits == 8)
-        hipLaunchKernelGGL(k_conv3x3_codes<8>, dim3((unsigned)blocks), dim3(256), 0, st, codes, g9.d_fill, B, H,
-                           W, n_chunks, codes9);
+        hipLaunchKernelGGL(k_conv3x3_codes<8>, dim3((unsigned)blocks), dim3(256), 0, st, codes, g9.d_fill, rows,
+                           H, W, n_chunks, codes9);
     else
-        hipLaunchKernelGGL(k_conv3x3_codes<4>, dim3((unsigned)blocks), dim3(256), 0, st, codes, g9.d_fill, B, H,
-                           W, n_chunks, codes9);
+        hipLaunchKernelGGL(k_conv3x3_codes<4>, dim3((unsigned)blocks), dim3(256), 0, st, codes, g9.d_fill, rows,
+                           H, W, n_chunks, codes9);
     return hipGetLastError();
 }
 
