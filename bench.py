@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--probe-copy", action="store_true",
                     help="run only a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB), "
                          "three times: the reference that scales the profiler's HBM byte counters")
+    ap.add_argument("--probe-selfattn", action="store_true",
+                    help="run only dgq_selfattn_logq on 16 x 10 heads x 4096 tokens x 64, 8-bit codes, "
+                         "three times: the launches the profiler's counters are read for")
     return ap.parse_args()
 
 
@@ -97,6 +100,17 @@ def main():
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
         print(json.dumps(dict(probe="copy", read_bytes=4 * n, write_bytes=4 * n, launches=3)))
+        return
+    if args.probe_selfattn:
+        B_, N_, H_, d_ = 16, 4096, 10, 64
+        c_ = di.selfattn_case(77, 1, N_, H_, d_)
+        qs, ks, vs = (torch.from_numpy(c_[n]).to(dev).expand(B_, N_, H_, d_).contiguous() for n in ("Q", "K", "V"))
+        ones = torch.ones(B_, dtype=torch.float32, device=dev)
+        outs = torch.empty_like(qs)
+        for _ in range(3):
+            dgq.dgq_selfattn_logq(qs, ks, vs, 8, ones, out=outs)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(probe="selfattn", B=B_, N=N_, H=H_, d=d_, launches=3)))
         return
     cfg, desc = workload(args.workload)
 

@@ -564,10 +564,21 @@ constexpr int kSWaves = 8;  // wavefronts per workgroup: 256 queries share every
 __device__ __host__ constexpr int v_slot(int j) {
     return 16 * (j >> 4) + 8 * ((j >> 2) & 1) + (j & 3) + 4 * ((j >> 3) & 1);
 }
-// byte offsets inside a tile image: 16-byte slot c of K row j (the XOR stays inside a group
-// of 8 slots) / of V^T row t (4 slots)
-__device__ __host__ constexpr int k_row_slot(int pitch, int j, int c) { return j * pitch + ((c ^ (j & 7)) << 4); }
-__device__ __host__ constexpr int v_row_slot(int t, int c) { return t * 64 + ((c ^ ((t >> 1) & 3)) << 4); }
+// byte offsets inside a tile image: 16-byte slot c of K row j / of V^T row t.  A wave reads
+// 16 bytes per lane from 32 consecutive rows, and LDS serves 16 lanes (256 bytes, 64 banks)
+// at a time: the sixteen 16-byte bank groups those lanes touch -- address bits 4..7 -- must
+// all differ.  64-byte rows (V^T): bits 6..7 are row bits 0..1, the slot takes bit 2 and
+// bit 1 ^ bit 3 (the permutation of the contraction kernel's rows, which measures no bank
+// conflict).  128- and 384-byte rows: bit 7 is row bit 0, the slot takes row bits 1..3.
+// 256-byte rows: no row bit reaches the bank bits, the slot takes all four.  (XOR-ing with
+// row % 8 left half of the LDS cycles in conflict.)
+__device__ __host__ inline int k_row_key(int pitch, int j) {
+    return ((j >> 1) & 7) | (pitch == 256 ? (j & 1) << 3 : 0);
+}
+__device__ __host__ inline int k_row_slot(int pitch, int j, int c) {
+    return j * pitch + ((c ^ k_row_key(pitch, j)) << 4);
+}
+__device__ __host__ inline int v_row_slot(int t, int c) { return t * 64 + ((c ^ swz64(t)) << 4); }
 
 #define DGQ_X_LDS_DMA16(sbase, voff, l0)                                              \
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"      \
@@ -704,8 +715,7 @@ __global__ __launch_bounds__(64 * kSWaves, CF::OCC) void k_selfattn(
         if (kt + 2 < n_tiles) issue(with_v, kt + 2);
     };
 
-    // slot 2 s + hh: s % 4 enters as an XOR (bits 1..2 of the slot), s / 4 as a group of 8 slots
-    const int k_off = k_row_slot(CF::PITCH, n, hh);
+    const int k_row = n * CF::PITCH, k_key = k_row_key(CF::PITCH, n) ^ hh;  // slot 2 s + hh of row n
     // S^T of the tile in `stage` for the wave's 32 queries, in log2 units; padding keys -inf
     auto s_tile = [&](int32_t kt, v16f &sm) {
         const uint8_t *st = ring + (kt % STAGES) * CF::TILE_BYTES;
@@ -714,7 +724,7 @@ __global__ __launch_bounds__(64 * kSWaves, CF::OCC) void k_selfattn(
         constexpr int NF = KS <= 4 ? KS : 2;
         u32x4 fh[NF], fl[NF];
         auto frag = [&](int s) __attribute__((always_inline)) {
-            const int off = (k_off ^ ((s & 3) << 5)) + 128 * (s >> 2);
+            const int off = k_row + ((k_key ^ (2 * s)) << 4);
             fh[s % NF] = *reinterpret_cast<const u32x4 *>(st + off);
             fl[s % NF] = *reinterpret_cast<const u32x4 *>(st + 32 * CF::PITCH + off);
         };
