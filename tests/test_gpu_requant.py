@@ -52,7 +52,7 @@ def _oracle_h(oracle, og1, X, W, bias):
 
 
 def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=None, cal_rows=256,
-         next_bits=8):
+         next_bits=8, run_rows=None):
     """Layer 1: C1 -> 2 C2 (hybrid grid, two pixel classes, act_bits codes); layer 2 takes
     the C2 gated channels with 8-bit codes and channel groups only."""
     import torch
@@ -60,6 +60,8 @@ def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=No
     run = di.linear_case(seed, B, N, C1, O)
     cal = di.linear_case(seed, B, N, C1, O, calib=True)
     X, W = run["X"], run["W"] * np.float32(8.0)   # pre-activations of order one, so GELU bends
+    if run_rows is not None:                        # a few rows of the same layer
+        X = np.ascontiguousarray(X[:run_rows])
     rows = X.shape[0]
     bias = (np.random.default_rng(seed).standard_normal(O) * 0.3).astype(np.float32)
     sel = np.arange(rows) if sample is None else np.asarray(sample)
@@ -70,7 +72,8 @@ def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=No
 
     # the following layer is calibrated on the oracle's gated activation of calibration rows
     rng = np.random.default_rng(seed + 1)
-    crow = np.sort(rng.choice(rows, min(cal_rows, rows), replace=False))
+    n_cal = cal["X"].shape[0]
+    crow = np.sort(rng.choice(n_cal, min(cal_rows, n_cal), replace=False))
     _, hcal = _oracle_h(oracle, og1, cal["X"][crow], W, bias)
     if next_kind == "kmeans":
         og2 = oracle.calibrate_kmeans(hcal, next_bits, K, 0)
@@ -128,7 +131,8 @@ def _run(dgq, oracle, B, N, C1, C2, G, act_bits, seed, next_kind, K=8, sample=No
     assert not (diff & decided).any(), "%d decided codes differ" % int((diff & decided).sum())
     assert np.abs(q_got - q_ref).max() <= 1
     assert diff.mean() < 2e-3, "too many codes differ: %.2e" % diff.mean()
-    assert np.unique(q_ref).size > (30 if next_bits == 8 else 8)  # not a trivial case
+    if run_rows is None:
+        assert np.unique(q_ref).size > (30 if next_bits == 8 else 8)  # not a trivial case
     for hnd in (wt_f, wt, g1, g2):
         hnd.free()
     return float(decided.mean()), float(diff.mean())
@@ -168,6 +172,13 @@ def test_four_bit_codes_for_the_following_layer(dgq, oracle, B, N, C1, C2, G, ab
     decided, _ = _run(dgq, oracle, B, N, C1, C2, G, ab, 950 + C1 + C2, next_kind, sample=sample,
                       next_bits=4)
     assert decided > 0.99
+
+
+@pytest.mark.parametrize("next_bits", [8, 4])
+@pytest.mark.parametrize("rows", [1, 17, 33])
+def test_a_few_rows(dgq, oracle, rows, next_bits):
+    """Fewer rows than one code block of the following layer, and one more than a block."""
+    _run(dgq, oracle, 2, 150, 328, 256, 64, 8, 1234, "kmeans", run_rows=rows, next_bits=next_bits)
 
 
 def test_config5_feed_forward_sampled(dgq, oracle):
