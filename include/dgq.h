@@ -16,14 +16,27 @@
  *   dgq_xattn_logq         text cross-attention whose softmax probabilities,
  *                          except the <start> column, are log2-quantized with a
  *                          prompt-specific scale before the product with V
+ * and, around it:
+ *   dgq_calibrate_kmeans   the paper's single-dimension grouping (K clusters of
+ *                          channels or of pixels), one handle per timestep
+ *   dgq_linear_geglu, dgq_pack_weight_gated_for, dgq_linear_geglu_requant
+ *                          the gated feed-forward activation in the contraction's
+ *                          epilogue, optionally writing the next layer's codes
+ *   dgq_groups_for_conv3x3, dgq_conv3x3_codes
+ *                          3 x 3 convolutions through the same quantizer and
+ *                          contraction
+ *   dgq_quantize_value, dgq_xattn_logq_static, dgq_selfattn_logq
+ *                          the quantized value tensor, the attention with a given
+ *                          scale, and self-attention over N keys
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer unless the comment says "host".
  *     Tensors are row-major with the innermost dimension contiguous and a base
  *     address aligned to 16 bytes (else DGQ_EALIGN).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     The three hot calls (quantize_act, linear, xattn_logq) only enqueue work:
- *     they neither synchronise nor allocate.  The caller owns every tensor and
+ *     The hot calls (quantize_act, linear and its variants, conv3x3_codes,
+ *     quantize_value, the attentions) only enqueue work: they neither
+ *     synchronise nor allocate.  The caller owns every tensor and
  *     keeps it alive until the stream has passed the call.
  *   - Return value: DGQ_OK or a negative dgq_status.  Nothing is enqueued when
  *     an argument error is returned.  dgq_last_error() gives a host string for
