@@ -244,6 +244,7 @@ void dgq_weight_free(dgq_weight_t *w);
  *          16-byte slots are XOR-permuted: slot k is stored at slot
  *              k ^ ( bit2(t) | ((bit1(t) ^ bit3(t)) << 1) )          (8 bit, 4 slots)
  *              k ^ bit3(t)                                           (4 bit, 2 slots)
+ *          and, at 4 bit, rows t >= 16 keep the two 8-byte halves of every slot swapped.
  *          8 bit: one int8 per position.  4 bit: positions are packed in groups of 8
  *          into 4 bytes, byte i holding position i in its low nibble and position
  *          i+4 in its high nibble, each nibble the unsigned q.

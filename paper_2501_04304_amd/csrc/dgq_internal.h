@@ -25,6 +25,10 @@ __host__ __device__ inline int swz64(int row) {  // 4 slots
     return ((row >> 2) & 1) | ((((row >> 1) ^ (row >> 3)) & 1) << 1);
 }
 __host__ __device__ inline int swz32(int row) { return (row >> 3) & 1; }  // 2 slots
+// Packed 4-bit rows are read 8 bytes per lane (one k-half of a 32-position step), 32 lanes at a
+// time: with 32-byte rows the 32 rows of one k-half would touch only every other 8-byte bank
+// pair, so rows 16..31 of a block keep the two 8-byte halves of every slot swapped.
+__host__ __device__ inline int half32(int row) { return (row >> 4) & 1; }
 // byte offset of 16-byte slot kq of (row, chunk) in a 64-B-per-row tensor
 __host__ __device__ inline int64_t tiled64_offset(int64_t row, int32_t chunk, int32_t n_chunks, int kq) {
     const int t = (int)(row & 15);

@@ -233,7 +233,8 @@ __global__ __launch_bounds__(256) void k_quantize_act(
             int8_t *out_row = codes + (((r >> (BITS == 8 ? 4 : 5)) * n_chunks) << 10) +
                               t16 * (BITS == 8 ? 64u : 32u);
             const uint32_t out_off =
-                out_lane + ((slot_lane ^ (uint32_t)(BITS == 8 ? swz64((int)t16) : swz32((int)t16))) << 4);
+                (out_lane + ((slot_lane ^ (uint32_t)(BITS == 8 ? swz64((int)t16) : swz32((int)t16))) << 4)) ^
+                (BITS == 8 ? 0u : (uint32_t)half32((int)t16) << 3);  // 4 bit: halves swapped in rows 16..31
 
             // NT steps together, so that their LDS round trips overlap
             auto steps = [&](auto nt_tag, const int32_t j0) __attribute__((always_inline)) {
@@ -347,7 +348,8 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
             }
             const int64_t off = BITS == 8 ? tiled64_offset(r, ch, n_chunks, (jd >> 2) & 3)
                                           : tiled32_offset(r, ch, n_chunks, (jd >> 2) & 1);
-            *reinterpret_cast<uint32_t *>(codes + off + (jd & 3) * 4) = word;
+            const int dw = BITS == 8 ? (jd & 3) : ((jd & 3) ^ (2 * half32((int)(r & 31))));
+            *reinterpret_cast<uint32_t *>(codes + off + dw * 4) = word;
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();

@@ -254,7 +254,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         if (ABITS == 8)
             a_off[ks] = rowa * 64 + (((ks * 2 + kh) ^ swz64(rowa)) * 16);
         else
-            a_off[ks] = rowa * 32 + ((ks ^ swz32(rowa)) * 16) + kh * 8;
+            a_off[ks] = rowa * 32 + ((ks ^ swz32(rowa)) * 16) + (kh ^ half32(rowa)) * 8;
         b_off[ks] = CF::ABYTES + rowb * 64 + (((ks * 2 + kh) ^ swz64(rowb)) * 16);
     }
     // 16 bytes of K per lane for each row-block / channel-block
@@ -508,7 +508,8 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
                             const uint32_t x23 = __builtin_amdgcn_perm(q3, q2, sel);
                             const uint32_t low = __builtin_amdgcn_perm(x23, x01, 0x05040100u);
                             const uint32_t high = (uint32_t)__shfl_down((int)low, 4, 64);
-                            const uint32_t lo = ((g4 & 1) ? l4_1 : l4_0) + 256u * g4;
+                            // rows 16..31 of the block (g4 >= 2): the 8-byte halves of a slot swapped
+                            const uint32_t lo = (((g4 & 1) ? l4_1 : l4_0) ^ (g4 >= 2 ? 8u : 0u)) + 256u * g4;
                             if (!(c & 1u) && !((past[a] >> (4 * g4 + (int)j)) & 1))
                                 *reinterpret_cast<uint32_t *>(blk + lo) = low | (high << 4);
                         }

@@ -52,9 +52,14 @@ __global__ __launch_bounds__(256) void k_conv3x3_codes(
             src = reinterpret_cast<const int8_t *>(fill) + kq * 16;
             stride = ROW_BYTES;
         }
-        for (int32_t ch = q; ch < n_chunks; ch += 4)
-            *reinterpret_cast<uint4 *>(dst + ((int64_t)(t * n_chunks + ch) << 10)) =
-                *reinterpret_cast<const uint4 *>(src + (int64_t)ch * stride);
+        // 4-bit rows keep the 8-byte halves of a slot swapped in rows 16..31 of a block (the
+        // fill row is stored unswapped): swap when source and destination differ in that
+        const bool swap = BITS == 4 && ((inside ? (int)(rs >> 4) & 1 : 0) != ((tr >> 4) & 1));
+        for (int32_t ch = q; ch < n_chunks; ch += 4) {
+            uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)ch * stride);
+            if (swap) v = make_uint4(v.z, v.w, v.x, v.y);
+            *reinterpret_cast<uint4 *>(dst + ((int64_t)(t * n_chunks + ch) << 10)) = v;
+        }
     }
 }
 

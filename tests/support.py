@@ -32,7 +32,7 @@ def codes_to_q(codes_np, act_bits, kp, rows):
 
     Layout (include/dgq.h): blocks of 1 KiB ordered [row block][chunk]; a block is one
     64-position chunk of 16 rows x 64 B (8 bit) or 32 rows x 32 B (4 bit); the 16-byte
-    slots of row t are XOR-permuted."""
+    slots of row t are XOR-permuted (and, in 4-bit rows 16..31, the halves of a slot swapped)."""
     n_chunks = kp // 64
     b = codes_np.view(np.uint8).reshape(-1, n_chunks, 1024)
     if act_bits == 8:
@@ -48,6 +48,8 @@ def codes_to_q(codes_np, act_bits, kp, rows):
     for t in range(32):
         for h in range(2):
             out[:, :, t, h] = blk[:, :, t, h ^ ((t >> 3) & 1)]
+    # rows 16..31 of a block keep the two 8-byte halves of every slot swapped
+    out[:, :, 16:] = np.concatenate([out[:, :, 16:, :, 8:], out[:, :, 16:, :, :8]], axis=-1)
     packed = out.transpose(0, 2, 1, 3, 4).reshape(-1, kp // 8, 4)[:rows]  # groups of 8 positions
     q = np.empty((packed.shape[0], kp // 8, 8), np.uint8)
     q[:, :, 0:4] = packed & 0x0F   # byte i: position i in the low nibble,
