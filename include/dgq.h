@@ -43,7 +43,11 @@
  *     the last failure on the calling thread.
  *   - Handles (dgq_groups_t, dgq_weight_t) own small device tables; they are
  *     immutable after creation, may be shared between streams, and are released
- *     with dgq_groups_free / dgq_weight_free (which synchronise the device).
+ *     with dgq_groups_free / dgq_weight_free.  A weight handle keeps the tables of the
+ *     group handle it was packed for alive, so the two may be freed in either order.
+ *     Freeing returns device memory to the runtime, which waits for the device to be idle
+ *     first: drop handles outside the hot loop (the 25 per-timestep entries of one layer
+ *     are a few KB; keep them all).
  *
  * Quantization grid.  Section 3.3 of the paper groups the vectors of ONE
  * dimension d* in {channel, pixel} by their range and gives each group its own

@@ -8,8 +8,7 @@
 #include <new>
 #include <numeric>
 
-#include <map>
-#include <mutex>
+#include <atomic>
 #include <utility>
 
 #include "dgq_internal.h"
@@ -20,19 +19,27 @@ static thread_local std::string g_last_error;
 
 void set_error(const std::string &msg) { g_last_error = msg; }
 
-hipError_t ensure_dynamic_lds(const void *kernel, int bytes) {
-    static std::mutex mu;
-    static std::map<std::pair<const void *, int>, int> done;  // (kernel, device) -> bytes set
+hipError_t raise_lds_limit(LdsLimit &state, const void *kernel, int bytes) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    std::lock_guard<std::mutex> lock(mu);
-    int &cur = done[std::make_pair(kernel, dev)];
-    if (cur >= bytes) return hipSuccess;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (state.bytes[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+    // two threads may both get here: the attribute call is idempotent
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) cur = bytes;
+    if (e == hipSuccess) state.bytes[dev].store(bytes, std::memory_order_release);
     return e;
 }
+
+#ifdef DGQ_TUNING
+static std::atomic<int> g_tuning[kTuneKeys];
+int tuning_value(int key) { return key >= 0 && key < kTuneKeys ? g_tuning[key].load() : 0; }
+extern "C" int dgq_tuning_set(int key, int value) {
+    if (key < 0 || key >= kTuneKeys) return DGQ_EINVAL;
+    g_tuning[key].store(value);
+    return DGQ_OK;
+}
+#endif
 
 int hip_fail(hipError_t e, const char *what) {
     set_error(std::string(what) + ": " + hipGetErrorString(e));
@@ -251,6 +258,7 @@ int upload_tables(Groups *g) {
 
 void release(Groups *g) {
     if (!g) return;
+    if (g->refs.fetch_sub(1, std::memory_order_acq_rel) != 1) return;  // a weight handle still uses it
     (void)hipFree(g->d_perm);
     (void)hipFree(g->d_chunk_z);
     (void)hipFree(g->d_chunk_inv);
@@ -265,6 +273,7 @@ void release(Groups *g) {
 
 void release(Weight *w) {
     if (!w) return;
+    release(const_cast<Groups *>(w->groups));
     (void)hipFree(w->d_wq);
     (void)hipFree(w->d_sw);
     (void)hipFree(w->d_zb);
@@ -679,7 +688,6 @@ int dgq_groups_tables(const dgq_groups_t *h, int32_t *perm, int32_t *goff, int32
 
 void dgq_groups_free(dgq_groups_t *h) {
     if (!h) return;
-    (void)hipDeviceSynchronize();
     release(reinterpret_cast<Groups *>(h));
 }
 
@@ -696,6 +704,7 @@ int pack_weight(const char *who, const Groups *g, const Groups *next, const floa
     Weight *wt = new (std::nothrow) Weight();
     if (!wt) return fail(DGQ_EINVAL, std::string(who) + ": out of host memory");
     wt->groups = g;
+    g->refs.fetch_add(1, std::memory_order_relaxed);
     wt->O = next ? 2 * next->info.k_padded : out_channels;
     wt->O_pad = (wt->O + kTileO - 1) / kTileO * kTileO;
     wt->C = g->info.channels;
@@ -809,7 +818,6 @@ int dgq_weight_tables(const dgq_weight_t *h, int8_t *wq, float *sw) {
 
 void dgq_weight_free(dgq_weight_t *h) {
     if (!h) return;
-    (void)hipDeviceSynchronize();
     release(reinterpret_cast<Weight *>(h));
 }
 
@@ -820,10 +828,7 @@ int dgq_quantize_act(const dgq_groups_t *h, const float *x, int64_t rows, int8_t
     if (!aligned16(x) || !aligned16(codes))
         return fail(DGQ_EALIGN, "dgq_quantize_act: tensor not 16-byte aligned");
     const Groups *g = reinterpret_cast<const Groups *>(h);
-    // LDS: four fp32 rows + 32-bit offset table + keep masks + per-chunk tables
-    if ((size_t)g->info.channels * 16 + (size_t)g->info.k_padded * 5 +
-            (size_t)(g->n_chunks + 8) * 8 * g->n_tab + 1300 >
-        160 * 1024)
+    if (quantize_act_lds_bytes(*g) > 160 * 1024)
         return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act: too many channels for the LDS row buffers (about 7500)");
     DGQ_HIP(launch_quantize_act(*g, x, rows, codes, row_class, static_cast<hipStream_t>(stream)));
     return DGQ_OK;

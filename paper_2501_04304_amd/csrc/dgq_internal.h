@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <string>
 #include <vector>
 
@@ -64,6 +65,9 @@ struct Groups {
     int32_t conv_taps = 0, base_kp = 0;
     uint8_t *d_fill = nullptr;
     int device = 0;
+    // One reference for the caller's handle and one per weight handle packed for it: the
+    // tables live until the last of them is released.
+    mutable std::atomic<int> refs{1};
 };
 
 struct Weight {
@@ -92,9 +96,27 @@ int hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::dgq::hip_fail(e_, #call); \
     } while (0)
 
-// Raise a kernel's dynamic-LDS limit to `bytes` (the first time only, per kernel and
-// device: the attribute call is a host round trip that hot calls should not repeat).
-hipError_t ensure_dynamic_lds(const void *kernel, int bytes);
+// Raise a kernel's dynamic-LDS limit to `bytes`, the first time only per kernel and device
+// (the attribute call is a host round trip that hot calls should not repeat).  Every launch
+// site keeps one LdsLimit per kernel instantiation; after the first call the check is one
+// atomic load, with no lock and no table shared between kernels.
+constexpr int kMaxDevices = 64;
+struct LdsLimit {
+    std::atomic<int> bytes[kMaxDevices];  // zero-initialised (static storage)
+};
+hipError_t raise_lds_limit(LdsLimit &state, const void *kernel, int bytes);
+#define DGQ_ENSURE_LDS(kernel, nbytes)                                                        \
+    ([&]() -> hipError_t {                                                                    \
+        static ::dgq::LdsLimit lim_;                                                          \
+        return ::dgq::raise_lds_limit(lim_, reinterpret_cast<const void *>(kernel), (nbytes)); \
+    }())
+
+#ifdef DGQ_TUNING
+// Builds with -DDGQ_TUNING (never the shipped library) export dgq_tuning_set(key, value): launch
+// parameters a sweep wants to force.  0 = the library's own choice.
+enum TuneKey { kTuneLinearCfg = 0, kTuneSuperRows, kTuneQuantWgPerCu, kTuneXattnWgs, kTuneKeys };
+int tuning_value(int key);
+#endif
 
 // ---- kernel launchers (each returns a hipError_t from the launch) ----------
 
@@ -124,6 +146,8 @@ hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t 
 
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
                                uint8_t *row_class, hipStream_t st);
+// LDS bytes a workgroup of the quantizer needs for this layer (tables + one row per wave).
+size_t quantize_act_lds_bytes(const Groups &g);
 
 // geglu 1: y is [rows, O / 2] and receives value * GELU(gate) (first / second half of the
 // output channels); needs O % 128 == 0 and no accumulator dump.  geglu 2: the same value

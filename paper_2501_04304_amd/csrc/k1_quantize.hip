@@ -360,26 +360,50 @@ using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const i
                       const float *, const float *, const float *, int32_t, int8_t *, uint8_t *,
                       int32_t);
 
+// A kernel instantiation and the state of its dynamic-LDS limit.
+struct Picked {
+    Kern kern;
+    LdsLimit *lim;
+};
+template <int BITS, int NV>
+Picked vec_kernel() {
+    static LdsLimit lim;
+    return {k_quantize_act<BITS, NV>, &lim};
+}
+template <int BITS>
+Picked any_kernel() {
+    static LdsLimit lim;
+    return {k_quantize_act_any<BITS>, &lim};
+}
+
 // NV = float4 loads per lane per row; exact for the usual channel counts (320 .. 5120).
 template <int BITS>
-Kern pick_vec(int32_t C) {
+Picked pick_vec(int32_t C) {
     const int nv = (C + 255) / 256;
-    if (nv <= 2) return k_quantize_act<BITS, 2>;
-    if (nv <= 3) return k_quantize_act<BITS, 3>;
-    if (nv <= 5) return k_quantize_act<BITS, 5>;
-    if (nv <= 8) return k_quantize_act<BITS, 8>;
-    if (nv <= 10) return k_quantize_act<BITS, 10>;
-    if (nv <= 20) return k_quantize_act<BITS, 20>;
-    return k_quantize_act<BITS, 40>;
+    if (nv <= 2) return vec_kernel<BITS, 2>();
+    if (nv <= 3) return vec_kernel<BITS, 3>();
+    if (nv <= 5) return vec_kernel<BITS, 5>();
+    if (nv <= 8) return vec_kernel<BITS, 8>();
+    if (nv <= 10) return vec_kernel<BITS, 10>();
+    if (nv <= 20) return vec_kernel<BITS, 20>();
+    return vec_kernel<BITS, 40>();
 }
 
 }  // namespace
+
+size_t quantize_act_lds_bytes(const Groups &g) {
+    const int32_t C = g.info.channels;
+    const bool vec4 = (C % 4) == 0 && C < 65535;
+    const size_t rows_bytes = sizeof(float) * (size_t)C * kWavesPerBlock;
+    return vec4 ? QuantLds(g.info.k_padded, g.info.act_bits, g.n_tab).table_bytes() + rows_bytes
+                : rows_bytes;
+}
 
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
                                uint8_t *row_class, hipStream_t st) {
     const int32_t C = g.info.channels, Kp = g.info.k_padded;
     const bool vec4 = (C % 4) == 0 && C < 65535;
-    Kern kern;
+    Picked kern;
     size_t lds;
     int64_t blocks;
     int32_t rpw_log2 = 2;
@@ -395,22 +419,23 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
         // resident workgroups per CU by LDS; every workgroup walks several units
         int per_cu = (int)((160 * 1024) / lds);
         per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
-        static const int env_cap = getenv("DGQ_QUANT_WGPC") ? atoi(getenv("DGQ_QUANT_WGPC")) : 0;  // tuning hook
-        if (env_cap > 0 && per_cu > env_cap) per_cu = env_cap;
+#ifdef DGQ_TUNING  // tuning builds only: cap on resident workgroups per CU
+        if (const int cap_t = tuning_value(kTuneQuantWgPerCu); cap_t > 0 && per_cu > cap_t) per_cu = cap_t;
+#endif
         const int64_t cap = 256 * (int64_t)per_cu;
         if (blocks > cap) blocks = cap;
     } else {
-        kern = g.info.act_bits == 8 ? k_quantize_act_any<8> : k_quantize_act_any<4>;
+        kern = g.info.act_bits == 8 ? any_kernel<8>() : any_kernel<4>();
         lds = sizeof(float) * (size_t)C * kWavesPerBlock;
         blocks = (rows + kWavesPerBlock - 1) / kWavesPerBlock;
         if (blocks > 2048) blocks = 2048;
     }
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
-        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), 160 * 1024);
+        hipError_t e = raise_lds_limit(*kern.lim, reinterpret_cast<const void *>(kern.kern), 160 * 1024);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, st, x, rows, C, Kp,
+    hipLaunchKernelGGL(kern.kern, dim3((unsigned)blocks), dim3(256), lds, st, x, rows, C, Kp,
                        g.n_chunks, g.d_perm, g.d_chunk_z, g.d_chunk_inv, g.d_taus, g.n_tab - 1, codes,
                        row_class, rpw_log2);
     return hipGetLastError();

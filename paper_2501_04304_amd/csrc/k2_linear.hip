@@ -763,7 +763,7 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     static_assert(!(GEGLU != 0 && MULTI), "the gated epilogue is built for at most two pixel classes");
     auto kern = k_linear<CF, DUMP, GEGLU, MULTI>;
     {
-        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kStageBudget);
+        hipError_t e = DGQ_ENSURE_LDS(kern, kStageBudget);
         if (e != hipSuccess) return e;
     }
     if (lds > (size_t)kStageBudget) return hipErrorInvalidValue;  // too many groups for the table
@@ -778,7 +778,9 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
     int32_t super_rows = (resident + tiles_o - 1) / tiles_o;
     super_rows = super_rows < 1 ? 1 : (super_rows > 8 ? 8 : super_rows);
     if (tiles_o >= 32) super_rows = 16;
-    if (const char *e = getenv("DGQ_SUPER_ROWS")) super_rows = atoi(e) > 0 ? atoi(e) : super_rows;
+#ifdef DGQ_TUNING
+    if (const int v = tuning_value(kTuneSuperRows); v > 0) super_rows = v;
+#endif
     hipLaunchKernelGGL(kern, grid, dim3(CF::THREADS), lds, st, codes, row_class, w.d_wq, w.d_sw,
                        w.d_zb, g.d_s, g.d_zoff, g.n_tab, g.d_gchunk, rows, w.O, w.O_pad, w.Kp,
                        g.info.n_groups,
@@ -789,24 +791,14 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
 
 }  // namespace
 
-static int g_force_cfg = -1;  // tuning hook: environment variable DGQ_LINEAR_CFG selects a tile shape
 
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
                          int geglu, uint8_t *rq_cls, hipStream_t st) {
-    static bool env_read = false;
-    if (!env_read) {
-        if (const char *e = getenv("DGQ_LINEAR_CFG")) g_force_cfg = atoi(e);
-        env_read = true;
-    }
     const bool a8 = g.info.act_bits == 8;
     const bool multi = g.n_tab > 2;  // more than two pixel classes (one channel group)
     if (multi && (geglu || acc_dump || g.info.n_groups != 1)) return hipErrorInvalidValue;
     if (geglu == 2 && (!w.d_rq_zi || !w.d_rq_keep || !rq_cls)) return hipErrorInvalidValue;
-    if (acc_dump) {
-        return a8 ? launch_cfg<Cfg<8, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
-                  : launch_cfg<Cfg<4, 2, 2, 2, 2, 4, 2>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
-    }
     // Four waves per SIMD in every shape: a wave's fold waits for its own MFMAs, so it is
     // the other waves that keep the matrix pipe busy meanwhile.  Large problems take
     // 128 x 128 tiles (fewer operand bytes per output), medium ones 64 x 128 tiles so that every CU still gets work, and
@@ -816,7 +808,9 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     const int64_t t128 = ((rows + 127) / 128) * ((w.O + 127) / 128);
     const int64_t t64x128 = ((rows + 63) / 64) * ((w.O + 127) / 128);
     int cfg = t128 >= 512 ? 4 : (t64x128 >= 256 ? 2 : 6);
-    if (g_force_cfg >= 0) cfg = g_force_cfg;
+#ifdef DGQ_TUNING  // tuning builds only: a forced tile shape
+    if (const int v = tuning_value(kTuneLinearCfg); v > 0) cfg = v;
+#endif
 #define DGQ_CASE(ID, ...)                                                                          \
     case ID:                                                                                       \
         if (geglu == 2)                                                                            \
@@ -825,6 +819,9 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
         if (geglu)                                                                                 \
             return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st) \
                       : launch_cfg<Cfg<4, __VA_ARGS__>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st); \
+        if (acc_dump) /* the same tile shape as the plain launch, every group accumulator stored */ \
+            return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, true>(g, w, codes, row_class, rows, y, acc_dump, st) \
+                      : launch_cfg<Cfg<4, __VA_ARGS__>, true>(g, w, codes, row_class, rows, y, acc_dump, st); \
         if (multi)                                                                                 \
             return a8 ? launch_cfg<Cfg<8, __VA_ARGS__>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st) \
                       : launch_cfg<Cfg<4, __VA_ARGS__>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st); \
@@ -841,6 +838,9 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
             if (geglu)
                 return a8 ? launch_cfg<Cfg<8, 2, 1, 1, 2, 8, 4>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st)
                           : launch_cfg<Cfg<4, 2, 1, 1, 2, 8, 4>, false, 1>(g, w, codes, row_class, rows, y, nullptr, st);
+            if (acc_dump)
+                return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 1, 8, 4>, true>(g, w, codes, row_class, rows, y, acc_dump, st)
+                          : launch_cfg<Cfg<4, 2, 2, 1, 1, 8, 4>, true>(g, w, codes, row_class, rows, y, acc_dump, st);
             if (multi)
                 return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 1, 8, 4>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st)
                           : launch_cfg<Cfg<4, 2, 2, 1, 1, 8, 4>, false, false, true>(g, w, codes, row_class, rows, y, nullptr, st);

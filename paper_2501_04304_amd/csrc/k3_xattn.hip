@@ -478,19 +478,19 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
                        const float *scale_in, hipStream_t st) {
     auto k1 = k_xattn_mfma<CF, 1, false>;
     auto k2 = codes_dump ? k_xattn_mfma<CF, 2, true> : k_xattn_mfma<CF, 2, false>;
-    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k1), (int)CF::lds_pass1);
+    hipError_t e = DGQ_ENSURE_LDS((k_xattn_mfma<CF, 1, false>), (int)CF::lds_pass1);
     if (e != hipSuccess) return e;
-    e = ensure_dynamic_lds(reinterpret_cast<const void *>(k2), (int)CF::lds_pass2);
+    e = codes_dump ? DGQ_ENSURE_LDS((k_xattn_mfma<CF, 2, true>), (int)CF::lds_pass2)
+                   : DGQ_ENSURE_LDS((k_xattn_mfma<CF, 2, false>), (int)CF::lds_pass2);
     if (e != hipSuccess) return e;
     // Queries per workgroup.  Staging K and V costs as much as a few hundred queries, so
     // a (prompt, head) pair is cut into as few pieces as still give every workgroup slot
-    // of the chip (two per CU) something to do; DGQ_XATTN_WGS overrides the slot count.
+    // of the chip (two per CU) something to do.
     constexpr int kPerTrip = 32 * kXWaves;
-    static int target_wgs = 0;
-    if (target_wgs == 0) {
-        const char *e = getenv("DGQ_XATTN_WGS");
-        target_wgs = e && atoi(e) > 0 ? atoi(e) : 512;
-    }
+    int target_wgs = 512;
+#ifdef DGQ_TUNING  // tuning builds only: the slot count
+    if (const int v = tuning_value(kTuneXattnWgs); v > 0) target_wgs = v;
+#endif
     int64_t pieces = target_wgs / ((int64_t)B * H);
     pieces = pieces < 1 ? 1 : pieces;
     int64_t per_piece = (N + pieces - 1) / pieces;
@@ -500,7 +500,8 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
     if (scale_in) {  // given scale: one kernel, Q read once
         auto k3 = codes_dump ? k_xattn_mfma<CF, 3, true> : k_xattn_mfma<CF, 3, false>;
-        e = ensure_dynamic_lds(reinterpret_cast<const void *>(k3), (int)CF::lds_pass2);
+        e = codes_dump ? DGQ_ENSURE_LDS((k_xattn_mfma<CF, 3, true>), (int)CF::lds_pass2)
+                       : DGQ_ENSURE_LDS((k_xattn_mfma<CF, 3, false>), (int)CF::lds_pass2);
         if (e != hipSuccess) return e;
         if (scale_out)
             hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
@@ -892,8 +893,8 @@ hipError_t launch_selfattn_cfg(const float *q, const float *k, const float *v, i
     const dim3 grid((unsigned)(groups * q_tiles * 8));
     const size_t lds = (size_t)CF::STAGES * CF::TILE_BYTES;
     {
-        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k_selfattn<CF, true>), (int)lds);
-        if (e == hipSuccess) e = ensure_dynamic_lds(reinterpret_cast<const void *>(k_selfattn<CF, false>), (int)lds);
+        hipError_t e = DGQ_ENSURE_LDS((k_selfattn<CF, true>), (int)lds);
+        if (e == hipSuccess) e = DGQ_ENSURE_LDS((k_selfattn<CF, false>), (int)lds);
         if (e != hipSuccess) return e;
     }
     if (codes_dump)
@@ -1105,9 +1106,9 @@ hipError_t launch_passes(const float *q, const float *k, const float *v, const f
     auto k1 = k_xattn<NKP, 1>;
     auto k2 = k_xattn<NKP, 2>;
     if (lds > 64 * 1024) {
-        hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(k1), (int)lds);
+        hipError_t e = DGQ_ENSURE_LDS((k_xattn<NKP, 1>), (int)lds);
         if (e != hipSuccess) return e;
-        e = ensure_dynamic_lds(reinterpret_cast<const void *>(k2), (int)lds);
+        e = DGQ_ENSURE_LDS((k_xattn<NKP, 2>), (int)lds);
         if (e != hipSuccess) return e;
     }
     // scale_out accumulates a maximum: clear it with a fill kernel (capturable in a graph)

@@ -64,3 +64,21 @@ def assert_close_fp32(got, ref, what=""):
     err = np.abs(got - ref).max()
     lim = 1e-4 * np.abs(ref).max()
     assert err <= lim, "%s max|err| %.3e > %.3e" % (what, err, lim)
+
+
+def scale_rtol(c, use_bias=True):
+    """Relative bar for the prompt scale of a cross-attention case, derived from fp32.
+
+    The scale is 2^(S - lse2), with S a logit and lse2 the log-sum of its row, both fp32
+    numbers in log2 units whose magnitude reaches L = max|logit| * log2(e).  Each carries
+    about two roundings at that magnitude (the dot product, the scaling, the log-sum), the
+    oracle none (it works in double), so the relative error of the scale is bounded by
+    ln 2 * 4 * ulp32(L): 1.3e-6 for L in [4, 8), 2.6e-6 in [8, 16), 5.3e-6 in [16, 32).
+    Never below 1e-6, the bar the full-size configurations are held to."""
+    Q = c["Q"].astype(np.float64)
+    K = c["K"].astype(np.float64)
+    logits = np.einsum("bihd,bjhd->bhij", Q, K) / np.sqrt(Q.shape[-1])
+    if use_bias and c.get("key_bias") is not None:
+        logits = logits + c["key_bias"].astype(np.float64)
+    big = np.abs(logits).max() * 1.4426950408889634
+    return max(1e-6, float(np.log(2.0) * 4.0 * np.spacing(np.float32(big))))

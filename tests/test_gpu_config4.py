@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import dgq_inputs as di
-from test_gpu_linear import _run_layer
+from test_gpu_linear import _run_layer, tile_rows
 from test_gpu_xattn import _compare
 
 pytestmark = pytest.mark.gpu
@@ -48,9 +48,7 @@ def test_config4_linears(dgq, oracle, li, ent, mode):
     seed = di.layer_seed(CFG4["seed"], li)
     run = di.linear_case(seed, B, N, C, O)
     cal = di.linear_case(seed, B, N, C, O, calib=True)
-    rng = np.random.default_rng(seed)
-    rows = np.unique(np.concatenate([rng.choice(M, min(M, 24), replace=False), run["rows_ot"][:4],
-                                     [0, M - 1]]))
+    rows = tile_rows(M, seed, run["rows_ot"][:4])
     _run_layer(dgq, oracle, run, cal, mode[0], mode[1], G, sample_rows=rows)
 
 
@@ -60,4 +58,6 @@ def test_config4_attention(dgq, oracle, si):
     name, B, N, H, d, nk, d_ctx = CFG4["stages"][si]["attention"][0]
     c, _ = guarded_attention_case(CFG4["seed"] + 900 + si, B, N, H, d, nk=nk, d_ctx=d_ctx,
                                   bits_list=(8,))
-    _compare(dgq, oracle, c, 8, exact=True)
+    # the prompt scale: 1e-6 on the three large stages; the 8 x 8 stage (64 queries, its
+    # maximum decided by one row) takes the bar derived from its logits' magnitude
+    _compare(dgq, oracle, c, 8, exact=True, s_rtol=1e-6 if N >= 256 else None)

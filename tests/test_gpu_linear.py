@@ -54,28 +54,39 @@ def _run_layer(dgq, oracle, run, cal, act_bits, w_bits, G, P=2, bias=None, sampl
 
     y = dgq.dgq_linear(gg, wt, codes, cls)
     torch.cuda.synchronize()
-    y_np = y.cpu().numpy()
     sel = np.arange(rows) if sample_rows is None else np.asarray(sample_rows)
+    sel_dev = torch.from_numpy(sel).cuda()
+    y_sel = y[sel_dev].cpu().numpy()
     oy, oacc = oracle.linear(og, oq["q"][sel], oq["cls"][sel], owq, osw, bias, want_acc=check_acc)
-    assert_close_fp32(y_np[sel], oy, "y")
+    assert_close_fp32(y_sel, oy, "y")
+    # the same bar per pixel class: the outlier rows are 25 times larger and would otherwise
+    # set the scale of the tolerance for every regular row
+    for p in np.unique(oq["cls"][sel]):
+        m = oq["cls"][sel] == p
+        assert_close_fp32(y_sel[m], oy[m], "y(class %d rows)" % p)
     if check_acc:
-        if sample_rows is None:
-            dump = torch.full((rows, O, og.NG), -7, dtype=torch.int32, device="cuda")
-            y2 = dgq.dgq_linear(gg, wt, codes, cls, acc_dump=dump)
-            torch.cuda.synchronize()
-            assert np.array_equal(dump.cpu().numpy(), oacc)
-            assert np.array_equal(y2.cpu().numpy(), y_np)  # the dump path gives the same y
-        else:
-            # re-run the sampled rows alone with the accumulator dump
-            sub_codes, sub_cls = dgq.dgq_quantize_act(gg, _dev(X[sel]))
-            dump = torch.full((len(sel), O, og.NG), -7, dtype=torch.int32, device="cuda")
-            y2 = dgq.dgq_linear(gg, wt, sub_codes, sub_cls, acc_dump=dump)
-            torch.cuda.synchronize()
-            assert np.array_equal(dump.cpu().numpy(), oacc)
-            assert_close_fp32(y2.cpu().numpy(), oy, "y(sampled)")
+        # The accumulator dump runs the SAME tile shape as the plain launch (the launcher
+        # picks the shape from the problem size alone), at full size: every int32 group
+        # accumulator of the sampled rows against the oracle, and the dump launch's y
+        # against the plain launch's y on the whole tensor, bit for bit (same fold order).
+        dump = torch.full((rows, O, og.NG), -7, dtype=torch.int32, device="cuda")
+        y2 = dgq.dgq_linear(gg, wt, codes, cls, acc_dump=dump)
+        torch.cuda.synchronize()
+        assert np.array_equal(dump[sel_dev].cpu().numpy(), oacc)
+        assert torch.equal(y2.view(torch.int32), y.view(torch.int32))
+        del dump, y2
     wt.free()
     gg.free()
     return og
+
+
+def tile_rows(M, seed, extra=()):
+    """One row of every 128-row tile (a random offset in each), the tensor's first and last
+    rows, and `extra`: a fault tied to a tile index cannot hide between the samples."""
+    rng = np.random.default_rng(seed)
+    starts = np.arange(0, M, 128)
+    picks = np.minimum(starts + rng.integers(0, 128, size=len(starts)), M - 1)
+    return np.unique(np.concatenate([picks, np.asarray(extra, dtype=np.int64), [0, M - 1]]))
 
 
 SMALL = [
@@ -142,25 +153,24 @@ def test_config2_layers(dgq, oracle, li, mode):
     seed = di.layer_seed(CFG2["seed"], li)
     run = di.linear_case(seed, B, N, C, O)
     cal = di.linear_case(seed, B, N, C, O, calib=True)
-    rng = np.random.default_rng(seed)
-    rows = np.unique(np.concatenate([rng.choice(M, 40, replace=False), run["rows_ot"],
-                                     [0, 127, 128, M - 1]]))
+    rows = tile_rows(M, seed, np.concatenate([run["rows_ot"], [127, 128]]))
     _run_layer(dgq, oracle, run, cal, mode[0], mode[1], G, sample_rows=rows)
 
 
 @pytest.mark.parametrize("mode", [(8, 8), (4, 8)])
 @pytest.mark.parametrize("shape", [(16, 4096, 640, 640), (16, 4096, 640, 5120),
-                                   (16, 1024, 1280, 10240), (16, 1024, 5120, 1280)])
+                                   (16, 4096, 2560, 640), (16, 1024, 1280, 1280),
+                                   (16, 1024, 1280, 10240), (16, 1024, 5120, 1280),
+                                   (16, 77, 2048, 640), (16, 77, 2048, 1280)])
 def test_config5_sampled(dgq, oracle, shape, mode):
-    """SDXL-scale layers (q/k/v/out, both ff.in shapes, the long-K ff.out) in the launch
-    configuration bench.py times, both activation code widths."""
+    """Every distinct launch shape of the SDXL-scale step bench.py times (q/k/v/out, ff.in
+    and ff.out at both resolutions, the two projections of the 77-token prompt), both
+    activation code widths, at full size; the oracle checks one row of every 128-row tile."""
     B, N, C, O = shape
     run = di.linear_case(5000 + C + O, B, N, C, O)
     cal = di.linear_case(5000 + C + O, B, N, C, O, calib=True)
     M = B * N
-    rng = np.random.default_rng(1)
-    rows = np.unique(np.concatenate([rng.choice(M, 24, replace=False), run["rows_ot"][:4],
-                                     [0, M - 1]]))
+    rows = tile_rows(M, 1, run["rows_ot"][:4])
     _run_layer(dgq, oracle, run, cal, mode[0], mode[1], 128, sample_rows=rows)
 
 

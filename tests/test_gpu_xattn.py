@@ -3,20 +3,21 @@
 Codes are compared bit-exactly on margin-guarded inputs (oracle/guard.py: no
 rounding decision within 2^-13 log2 units of a boundary); on raw inputs every
 element whose oracle margin is at least that large must still match and the
-few others may differ by one step.  The prompt scale is exp2 of an fp32 logit
-difference: logits reach 2^4..2^5 in log2 units, where one fp32 ulp is 2e-6 to
-4e-6, so a handful of roundings (input scaling, the accumulation, the log-sum)
-bound its relative error by S_RTOL = 1e-5.  The product is held to
-1e-4 * max|ref|."""
+few others may differ by one step.  The prompt scale is an fp32 output: the
+full-size configurations (config 3, config 5) are held to S_RTOL = 1e-6; the
+small cases, whose maximum sits wherever a handful of rows put it, to the bar
+support.scale_rtol derives from the magnitude of their logits (four fp32
+roundings at that magnitude, 1.3e-6 to 5.3e-6; measured up to 2.2e-6).  The
+product is held to 1e-4 * max|ref|."""
 import numpy as np
 import pytest
 
 import dgq_inputs as di
-from support import assert_close_fp32
+from support import assert_close_fp32, scale_rtol
 
 pytestmark = pytest.mark.gpu
 
-S_RTOL = 1e-5
+S_RTOL = 1e-6
 
 
 @pytest.fixture(scope="module")
@@ -45,11 +46,13 @@ def _gpu(dgq, c, bits, use_bias=True):
     return out.cpu().numpy(), s.cpu().numpy(), codes.cpu().numpy()
 
 
-def _compare(dgq, oracle, c, bits, exact=True, use_bias=True):
+def _compare(dgq, oracle, c, bits, exact=True, use_bias=True, s_rtol=None):
     from oracle.guard import DELTA
     ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"] if use_bias else None, bits)
     out, s, codes = _gpu(dgq, c, bits, use_bias)
-    assert np.all(np.abs(s - ref["s"]) <= S_RTOL * ref["s"])
+    if s_rtol is None:
+        s_rtol = scale_rtol(c, use_bias)
+    assert np.all(np.abs(s - ref["s"]) <= s_rtol * ref["s"])
     safe = ref["margin"] >= DELTA
     assert np.array_equal(codes[safe], ref["codes"][safe])
     if exact:
@@ -110,20 +113,21 @@ def test_config3_full(dgq, oracle, bits):
     name, B, N, H, d, nk, d_ctx = di.config3()["attention"][0]
     c, n_redrawn = guarded_attention_case(3000, B, N, H, d, nk=nk, d_ctx=d_ctx, bits_list=(4, 8))
     assert n_redrawn < 0.1 * B * N * H
-    _compare(dgq, oracle, c, bits, exact=True)
+    _compare(dgq, oracle, c, bits, exact=True, s_rtol=S_RTOL)
 
 
-def test_config5_shape_sampled(dgq, oracle):
-    """SDXL-scale launch shape (16 prompts, 10 heads, d = 64); the oracle checks
-    two whole prompts, which is what a per-prompt scale allows."""
+@pytest.mark.parametrize("bits", [4, 8])
+def test_config5_shape_sampled(dgq, oracle, bits):
+    """SDXL-scale launch shape (16 prompts, 10 heads, d = 64), both code widths bench.py
+    times; the oracle checks two whole prompts, which is what a per-prompt scale allows."""
     import torch
     name, B, N, H, d, nk, d_ctx = di.config5()["attention"][0]
     c = di.attention_case(5000, B, N, H, d, nk=nk, d_ctx=d_ctx)
     from oracle.guard import DELTA
-    out, s, codes = _gpu(dgq, c, 8)
+    out, s, codes = _gpu(dgq, c, bits)
     for b in (0, B - 1):
         sub = {k: (v[b:b + 1] if k != "key_bias" else v) for k, v in c.items()}
-        ref = oracle.xattn(sub["Q"], sub["K"], sub["V"], sub["key_bias"], 8)
+        ref = oracle.xattn(sub["Q"], sub["K"], sub["V"], sub["key_bias"], bits)
         assert abs(s[b] - ref["s"][0]) <= S_RTOL * ref["s"][0]
         safe = ref["margin"][0] >= DELTA
         assert np.array_equal(codes[b][safe], ref["codes"][0][safe])
@@ -147,7 +151,7 @@ def test_scale_buffer_is_reset_between_calls(dgq, oracle):
                                     8, scale_out=s_buf)
         torch.cuda.synchronize()
         ref = oracle.xattn(c["Q"], c["K"], c["V"], c["key_bias"], 8)
-        assert abs(s.item() - ref["s"][0]) <= S_RTOL * ref["s"][0]
+        assert abs(s.item() - ref["s"][0]) <= scale_rtol(c) * ref["s"][0]
 
 
 @pytest.mark.parametrize("bits", [4, 8])
@@ -184,4 +188,4 @@ def test_given_scale_one_pass(dgq, oracle, B, N, H, d, nk, bits):
         good = np.transpose(safe.all(-1), (0, 2, 1))  # [B, N, H]: rows without a marginal code
         err = np.abs(out.cpu().numpy() - ref["out"])[good]
         assert err.size and err.max() <= 1e-4 * np.abs(ref["out"]).max()
-        assert np.all(np.abs(ref["s"] - s_dyn) <= S_RTOL * s_dyn)
+        assert np.all(np.abs(ref["s"] - s_dyn) <= scale_rtol(c) * s_dyn)
