@@ -365,6 +365,27 @@ int dgq_xattn_logq(const float *q, const float *k, const float *v,
 size_t dgq_xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d,
                                  int32_t nk);
 
+/*
+ * dgq_xattn_logq for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same computation, same kernels and the same results bit for bit; the float per (b, h,
+ * query) kept between the two kernels lives in a fixed array inside the library's device
+ * image instead of a caller's workspace.  The call allocates nothing and frees nothing.
+ *   Limit: B * H * N <= DGQ_XATTN_NOALLOC_MAX_ROWS (4 MiB of floats; DGQ_EWORKSPACE beyond,
+ *          nothing is enqueued).  Every GPU the library runs on holds those 4 MiB from the
+ *          first call on it until the process ends.
+ *   Sharing: all calls on one GPU use the same array, whichever stream they run on, and the
+ *          array keeps the last call's contents (nothing in it needs clearing: the first
+ *          kernel writes every entry the second one reads).  Two calls that overlap in time
+ *          on one GPU race; calls on one stream, or ordered by events, do not.
+ * Arguments as in dgq_xattn_logq, without workspace and workspace_bytes.
+ */
+#define DGQ_XATTN_NOALLOC_MAX_ROWS (1u << 20)
+int dgq_xattn_logq_noalloc(const float *q, const float *k, const float *v,
+                           const float *key_bias, int32_t B, int32_t N, int32_t H,
+                           int32_t d, int32_t nk, int32_t attn_bits, float *out,
+                           float *scale_out, uint8_t *codes_dump, void *stream);
+
 /* Host string describing the last error on this thread ("" if none). */
 const char *dgq_last_error(void);
 

@@ -73,6 +73,8 @@ def lib():
         L.dgq_xattn_logq.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
                                      vp, sz, vp]
         L.dgq_xattn_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.dgq_xattn_logq_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp,
+                                             vp, vp]
         L.dgq_quantize_value.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         L.dgq_xattn_logq_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
                                             vp, vp]
@@ -386,6 +388,36 @@ def dgq_xattn_logq(q, k, v, key_bias, attn_bits: int, out=None, scale_out=None, 
     _check(lib().dgq_xattn_logq(_ptr(q), _ptr(k), _ptr(v), _ptr(key_bias), B, N, H, d, nk,
                                 attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
                                 _ptr(workspace), wbytes, _stream(stream)))
+    return out, scale_out
+
+
+XATTN_NOALLOC_MAX_ROWS = 1 << 20
+
+
+def dgq_xattn_logq_noalloc(q, k, v, key_bias, attn_bits: int, out, scale_out, codes_dump=None,
+                           stream=None):
+    """dgq_xattn_logq without a workspace: the caller passes every buffer (out [B,N,H,d],
+    scale_out [B]) and nothing is allocated, here or in the library."""
+    import torch
+    for t, name in ((q, "q"), (k, "k"), (v, "v"), (out, "out"), (scale_out, "scale_out")):
+        _dev(t, torch.float32, name)
+    if key_bias is not None:
+        _dev(key_bias, torch.float32, "key_bias")
+    B, N, H, d = q.shape
+    nk = k.shape[1]
+    if tuple(k.shape) != (B, nk, H, d) or tuple(v.shape) != (B, nk, H, d):
+        raise ValueError("k / v have the wrong shape")
+    if tuple(out.shape) != (B, N, H, d) or scale_out.numel() != B:
+        raise ValueError("out / scale_out have the wrong shape")
+    if key_bias is not None and key_bias.numel() != nk:
+        raise ValueError("key_bias has the wrong shape")
+    if codes_dump is not None:
+        _dev(codes_dump, torch.uint8, "codes_dump")
+        if tuple(codes_dump.shape) != (B, H, N, nk - 1):
+            raise ValueError("codes_dump has the wrong shape")
+    _check(lib().dgq_xattn_logq_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(key_bias), B, N, H, d, nk,
+                                        attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
+                                        _stream(stream)))
     return out, scale_out
 
 

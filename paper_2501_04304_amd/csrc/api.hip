@@ -940,6 +940,70 @@ int dgq_xattn_logq(const float *q, const float *k, const float *v, const float *
     return DGQ_OK;
 }
 
+// ---- the attention for callers that cannot allocate ---------------------------------------
+// dgq_xattn_logq keeps one float per (prompt, head, query) between its two kernels in a
+// workspace the caller brings.  This variant keeps it in device memory that is part of the
+// loaded library: a fixed array every GPU holds its own copy of.  The array's name is a
+// host-side stand-in, not a device address; the address on the current device comes from
+// hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+}  // extern "C"
+
+constexpr size_t kScratchFloats = DGQ_XATTN_NOALLOC_MAX_ROWS;
+static __device__ __align__(256) float scratch[kScratchFloats];
+
+namespace {
+std::atomic<float *> g_scratch_ptr[kMaxDevices];
+
+int scratch_on_current_device(float **out) {
+    int dev = 0;
+    DGQ_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_noalloc: device index above 63");
+    float *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        DGQ_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+        if (!sym) return fail(DGQ_EHIP, "dgq_xattn_logq_noalloc: no device address for the scratch array");
+        p = static_cast<float *>(sym);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // the same value from every thread
+    }
+    *out = p;
+    return DGQ_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int dgq_xattn_logq_noalloc(const float *q, const float *k, const float *v, const float *key_bias,
+                           int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk,
+                           int32_t attn_bits, float *out, float *scale_out, uint8_t *codes_dump,
+                           void *stream) {
+    if (!q || !k || !v || !out || !scale_out)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq_noalloc: null pointer");
+    if (B < 1 || N < 1 || H < 1) return fail(DGQ_EINVAL, "dgq_xattn_logq_noalloc: empty tensor");
+    if (attn_bits != 4 && attn_bits != 8)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq_noalloc: attn_bits must be 4 or 8");
+    if (nk < 2 || nk > 128 || d < 1 || d > 256)
+        return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_noalloc: needs 2 <= nk <= 128 and 1 <= d <= 256");
+    if (B > 65535 || H > 65535)
+        return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_noalloc: B or H above 65535");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) ||
+        (key_bias && !aligned16(key_bias)))
+        return fail(DGQ_EALIGN, "dgq_xattn_logq_noalloc: tensor not 16-byte aligned");
+    const size_t need = xattn_workspace_bytes(B, N, H, d, nk);
+    if (need > sizeof(float) * kScratchFloats)
+        return fail(DGQ_EWORKSPACE,
+                    "dgq_xattn_logq_noalloc: B * H * N exceeds DGQ_XATTN_NOALLOC_MAX_ROWS; use "
+                    "dgq_xattn_logq with a workspace");
+    float *ws = nullptr;
+    if (need) {
+        const int rc = scratch_on_current_device(&ws);
+        if (rc != DGQ_OK) return rc;
+    }
+    DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
+                         ws, nullptr, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
 int dgq_xattn_logq_static(const float *q, const float *k, const float *v, const float *key_bias,
                           int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t attn_bits,
                           const float *scale_in, float *out, float *scale_out, uint8_t *codes_dump,

@@ -49,6 +49,7 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_linear_geglu_requant(None, None, None, None, 4, None, None, None) == -1
     assert lib.dgq_pack_weight_gated_for(None, None, None, None, 512, 8, None, None) == -1
     assert lib.dgq_xattn_logq_static(None, None, None, None, 1, 1, 1, 8, 77, 8, None, None, None, None, None) == -1
+    assert lib.dgq_xattn_logq_noalloc(None, None, None, None, 1, 1, 1, 8, 77, 8, None, None, None, None) == -1
     assert lib.dgq_quantize_value(None, 1, 77, 1, 8, 8, None, None, None, None) == -1
     assert lib.dgq_selfattn_logq(None, None, None, 1, 8, 1, 8, 8, None, None, None, None, None, 0, None) == -1
     assert lib.dgq_groups_for_conv3x3(None, None) == -1
