@@ -39,12 +39,86 @@ def measured_traffic():
 METRIC = "dgq_linear int8 TOPS (% MFMA peak) + xattn_logq GB/s (% HBM), 1 MI355X"
 
 
+def cpu_model():
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.lower().startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def measure_ceilings(torch, dgq, dev, which=("mfma", "stream")):
+    """What this very box delivers: the bare int8 matrix instruction and plain streaming
+    kernels over a buffer eight times the 256 MB memory-side cache (best of three each)."""
+    import ctypes as C
+    L = dgq.lib()
+    L.dgq_probe_mfma_i8.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.dgq_probe_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+    stream = torch.cuda.current_stream()
+    sp = C.c_void_p(stream.cuda_stream)
+    out = {}
+
+    def best_us(fn, n=3):
+        fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3
+            best = us if best is None else min(best, us)
+        return best
+
+    if "mfma" in which:
+        blocks, iters = 1024, 4000   # four workgroups of four waves per CU: four waves per SIMD
+        sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
+
+        def run_mfma():
+            if L.dgq_probe_mfma_i8(blocks, iters, C.c_void_p(sink.data_ptr()), sp) != 0:
+                raise RuntimeError(L.dgq_last_error().decode())
+        us = best_us(run_mfma)
+        assert int(sink[0]) == 32 * iters, "the matrix-instruction probe computed something else"
+        ops = blocks * 4.0 * iters * 4 * 2 * 32 * 32 * 32
+        out["mfma_i8_tops"] = round(ops / us / 1e6, 1)
+        del sink
+    if "stream" in which:
+        nbytes = 1 << 31
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        for mode, key, moved in ((0, "hbm_read_gbs", nbytes), (1, "hbm_write_gbs", nbytes),
+                                 (2, "hbm_copy_gbs", 2 * nbytes)):
+            def run_stream(mode=mode):
+                if L.dgq_probe_stream(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), C.c_size_t(nbytes),
+                                      mode, C.c_void_p(sink.data_ptr()), sp) != 0:
+                    raise RuntimeError(L.dgq_last_error().decode())
+            us = best_us(run_stream)
+            out[key] = round(moved / us / 1e3, 1)
+        L.dgq_probe_write_tiles.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+        for oc in (640, 5120):   # the fp32 output of the narrow and of the wide layers, 2 GiB each
+            rows_t = nbytes // (4 * oc) // 128 * 128
+
+            def run_tiles(oc=oc, rows_t=rows_t):
+                if L.dgq_probe_write_tiles(C.c_void_p(dst.data_ptr()), rows_t, oc, sp) != 0:
+                    raise RuntimeError(L.dgq_last_error().decode())
+            us = best_us(run_tiles)
+            out["tile_write_gbs_o%d" % oc] = round(4.0 * rows_t * oc / us / 1e3, 1)
+        del src, dst
+    torch.cuda.synchronize()
+    return out
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config5", choices=["config5", "config2+3"])
+    ap.add_argument("--workload", default="config5", choices=["config5", "config2+3", "config4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--step-only", action="store_true",
                     help="skip the measurements beside the step (fused gated epilogue, K-means "
@@ -54,6 +128,12 @@ def parse():
     ap.add_argument("--probe-copy", action="store_true",
                     help="run only a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB), "
                          "three times: the reference that scales the profiler's HBM byte counters")
+    ap.add_argument("--probe-mfma", action="store_true",
+                    help="run only the bare v_mfma_i32_32x32x32_i8 loop and print its rate")
+    ap.add_argument("--probe-stream", action="store_true",
+                    help="run only the streaming read / write / copy kernels over 2 GiB and print their rates")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (bare matrix instruction, streaming kernels)")
     ap.add_argument("--probe-selfattn", action="store_true",
                     help="run only dgq_selfattn_logq on 16 x 10 heads x 4096 tokens x 64, 8-bit codes, "
                          "three times: the launches the profiler's counters are read for")
@@ -67,6 +147,22 @@ def workload(name):
         desc = ("config5: SDXL-scale sweep, 1024x1024, batch 8x2; linears [65536x640] and "
                 "[16384x1280] (q,k,v,out, text k/v from 2048, ff.in, ff.out), G=128, A8W8 and "
                 "A4W8; cross-attention 16x10 heads x 4096 queries x 77 keys, d=64, 4- and 8-bit codes")
+        return c, desc
+    if name == "config4":
+        c4 = di.config4()
+        lin, att, reps = [], [], {}
+        for st in c4["stages"]:
+            for ent in st["linears"]:
+                lin.append(ent)
+                reps[ent[0]] = st["reps"]
+            for a in st["attention"]:
+                att.append(a)
+                reps[a[0]] = st["reps"]
+        c = dict(seed=c4["seed"], linears=lin, modes=c4["modes"], attention=att,
+                 attn_bits=c4["attn_bits"], reps=reps)
+        desc = ("config4: every DGQ linear and cross-attention of one transformer block at each of the "
+                "four stages of an SD-v1.4 UNet step, 512x512, batch 2 (64x64/320, 32x32/640, 16x16/1280, "
+                "8x8/1280; blocks per stage 5/5/5/1 listed as reps), A8W8 and A8W4, 8-bit attention codes")
         return c, desc
     c2, c3 = di.config2(), di.config3()
     c = dict(seed=c2["seed"], linears=c2["linears"], modes=c2["modes"],
@@ -101,6 +197,11 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps(dict(probe="copy", read_bytes=4 * n, write_bytes=4 * n, launches=3)))
         return
+    if args.probe_mfma or args.probe_stream:
+        which = (("mfma",) if args.probe_mfma else ()) + (("stream",) if args.probe_stream else ())
+        print(json.dumps(dict(probe="ceilings", **measure_ceilings(torch, dgq, dev, which))))
+        return
+    ceilings = None if args.no_ceilings else measure_ceilings(torch, dgq, dev)
     if args.probe_selfattn:
         B_, N_, H_, d_ = 16, 4096, 10, 64
         c_ = di.selfattn_case(77, 1, N_, H_, d_)
@@ -133,7 +234,7 @@ def main():
             wt = dgq.dgq_pack_weight(g, w, None, wb)
             codes = torch.empty(dgq.codes_shape(g, M), dtype=torch.int8, device=dev)
             cls = torch.empty(M, dtype=torch.uint8, device=dev)
-            ent["modes"][(ab, wb)] = dict(g=g, wt=wt, codes=codes, cls=cls, Kp=g.info.k_padded)
+            ent["modes"][(ab, wb)] = dict(g=g, wt=wt, codes=codes, cls=cls, Kp=g.info.k_padded, wb=wb)
         ent["y"] = torch.empty((M, O), dtype=torch.float32, device=dev)
         del w, xc
         layers.append(ent)
@@ -157,7 +258,9 @@ def main():
         for (ab, wb) in cfg["modes"]:
             for ent in layers:
                 m = ent["modes"][(ab, wb)]
-                qbytes = ent["M"] * ent["C"] * 4 + ent["M"] * m["Kp"] * (1 if ab == 8 else 0.5) + ent["M"]
+                # algorithmic bytes per row: 4 C read, C (8-bit) or C / 2 (4-bit) code bytes and one
+                # class byte written; the padding positions the kernel also writes are overhead
+                qbytes = ent["M"] * (ent["C"] * 4 + ent["C"] * (1 if ab == 8 else 0.5) + 1)
                 calls.append(("quantize_a%d" % ab, (ent, m), qbytes))
                 calls.append(("linear_a%d" % ab, (ent, m), 2.0 * ent["M"] * ent["C"] * ent["O"]))
         for bits in cfg["attn_bits"]:
@@ -271,8 +374,16 @@ def main():
             ach, peak, unit, bound = a["units"] / sec / 1e12, PEAK_INT8_TOPS, "TOP/s", "mfma"
         else:
             ach, peak, unit, bound = a["units"] / sec / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+        pm = None
+        if ceilings:
+            # the contraction against the bare matrix instruction; the quantizer (reads 4 bytes
+            # per byte it writes) against the streaming read; the attention (reads as much as it
+            # writes) against the streaming copy
+            pm = (ceilings["mfma_i8_tops"] if bound == "mfma" else
+                  ceilings["hbm_read_gbs"] if kind.startswith("quantize") else ceilings["hbm_copy_gbs"])
         kernels[kind] = dict(bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
-                             frac=round(ach / peak, 4),
+                             frac=round(ach / peak, 4), peak_measured=pm,
+                             frac_of_measured=(round(ach / pm, 4) if pm else None),
                              avg_call_us=round(a["ms"] * 1e3 / a["launches"], 2),
                              calls_per_step=a["launches"] // args.steps)
     # per-layer view of the 8-bit contraction: % of the MFMA peak and % of the layer's own
@@ -289,12 +400,34 @@ def main():
                               tops=round(units / us / 1e6, 1),
                               frac_mfma=round(units / us / 1e6 / PEAK_INT8_TOPS, 4),
                               frac_roofline=round(t_roof * 1e6 / us, 4)))
+    # config 4: every call of the step as a table (one transformer block per stage; `reps` =
+    # blocks of that stage in the UNet), and the UNet-wide time the table adds up to
+    layer_table = None
+    unet_ms = None
+    if args.workload == "config4":
+        layer_table, unet_ms = [], 0.0
+        for ci, (kind, key, units) in enumerate(calls):
+            us = sum(ev[k][ci][0].elapsed_time(ev[k][ci][1]) for k in range(args.steps)) * 1e3 / args.steps
+            ent = key[0]
+            reps = cfg["reps"][ent["name"]]
+            row = dict(call=kind, layer=ent["name"], reps=reps, us=round(us, 2))
+            if kind.startswith("xattn"):
+                row.update(B=ent["B"], N=ent["N"], H=ent["H"], d=ent["d"], gbs=round(units / us / 1e3, 1))
+            else:
+                row.update(M=ent["M"], C=ent["C"], O=ent["O"])
+                if kind.startswith("linear"):
+                    row.update(w_bits=key[1]["wb"], tops=round(units / us / 1e6, 1))
+                else:
+                    row.update(gbs=round(units / us / 1e3, 1))
+            layer_table.append(row)
+            unet_ms += reps * us * 1e-3
     total_ops = sum(u for (kind, _, u) in calls if kind.startswith("linear"))
     value = total_ops / (ms_per_step * 1e-3) / 1e12
     dom = kernels["linear_a8"]
     roofline = dict(kernel="k_linear<8,false> (dgq_linear, 8-bit activation codes)",
                     bound="mfma", achieved=dom["achieved"], peak=PEAK_INT8_TOPS, unit="TOP/s",
-                    frac=dom["frac"],
+                    frac=dom["frac"], peak_measured=dom["peak_measured"],
+                    frac_of_measured=dom["frac_of_measured"],
                     traffic=measured_traffic() if args.workload == "config5" else None,
                     avg_launch_us=dom["avg_call_us"],
                     launches_per_step=dom["calls_per_step"])
@@ -559,6 +692,10 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
+        # one thread on one core: pin the process for the oracle leg and restore it afterwards
+        allowed = sorted(os.sched_getaffinity(0))
+        pinned = allowed[0]
+        os.sched_setaffinity(0, {pinned})
         t_ops = 0.0
         t_sec = 0.0
         frac = 24
@@ -577,9 +714,12 @@ def main():
             oracle.linear(og, oq["q"], oq["cls"], owq, osw, None)
             t_sec += time.perf_counter() - t1
             t_ops += 2.0 * rows * ent["C"] * ent["O"]
+        os.sched_setaffinity(0, set(allowed))
         cpu = dict(value=round(t_ops / t_sec / 1e12, 6), unit="TOPS", cores=1, kind="oracle",
+                   cpu_model=cpu_model(), nproc=os.cpu_count(), cores_allowed=len(allowed),
+                   pinned_to_core=pinned,
                    sample=("first 1/%d of the rows of every large linear layer, A8W8, quantize + "
-                           "contraction, single thread; %.1f s of CPU work" % (frac, t_sec)))
+                           "contraction, single thread pinned to one core; %.1f s of CPU work" % (frac, t_sec)))
 
     line = dict(metric=METRIC, value=round(value, 2), unit="TOPS", n_gpus=1, steps=args.steps,
                 warmup=args.warmup, ms_per_step=round(ms_per_step, 4),
@@ -589,7 +729,8 @@ def main():
                 scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
                 config=dict(workload=desc, linear_ops_per_step=total_ops,
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
-                roofline=roofline, kernels=kernels, linear_a8_layers=per_layer,
+                roofline=roofline, ceilings_measured=ceilings, kernels=kernels, linear_a8_layers=per_layer,
+                layer_table=layer_table, ms_whole_unet_from_table=(round(unet_ms, 3) if unet_ms else None),
                 linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, value_quant=value_quant, self_attention=self_attn, conv3x3=conv, cpu_baseline=cpu)
     print(json.dumps(line))
 

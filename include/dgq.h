@@ -351,7 +351,7 @@ size_t dgq_linear_workspace_bytes(const dgq_groups_t *g, const dgq_weight_t *w,
  * Limits: 2 <= nk <= 128, 1 <= d <= 256, attn_bits in {4, 8}.
  * Two kernels run back to back on `stream` (all probabilities must be known
  * before any of them can be coded).  Shapes with d a multiple of 8 up to 96 and
- * nk <= 126 run on the matrix cores, with q and k each split into two fp16
+ * nk <= 126, or up to 160 and nk <= 94, run on the matrix cores, with q and k each split into two fp16
  * pieces (|q| and |k| * log2(e) / sqrt(d) must stay below 65504 there) and one
  * float per (b, h, query) kept in the workspace between the two kernels; every
  * other shape uses fp32 vector arithmetic and no workspace.

@@ -14,7 +14,7 @@
 // which needs no exponential per element and is exact to ~1e-6 in log2 units;
 // a probability below 2^-150 rounds to zero in fp32 and takes the top code.
 //
-// Matrix-core path (head dim a multiple of 8 up to 96, nk <= 126)
+// Matrix-core path (head dim a multiple of 8 up to 96 with nk <= 126, up to 160 with nk <= 94)
 // ----------------------------------------------------------------
 // A workgroup owns one (prompt, head) pair and a range of queries; its eight
 // wavefronts each take 32 queries at a time.  The logits are computed
@@ -161,7 +161,13 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
     uint16_t *Vl = Vh + DP * VROW;
     __shared__ float red[kXWaves];
 
-    const int32_t b = blockIdx.z, head = blockIdx.y;
+    // (Walking pass 2 in the reverse of pass 1's order, workgroups and query blocks alike, so
+    // that it meets the rows of Q pass 1 read last while they might still sit in the memory-side
+    // cache, was measured: 5 % slower.  REV stays as a switch.)
+    constexpr bool REV = false;
+    const int32_t bx = REV ? (int32_t)(gridDim.x - 1 - blockIdx.x) : (int32_t)blockIdx.x;
+    const int32_t b = REV ? (int32_t)(gridDim.z - 1 - blockIdx.z) : (int32_t)blockIdx.z;
+    const int32_t head = REV ? (int32_t)(gridDim.y - 1 - blockIdx.y) : (int32_t)blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
     const int64_t hs = (int64_t)H * d;  // stride between tokens
@@ -218,7 +224,7 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
     }
     __syncthreads();
 
-    const int32_t q_begin = blockIdx.x * qpw;
+    const int32_t q_begin = bx * qpw;
     const int32_t q_end = min(q_begin + qpw, N);
     const float *qbase = q + ((int64_t)b * N * H + head) * d;
 
@@ -248,8 +254,12 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
 
     float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
 
-    QRaw cur = load_q(q_begin + 32 * wave);
-    for (int32_t q0 = q_begin + 32 * wave; q0 < q_end; q0 += 32 * kXWaves) {
+    const int32_t q_first = q_begin + 32 * wave;
+    const int32_t n_it = q_first < q_end ? (q_end - q_first + 32 * kXWaves - 1) / (32 * kXWaves) : 0;
+    auto q_of = [&](int32_t it) { return q_first + (REV ? n_it - 1 - it : it) * (32 * kXWaves); };
+    QRaw cur = load_q(n_it > 0 ? q_of(0) : q_first);
+    for (int32_t it = 0; it < n_it; ++it) {
+        const int32_t q0 = q_of(it);
         const int32_t qi = q0 + n;
         const bool valid = qi < N;
         // The K and V^T fragments of a lane do not depend on the query block; an opaque
@@ -316,7 +326,7 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
         // issued earlier the two overlap, registers spill, and every reload of a spilled
         // value waits for ALL outstanding vector memory, i.e. for this very prefetch.
         {
-            int32_t qn = q0 + 32 * kXWaves < q_end ? q0 + 32 * kXWaves : q0;
+            int32_t qn = it + 1 < n_it ? q_of(it + 1) : q0;
             asm volatile("" : "+v"(qn) : "v"(sm[NKB - 1][15]));  // not before the last MFMA
             cur = load_q(qn);
         }
@@ -517,7 +527,10 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     return hipGetLastError();
 }
 
-bool mfma_shape(int32_t d, int32_t nk) { return (d % 8) == 0 && d <= 96 && nk + 2 <= 128; }
+// Head dims above 96 keep K and V^T of at most 94 keys in LDS (the 96-key tile: 134 KB).
+bool mfma_shape(int32_t d, int32_t nk) {
+    return (d % 8) == 0 && ((d <= 96 && nk + 2 <= 128) || (d <= 160 && nk + 2 <= 96));
+}
 
 // ======================================================================================
 // Self-attention: every key quantized, given scale, keys streamed in tiles of 32
@@ -1146,7 +1159,7 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
                         const float *scale_in, hipStream_t st) {
     if (mfma_shape(d, nk)) {
         float *lse2 = static_cast<float *>(workspace);
-        const int ks = d <= 48 ? 3 : (d <= 64 ? 4 : 6);
+        const int ks = d <= 48 ? 3 : (d <= 64 ? 4 : (d <= 96 ? 6 : 10));
         const int nkb = nk + 2 <= 96 ? 3 : 4;
 #define DGQ_XATTN_CASE(NKB, KS)                                                              \
     if (nkb == NKB && ks == KS)                                                              \
@@ -1155,6 +1168,7 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
         DGQ_XATTN_CASE(3, 3)
         DGQ_XATTN_CASE(3, 4)
         DGQ_XATTN_CASE(3, 6)
+        DGQ_XATTN_CASE(3, 10)
         DGQ_XATTN_CASE(4, 3)
         DGQ_XATTN_CASE(4, 4)
         DGQ_XATTN_CASE(4, 6)

@@ -37,10 +37,12 @@ def _both(dgq, c, bits):
     out = torch.full((B, N, H, d), float("nan"), device="cuda")
     s = torch.full((B,), float("nan"), device="cuda")
     codes = torch.full((B, H, N, nk - 1), 0xEE, dtype=torch.uint8, device="cuda")
+    import gc
+    gc.collect()   # tensors of earlier tests must not be released in the middle of the check
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
     dgq.dgq_xattn_logq_noalloc(q, k, v, kb, bits, out, s, codes_dump=codes)
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before   # nothing was allocated through torch either
     codes_ref = torch.full_like(codes, 0xEE)
     out_ref, s_ref = dgq.dgq_xattn_logq(q, k, v, kb, bits, codes_dump=codes_ref)
     torch.cuda.synchronize()
