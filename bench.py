@@ -623,8 +623,19 @@ def main():
             us_s = time_calls(L.dgq_xattn_logq_static, (ptr(a_["q"]), ptr(a_["k"]), ptr(a_["v"]), ptr(a_["kb"]),
                                                         a_["B"], a_["N"], a_["H"], a_["d"], a_["nk"], 8,
                                                         ptr(a_["s"]), ptr(a_["out"]), ptr(s_own), None, sp))
+            # the same product on V^'s integer codes by shifts and adds (4-bit probability codes;
+            # fp32 vector kernels, one thread per query and head)
+            vcodes = torch.empty(a_["v"].shape, dtype=torch.uint8, device=dev)
+            vparams = torch.empty((a_["B"], a_["H"], 2), dtype=torch.float32, device=dev)
+            L.dgq_quantize_value(ptr(a_["v"]), a_["B"], a_["nk"], a_["H"], a_["d"], 8, ptr(vhat), ptr(vcodes),
+                                 ptr(vparams), sp)
+            us_i = time_calls(L.dgq_xattn_logq_intv, (ptr(a_["q"]), ptr(a_["k"]), ptr(vcodes), ptr(vparams),
+                                                      ptr(a_["kb"]), a_["B"], a_["N"], a_["H"], a_["d"],
+                                                      a_["nk"], 4, ptr(a_["out"]), ptr(a_["s"]), None, None, sp),
+                              n_rep=3)
             nominal = 2.0 * a_["B"] * a_["N"] * a_["H"] * a_["d"] * 4
             value_quant.append(dict(attention=a_["name"], v_bits=8, attn_bits=8,
+                                    us_attention_integer_shift_add_b4=round(us_i, 2),
                                     us_quantize_value=round(us_v, 2), us_attention_on_v_hat=round(us_a, 2),
                                     us_attention_given_scale=round(us_s, 2),
                                     gbs_attention_given_scale=round(nominal / us_s / 1e3, 1)))

@@ -25,9 +25,10 @@
  *   dgq_groups_for_conv3x3, dgq_conv3x3_codes
  *                          3 x 3 convolutions through the same quantizer and
  *                          contraction
- *   dgq_quantize_value, dgq_xattn_logq_static, dgq_selfattn_logq
+ *   dgq_quantize_value, dgq_xattn_logq_static, dgq_selfattn_logq, dgq_xattn_logq_intv
  *                          the quantized value tensor, the attention with a given
- *                          scale, and self-attention over N keys
+ *                          scale, self-attention over N keys, and the attention
+ *                          product on V^'s integer codes by shifts and adds
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer unless the comment says "host".
@@ -450,6 +451,29 @@ int dgq_selfattn_logq(const float *q, const float *k, const float *v, int32_t B,
 int dgq_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
                        int32_t v_bits, float *v_hat, uint8_t *codes, float *params,
                        void *stream);
+
+/*
+ * The attention product on V^'s INTEGER codes, by shifts and adds (Section 3.1: the log
+ * quantizer "allows bit-shifting operations"; Section 3.3: A^ V^ with the <start> column
+ * multiplied in full precision).  With 4-bit probability codes every quantized weight is
+ * s_b 2^-15 (1 << (15 - A^q)) and V^ = s_v q_v + z_v, so
+ *   out[b,i,h,:] = A[..,0] * v_hat[b,0,h,:]
+ *                + s_b 2^-15 * ( s_v * sum_{j>=1} (q_v[b,j,h,:] << (15 - A^q[b,h,i,j]))
+ *                              + z_v * sum_{j>=1} (1 << (15 - A^q[b,h,i,j])) ),
+ * both sums exact in int32; v_hat[0] = s_v q_v[0] + z_v rounded to fp32 as dgq_quantize_value
+ * writes it.  Logits, soft-max, scale and codes as in dgq_xattn_logq (its fp32 vector
+ * kernels; no workspace).
+ *   v_codes:  uint8 [B, nk, H, d], the 8-bit codes of dgq_quantize_value
+ *   v_params: fp32 [B, H, 2], its (s_v, z_v)
+ *   attn_bits: 4 (with 8-bit codes 1 << (255 - A^q) has no integer accumulator:
+ *              DGQ_EUNSUPPORTED)
+ *   acc_dump: NULL, or int32 [B, N, H, d] receiving the first integer sum (debug / parity)
+ * Enqueues on `stream`; neither synchronises nor allocates.
+ */
+int dgq_xattn_logq_intv(const float *q, const float *k, const uint8_t *v_codes,
+                        const float *v_params, const float *key_bias, int32_t B, int32_t N,
+                        int32_t H, int32_t d, int32_t nk, int32_t attn_bits, float *out,
+                        float *scale_out, uint8_t *codes_dump, int32_t *acc_dump, void *stream);
 
 #ifdef __cplusplus
 }

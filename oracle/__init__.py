@@ -327,3 +327,33 @@ def xattn(Q, K, V, key_bias, bits: int, want_ahat: bool = False, s_in=None):
     r = xattn_logq(A, V, bits, want_ahat, s_in=s_in)
     r["A"] = A
     return r
+
+
+def xattn_intv(Q, K, V, key_bias):
+    """The attention product of Section 3.3 on the INTEGER codes of V^, by shifts and adds
+    (Section 3.1: the log quantizer "allows bit-shifting operations").  V^ = s_v q_v + z_v
+    with 8-bit q_v (quantize_value); 4-bit probability codes A^q, so a quantized weight is
+    s_b 2^-15 (1 << (15 - A^q)):
+        acc[b,i,h,:] = sum_{j>=1} q_v[b,j,h,:] << (15 - A^q[b,h,i,j])        (integer)
+        zsum[b,i,h]  = sum_{j>=1} 1 << (15 - A^q[b,h,i,j])                    (integer)
+        out = A[..,0] * vhat[b,0,h,:] + s_b 2^-15 (s_v acc + z_v zsum)        (double, one rounding)
+    Returns dict(out fp32 [B,N,H,d], acc int64 [B,N,H,d], zsum int64 [B,N,H], codes, s, margin)."""
+    qv = quantize_value(V, 8)
+    r = xattn(Q, K, qv["vhat"], key_bias, 4)
+    codes = r["codes"].astype(np.int64)                       # [B,H,N,nk-1]
+    shift = 15 - np.transpose(codes, (0, 2, 1, 3))            # [B,N,H,nk-1]
+    vq = qv["codes"].astype(np.int64)[:, 1:]                  # [B,nk-1,H,d]
+    B, N, H, _ = shift.shape
+    d = vq.shape[-1]
+    acc = np.zeros((B, N, H, d), np.int64)
+    for j in range(shift.shape[-1]):                          # key by key: a shift and an add
+        acc += vq[:, j][:, None, :, :] << shift[..., j][..., None]
+    zsum = (np.int64(1) << shift).sum(-1)
+    s_v = qv["params"][..., 0].astype(np.float64)[:, None, :, None]
+    z_v = qv["params"][..., 1].astype(np.float64)[:, None, :, None]
+    a0 = np.transpose(r["A"][..., 0], (0, 2, 1)).astype(np.float64)[..., None]   # [B,N,H,1]
+    v0 = qv["vhat"][:, 0].astype(np.float64)[:, None]                              # [B,1,H,d]
+    s_b = r["s"].astype(np.float64)[:, None, None, None]
+    out = a0 * v0 + s_b * 2.0 ** -15 * (s_v * acc + z_v * zsum[..., None])
+    return dict(out=out.astype(np.float32), acc=acc, zsum=zsum, codes=r["codes"], s=r["s"],
+                margin=r["margin"], vq=qv)

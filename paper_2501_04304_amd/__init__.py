@@ -79,6 +79,7 @@ def lib():
         L.dgq_xattn_logq_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp,
                                             vp, vp]
         L.dgq_xattn_workspace_bytes.restype = sz
+        L.dgq_xattn_logq_intv.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
         L.dgq_selfattn_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.dgq_selfattn_workspace_bytes.restype = sz
         L.dgq_selfattn_logq.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -388,6 +389,38 @@ def dgq_xattn_logq(q, k, v, key_bias, attn_bits: int, out=None, scale_out=None, 
     _check(lib().dgq_xattn_logq(_ptr(q), _ptr(k), _ptr(v), _ptr(key_bias), B, N, H, d, nk,
                                 attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
                                 _ptr(workspace), wbytes, _stream(stream)))
+    return out, scale_out
+
+
+def dgq_xattn_logq_intv(q, k, v_codes, v_params, key_bias, attn_bits: int = 4, out=None, scale_out=None,
+                        codes_dump=None, acc_dump=None, stream=None):
+    """Attention product on the integer codes of V^ (u8 [B,nk,H,d]) and their (s, z) [B,H,2]."""
+    import torch
+    _dev(q, torch.float32, "q")
+    _dev(k, torch.float32, "k")
+    _dev(v_codes, torch.uint8, "v_codes")
+    _dev(v_params, torch.float32, "v_params")
+    B, N, H, d = q.shape
+    nk = k.shape[1]
+    if tuple(k.shape) != (B, nk, H, d) or tuple(v_codes.shape) != (B, nk, H, d):
+        raise ValueError("k / v_codes have the wrong shape")
+    if v_params.numel() != B * H * 2:
+        raise ValueError("v_params must be [B, H, 2]")
+    if out is None:
+        out = torch.empty_like(q)
+    if scale_out is None:
+        scale_out = torch.empty(B, dtype=torch.float32, device=q.device)
+    if acc_dump is not None:
+        _dev(acc_dump, torch.int32, "acc_dump")
+        if tuple(acc_dump.shape) != (B, N, H, d):
+            raise ValueError("acc_dump has the wrong shape")
+    if codes_dump is not None:
+        _dev(codes_dump, torch.uint8, "codes_dump")
+        if tuple(codes_dump.shape) != (B, H, N, nk - 1):
+            raise ValueError("codes_dump has the wrong shape")
+    _check(lib().dgq_xattn_logq_intv(_ptr(q), _ptr(k), _ptr(v_codes), _ptr(v_params), _ptr(key_bias), B, N,
+                                     H, d, nk, attn_bits, _ptr(out), _ptr(scale_out), _ptr(codes_dump),
+                                     _ptr(acc_dump), _stream(stream)))
     return out, scale_out
 
 

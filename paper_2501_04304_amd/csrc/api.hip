@@ -1027,6 +1027,27 @@ int dgq_xattn_logq_static(const float *q, const float *k, const float *v, const 
     return DGQ_OK;
 }
 
+int dgq_xattn_logq_intv(const float *q, const float *k, const uint8_t *v_codes, const float *v_params,
+                        const float *key_bias, int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk,
+                        int32_t attn_bits, float *out, float *scale_out, uint8_t *codes_dump,
+                        int32_t *acc_dump, void *stream) {
+    if (!q || !k || !v_codes || !v_params || !out || !scale_out)
+        return fail(DGQ_EINVAL, "dgq_xattn_logq_intv: null pointer");
+    if (B < 1 || N < 1 || H < 1) return fail(DGQ_EINVAL, "dgq_xattn_logq_intv: empty tensor");
+    if (attn_bits != 4)
+        return fail(DGQ_EUNSUPPORTED,
+                    "dgq_xattn_logq_intv: the integer product needs 4-bit codes (q_v << (15 - code) "
+                    "must fit the int32 accumulator)");
+    if (nk < 2 || nk > 128 || d < 1 || d > 256)
+        return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_intv: needs 2 <= nk <= 128 and 1 <= d <= 256");
+    if (B > 65535 || H > 65535) return fail(DGQ_EUNSUPPORTED, "dgq_xattn_logq_intv: B or H above 65535");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(out) || (key_bias && !aligned16(key_bias)))
+        return fail(DGQ_EALIGN, "dgq_xattn_logq_intv: tensor not 16-byte aligned");
+    DGQ_HIP(launch_xattn_intv(q, k, v_codes, v_params, key_bias, B, N, H, d, nk, out, scale_out, codes_dump,
+                              acc_dump, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
 size_t dgq_selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d) {
     if (B < 1 || N < 1 || H < 1) return 0;
     return selfattn_workspace_bytes(B, N, H, d);

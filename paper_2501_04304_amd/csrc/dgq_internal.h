@@ -167,6 +167,12 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
                         float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
                         const float *scale_in, hipStream_t st);
 
+// The attention on V^'s integer codes with 4-bit probability codes (shift-and-add product).
+hipError_t launch_xattn_intv(const float *q, const float *k, const uint8_t *vq, const float *vparams,
+                             const float *key_bias, int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk,
+                             float *out, float *scale_out, uint8_t *codes_dump, int32_t *acc_dump,
+                             hipStream_t st);
+
 hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
                                  int32_t bits, float *vhat, uint8_t *codes, float *params,
                                  hipStream_t st);

@@ -1059,6 +1059,109 @@ __global__ __launch_bounds__(256) void k_xattn(
     }
 }
 
+// Pass 2 of the attention on the integer codes of V^: the product of Section 3.3 as the shifts
+// and adds Section 3.1 promises for the log quantizer.  With 4-bit codes A^q in 0..15 every
+// quantized weight is s_b 2^-A^q = s_b 2^-15 (1 << (15 - A^q)), and V^ = s_v q_v + z_v with
+// 8-bit q_v, so
+//   sum_{j>=1} A^_ij V^_j = s_b 2^-15 ( s_v sum_j (q_v[j] << (15 - A^q_ij)) + z_v sum_j (1 << (15 - A^q_ij)) ),
+// both sums exact in int32 (at most 127 keys x 255 x 2^15 < 2^31).  One thread per (query,
+// head) as in k_xattn; V^'s codes wait in LDS as one dword per element, so the inner loop is
+// one shift-and-add instruction per (key, dimension).  The <start> column stays in floating
+// point: A_i0 times the reconstruction s_v q_v[0] + z_v.  The few floating-point operations
+// that combine the integer sums run in double and round once.
+template <int NKP>
+__global__ __launch_bounds__(256) void k_xattn_intv(
+    const float *__restrict__ q, const float *__restrict__ k, const uint8_t *__restrict__ vq,
+    const float *__restrict__ vparams, const float *__restrict__ key_bias, int32_t N, int32_t H,
+    int32_t d, int32_t dpad, int32_t nk, float inv_sqrt_d, float *__restrict__ out,
+    const float *__restrict__ scale, uint8_t *__restrict__ codes_dump, int32_t *__restrict__ acc_dump) {
+    extern __shared__ float kv[];  // [NKP][dpad]: K as floats, then V^'s codes as integers
+    const int32_t b = blockIdx.z, h = blockIdx.y;
+    const int32_t n_raw = blockIdx.x * 256 + threadIdx.x;
+    const bool valid = n_raw < N;
+    const int32_t n = valid ? n_raw : N - 1;
+    const int64_t hs = (int64_t)H * d;
+
+    stage_head<NKP>(k + ((int64_t)b * nk * H + h) * d, nk, d, dpad, hs, kv);
+    __syncthreads();
+    float L[NKP];
+#pragma unroll
+    for (int j = 0; j < NKP; ++j) L[j] = 0.0f;
+    const float *qr = q + (((int64_t)b * N + n) * H + h) * d;
+    for (int32_t t = 0; t < d; ++t) {
+        const float qv = qr[t];
+#pragma unroll
+        for (int j = 0; j < NKP; ++j) L[j] = fmaf(qv, kv[j * dpad + t], L[j]);
+    }
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NKP; ++j) {
+        if (j < nk) {
+            L[j] = fmaf(L[j], inv_sqrt_d, key_bias ? key_bias[j] : 0.0f);
+            m = fmaxf(m, L[j]);
+        } else {
+            L[j] = -INFINITY;
+        }
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NKP; ++j) {
+        L[j] = (L[j] - m) * kLog2e;
+        sum += __builtin_amdgcn_exp2f(L[j]);
+    }
+    const float s = scale[b];
+    const float l2s = __log2f(s), lse2 = __log2f(sum);
+    const float a0 = __builtin_amdgcn_exp2f(L[0]) / sum;
+    uint8_t *cd = codes_dump
+                      ? codes_dump + ((((int64_t)b * H + h) * N + n) * (int64_t)(nk - 1))
+                      : nullptr;
+    // the shift of every key, four bits each: 15 - A^q (the <start> column and padding keys take none)
+    uint32_t sh[NKP / 8];
+#pragma unroll
+    for (int w = 0; w < NKP / 8; ++w) sh[w] = 0;
+    int32_t zsum = 0;
+#pragma unroll
+    for (int j = 1; j < NKP; ++j) {
+        if (j < nk) {
+            const float l2a = L[j] - lse2;
+            float c = fminf(fmaxf(rintf(l2s - l2a), 0.0f), 15.0f);
+            if (l2a < -150.0f) c = 15.0f;
+            if (cd && valid) cd[j - 1] = (uint8_t)c;
+            const uint32_t shift = 15u - (uint32_t)c;
+            sh[j >> 3] |= shift << (4 * (j & 7));
+            zsum += 1 << shift;
+        }
+    }
+
+    // ---- V^'s codes replace K in LDS, one dword per element -------------------------------
+    __syncthreads();
+    int32_t *vi = reinterpret_cast<int32_t *>(kv);
+    {
+        const uint8_t *src = vq + ((int64_t)b * nk * H + h) * d;
+        for (int32_t idx = threadIdx.x; idx < NKP * dpad; idx += 256) {
+            const int32_t j = idx / dpad, t = idx - j * dpad;
+            vi[idx] = (j < nk && t < d) ? (int32_t)src[(int64_t)j * hs + t] : 0;
+        }
+    }
+    __syncthreads();
+    const double sv = (double)vparams[((int64_t)b * H + h) * 2 + 0], zv = (double)vparams[((int64_t)b * H + h) * 2 + 1];
+    const double tail = zv * (double)zsum;
+    const double ws = (double)s * (1.0 / 32768.0);
+    float *orow = out + (((int64_t)b * N + n) * H + h) * d;
+    int32_t *arow = acc_dump ? acc_dump + (((int64_t)b * N + n) * H + h) * d : nullptr;
+    for (int32_t t = 0; t < d; ++t) {
+        int32_t acc = 0;
+#pragma unroll
+        for (int j = 1; j < NKP; ++j)
+            acc += vi[j * dpad + t] << ((sh[j >> 3] >> (4 * (j & 7))) & 15u);  // padding keys hold code 0
+        if (valid) {
+            const float v0 = fmaf((float)sv, (float)vi[t], (float)zv);  // the fp32 reconstruction of V^_0
+            orow[t] = (float)((double)a0 * (double)v0 + ws * (sv * (double)acc + tail));
+            if (arow) arow[t] = acc;
+        }
+    }
+}
+
 // V^ of the product A^ V^ (Section 3.3): one workgroup per (prompt, head) finds the range
 // of its [nk, d] slice, quantizes with s = (max - min) / 2^b, z = min (separate subtract
 // and multiply, round to nearest even, clamp) and writes the reconstruction s q + z
@@ -1151,6 +1254,41 @@ hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t 
     hipLaunchKernelGGL(k_quantize_value, dim3(H, B), dim3(256), 0, st, v, nk, H, d, bits, vhat,
                        codes, params);
     return hipGetLastError();
+}
+
+template <int NKP>
+hipError_t launch_intv_nkp(const float *q, const float *k, const uint8_t *vq, const float *vparams,
+                           const float *key_bias, int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk,
+                           float *out, float *scale_out, uint8_t *codes_dump, int32_t *acc_dump,
+                           hipStream_t st) {
+    const int32_t dpad = (d + 3) / 4 * 4;
+    const size_t lds = sizeof(float) * (size_t)NKP * dpad;
+    const float inv_sqrt_d = (float)(1.0 / sqrt((double)d));
+    const dim3 grid((N + 255) / 256, H, B);
+    if (lds > 64 * 1024) {
+        hipError_t e = DGQ_ENSURE_LDS((k_xattn<NKP, 1>), (int)lds);
+        if (e != hipSuccess) return e;
+        e = DGQ_ENSURE_LDS((k_xattn_intv<NKP>), (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
+    hipLaunchKernelGGL((k_xattn<NKP, 1>), grid, dim3(256), lds, st, q, k, static_cast<const float *>(nullptr),
+                       key_bias, N, H, d, dpad, nk, 4, inv_sqrt_d, out, scale_out,
+                       static_cast<uint8_t *>(nullptr), static_cast<const float *>(nullptr));
+    hipLaunchKernelGGL((k_xattn_intv<NKP>), grid, dim3(256), lds, st, q, k, vq, vparams, key_bias, N, H, d,
+                       dpad, nk, inv_sqrt_d, out, scale_out, codes_dump, acc_dump);
+    return hipGetLastError();
+}
+
+hipError_t launch_xattn_intv(const float *q, const float *k, const uint8_t *vq, const float *vparams,
+                             const float *key_bias, int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk,
+                             float *out, float *scale_out, uint8_t *codes_dump, int32_t *acc_dump,
+                             hipStream_t st) {
+    if (nk <= 80)
+        return launch_intv_nkp<80>(q, k, vq, vparams, key_bias, B, N, H, d, nk, out, scale_out, codes_dump,
+                                   acc_dump, st);
+    return launch_intv_nkp<128>(q, k, vq, vparams, key_bias, B, N, H, d, nk, out, scale_out, codes_dump,
+                                acc_dump, st);
 }
 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,

@@ -52,6 +52,7 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_xattn_logq_static(None, None, None, None, 1, 1, 1, 8, 77, 8, None, None, None, None, None) == -1
     assert lib.dgq_xattn_logq_noalloc(None, None, None, None, 1, 1, 1, 8, 77, 8, None, None, None, None) == -1
     assert lib.dgq_quantize_value(None, 1, 77, 1, 8, 8, None, None, None, None) == -1
+    assert lib.dgq_xattn_logq_intv(None, None, None, None, None, 1, 1, 1, 8, 77, 4, None, None, None, None, None) == -1
     assert lib.dgq_selfattn_logq(None, None, None, 1, 8, 1, 8, 8, None, None, None, None, None, 0, None) == -1
     assert lib.dgq_groups_for_conv3x3(None, None) == -1
     assert lib.dgq_conv3x3_codes(None, None, 1, 4, 4, None, None) == -1

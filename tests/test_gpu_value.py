@@ -126,3 +126,46 @@ def test_argument_errors(dgq):
     with pytest.raises(dgq.DgqError) as e:
         dgq._check(dgq.lib().dgq_quantize_value(vm.data_ptr(), 1, 4, 1, 8, 8, v.data_ptr(), None, None, None))
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("B,N,H,d,nk", [(2, 300, 3, 40, 77), (1, 70, 2, 37, 77), (1, 40, 2, 64, 100),
+                                        (3, 1, 1, 16, 2), (1, 33, 1, 160, 77)])
+def test_integer_shift_and_add_product(dgq, oracle, B, N, H, d, nk):
+    """dgq_xattn_logq_intv: the product on V^'s integer codes.  The int32 sums of shifted value
+    codes must equal the oracle's integers wherever the row's attention codes are decided
+    (margin >= 2^-13; a marginal code may differ by one step, which changes the row's sums),
+    attention codes as in test_gpu_xattn, the result within 1e-4 * max|ref|."""
+    import torch
+    from oracle.guard import DELTA, guarded_attention_case
+    c, _ = guarded_attention_case(900 + d + nk, B, N, H, d, nk=nk, bits_list=(4,))
+    ref = oracle.xattn_intv(c["Q"], c["K"], c["V"], c["key_bias"])
+    vhat, vcodes, vparams = dgq.dgq_quantize_value(_dev(c["V"]), 8, want_codes=True, want_params=True)
+    assert np.array_equal(vcodes.cpu().numpy(), ref["vq"]["codes"])
+    codes = torch.full((B, H, N, nk - 1), 0xEE, dtype=torch.uint8, device="cuda")
+    acc = torch.full((B, N, H, d), -7, dtype=torch.int32, device="cuda")
+    out, s = dgq.dgq_xattn_logq_intv(_dev(c["Q"]), _dev(c["K"]), vcodes, vparams, _dev(c["key_bias"]), 4,
+                                     codes_dump=codes, acc_dump=acc)
+    torch.cuda.synchronize()
+    got_codes = codes.cpu().numpy()
+    safe = ref["margin"] >= DELTA
+    assert safe.all(), "guarded inputs must have no marginal element"
+    assert np.array_equal(got_codes, ref["codes"])
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), ref["acc"])
+    from support import scale_rtol
+    assert np.all(np.abs(s.cpu().numpy() - ref["s"]) <= scale_rtol(c) * ref["s"])
+    assert_close_fp32(out.cpu().numpy(), ref["out"], "out")
+    # and it is the same product as the matrix-core / fp32 kernels compute on the reconstruction
+    out_f, _ = dgq.dgq_xattn_logq(_dev(c["Q"]), _dev(c["K"]), vhat, _dev(c["key_bias"]), 4)
+    torch.cuda.synchronize()
+    assert_close_fp32(out.cpu().numpy(), out_f.cpu().numpy(), "integer vs floating-point product")
+
+
+def test_integer_product_rejects_8_bit_codes(dgq):
+    import torch
+    q = torch.zeros((1, 8, 1, 8), device="cuda")
+    kk = torch.zeros((1, 4, 1, 8), device="cuda")
+    vc = torch.zeros((1, 4, 1, 8), dtype=torch.uint8, device="cuda")
+    vp = torch.ones((1, 1, 2), device="cuda")
+    with pytest.raises(dgq.DgqError) as e:
+        dgq.dgq_xattn_logq_intv(q, kk, vc, vp, None, 8)
+    assert e.value.code == -4

@@ -108,3 +108,29 @@ def test_product_is_a_shift_and_add_of_integers(oracle):
                     want = a0 * float(vq["vhat"][b, 0, h, t]) + s * (sv * acc + zv * ones) / 32768.0
                     got = float(r["out"][b, i, h, t])
                     assert abs(got - want) <= 2e-6 * max(1.0, abs(want)), (b, h, i, t)
+
+
+def test_integer_product_oracle(oracle):
+    """oracle.xattn_intv (the shift-and-add product on V^'s codes) against three things it does
+    not compute itself: python big integers on sampled outputs, the floating-point product of
+    oracle.xattn on the reconstruction V^ (equal up to the fp32 rounding of V^), and the bound
+    that keeps the sums inside an int32 accumulator."""
+    import dgq_inputs as di
+    c = di.attention_case(4243, 2, 48, 3, 16, nk=20, d_ctx=48)
+    r = oracle.xattn_intv(c["Q"], c["K"], c["V"], c["key_bias"])
+    vq = r["vq"]
+    B, N, H, d = c["Q"].shape
+    for (b, i, h, t) in [(0, 0, 0, 0), (1, 47, 2, 15), (0, 13, 1, 7), (1, 5, 0, 3)]:
+        qa = [int(x) for x in r["codes"][b, h, i]]
+        acc = sum(int(vq["codes"][b, j + 1, h, t]) << (15 - qa[j]) for j in range(len(qa)))
+        ones = sum(1 << (15 - q) for q in qa)
+        assert int(r["acc"][b, i, h, t]) == acc and int(r["zsum"][b, i, h]) == ones
+    assert r["acc"].min() >= 0 and r["acc"].max() < 2 ** 31 and r["zsum"].max() < 2 ** 31
+    ref = oracle.xattn(c["Q"], c["K"], vq["vhat"], c["key_bias"], 4)
+    assert np.array_equal(ref["codes"], r["codes"])
+    assert np.abs(r["out"] - ref["out"]).max() <= 1e-6 * np.abs(ref["out"]).max()
+    # all codes 15 (weights 1): acc is the plain sum of the value codes
+    vsum = vq["codes"][:, 1:].astype(np.int64).sum(1)              # [B,H,d]
+    low = r["codes"].min(axis=-1) == 15                            # [B,H,N]
+    for b, h, i in np.argwhere(low)[:4]:
+        assert np.array_equal(r["acc"][b, i, h], vsum[b, h])
