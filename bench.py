@@ -687,8 +687,21 @@ def main():
             us_u = time_calls(L.dgq_conv3x3_codes, (C.c_void_p(g9.handle), ptr(c1), B_, H_, W_, ptr(c9), sp))
             us_l = time_calls(L.dgq_linear, (C.c_void_p(g9.handle), C.c_void_p(wt9.handle), ptr(c9), ptr(cl1),
                                              C.c_int64(M_), ptr(y9), None, None, C.c_size_t(0), sp))
+            # the same convolution with the nine taps gathered by the contraction's loads: the
+            # quantizer writes three shifted copies of the codes, nothing is unfolded
+            L.dgq_conv3x3_codes3_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+            L.dgq_conv3x3_codes3_bytes.restype = C.c_size_t
+            c3 = torch.empty(int(L.dgq_conv3x3_codes3_bytes(C.c_void_p(g9.handle), B_, H_, W_)),
+                             dtype=torch.int8, device=dev)
+            us_q3 = time_calls(L.dgq_quantize_act_conv3x3, (C.c_void_p(g1.handle), C.c_void_p(g9.handle), ptr(xs),
+                                                            B_, H_, W_, ptr(c3), ptr(cl1), sp))
+            us_l3 = time_calls(L.dgq_linear_conv3x3, (C.c_void_p(g9.handle), C.c_void_p(wt9.handle), ptr(c3),
+                                                      ptr(cl1), B_, H_, W_, ptr(y9), sp))
             ops = 2.0 * M_ * 9 * C_ * C_
             conv.append(dict(B=B_, H=H_, W=W_, C=C_, O=C_, k_padded=g9.info.k_padded,
+                             us_quantize_three_copies=round(us_q3, 2), us_linear_gathering=round(us_l3, 2),
+                             tops_linear_gathering=round(ops / us_l3 / 1e6, 1),
+                             tops_whole_gathering=round(ops / (us_q3 + us_l3) / 1e6, 1),
                              us_quantize=round(us_q, 2), us_unfold_codes=round(us_u, 2),
                              gbs_unfold=round((c1.numel() + c9.numel()) / us_u / 1e3, 1),
                              us_linear=round(us_l, 2), tops_linear=round(ops / us_l / 1e6, 1),
@@ -696,7 +709,7 @@ def main():
             wt9.free()
             g9.free()
             g1.free()
-            del xs, w9, c1, cl1, c9, y9
+            del xs, w9, c1, cl1, c9, y9, c3
 
     # ---------------- CPU baseline: the oracle on a bounded sample --------------------------
     cpu = None

@@ -190,6 +190,32 @@ int dgq_groups_for_conv3x3(const dgq_groups_t *g, dgq_groups_t **out);
 int dgq_conv3x3_codes(const dgq_groups_t *g9, const int8_t *codes, int32_t B, int32_t H,
                       int32_t W, int8_t *codes9, void *stream);
 
+/*
+ * The same convolution without the unfolded code buffer: the contraction's loads gather the
+ * nine taps themselves.  A tap (dy, dx) of a block of 16 consecutive output pixels (32 with
+ * 4-bit codes) is the code block dy image rows further -- one contiguous 1 KiB piece per chunk,
+ * as for a linear layer -- of the map shifted by dx pixels, or a block of the code of 0 outside
+ * the image; so the quantizer writes the map's codes three times (the map, and the map shifted
+ * one pixel to either side inside its image rows, the code of 0 at the image's edge), and
+ * nothing is unfolded.  Needs W % 16 == 0 (8-bit codes) or W % 32 == 0 (4-bit codes), channels a
+ * multiple of 4, one pixel class (DGQ_EUNSUPPORTED otherwise: use the calls above).
+ *
+ * dgq_quantize_act_conv3x3 (hot call): x fp32 [B*H*W, C] -> codes3, dgq_conv3x3_codes3_bytes(g9,
+ *   B, H, W) bytes (three copies of dgq_codes_bytes(g, B*H*W)), and row_class u8 [B*H*W] (zeros).
+ *   g: the map's handle, g9 = dgq_groups_for_conv3x3(g).
+ * dgq_linear_conv3x3 (hot call): y fp32 [B*H*W, O] = the convolution; w = dgq_pack_weight(g9,
+ *   [O, 9 C] tap-major kernel).  Same arithmetic as dgq_linear on the unfolded codes: the two
+ *   results are equal bit for bit.
+ * Both enqueue on `stream` and neither synchronise nor allocate.
+ */
+size_t dgq_conv3x3_codes3_bytes(const dgq_groups_t *g9, int32_t B, int32_t H, int32_t W);
+int dgq_quantize_act_conv3x3(const dgq_groups_t *g, const dgq_groups_t *g9, const float *x,
+                             int32_t B, int32_t H, int32_t W, int8_t *codes3,
+                             uint8_t *row_class, void *stream);
+int dgq_linear_conv3x3(const dgq_groups_t *g9, const dgq_weight_t *w, const int8_t *codes3,
+                       const uint8_t *row_class, int32_t B, int32_t H, int32_t W, float *y,
+                       void *stream);
+
 /* Host copy of the n_pixel_classes - 1 ascending row-range thresholds (taus: host). */
 int dgq_groups_thresholds(const dgq_groups_t *g, float *taus);
 

@@ -66,6 +66,10 @@ def lib():
         L.dgq_linear_geglu_requant.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp]
         L.dgq_groups_for_conv3x3.argtypes = [vp, C.POINTER(vp)]
         L.dgq_conv3x3_codes.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        L.dgq_conv3x3_codes3_bytes.argtypes = [vp, i32, i32, i32]
+        L.dgq_conv3x3_codes3_bytes.restype = sz
+        L.dgq_quantize_act_conv3x3.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.dgq_linear_conv3x3.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
         L.dgq_codes_bytes.argtypes = [vp, i64]
         L.dgq_codes_bytes.restype = sz
         L.dgq_linear_workspace_bytes.argtypes = [vp, vp, i64]
@@ -225,6 +229,46 @@ def dgq_conv3x3_codes(groups9: Groups, codes, B: int, H: int, W: int, codes9=Non
         raise ValueError("codes9 has the wrong shape")
     _check(lib().dgq_conv3x3_codes(groups9.handle, _ptr(codes), B, H, W, _ptr(codes9), _stream(stream)))
     return codes9
+
+
+def dgq_quantize_act_conv3x3(groups: Groups, groups9: Groups, x, B: int, H: int, W: int, codes3=None,
+                             row_class=None, stream=None):
+    """x fp32 [B*H*W, C] -> (codes3, row_class): the three shifted copies of the map's codes that
+    dgq_linear_conv3x3 gathers its nine taps from."""
+    import torch
+    _dev(x, torch.float32, "x")
+    rows = B * H * W
+    if tuple(x.shape) != (rows, groups.info.channels):
+        raise ValueError("x must be [B*H*W, C]")
+    nbytes = int(lib().dgq_conv3x3_codes3_bytes(groups9.handle, B, H, W))
+    if codes3 is None:
+        codes3 = torch.empty(nbytes, dtype=torch.int8, device=x.device)
+    if row_class is None:
+        row_class = torch.empty(rows, dtype=torch.uint8, device=x.device)
+    _dev(codes3, torch.int8, "codes3")
+    _dev(row_class, torch.uint8, "row_class")
+    if codes3.numel() != nbytes or row_class.numel() != rows:
+        raise ValueError("codes3 / row_class have the wrong size")
+    _check(lib().dgq_quantize_act_conv3x3(groups.handle, groups9.handle, _ptr(x), B, H, W, _ptr(codes3),
+                                          _ptr(row_class), _stream(stream)))
+    return codes3, row_class
+
+
+def dgq_linear_conv3x3(groups9: Groups, weight: "Weight", codes3, row_class, B: int, H: int, W: int, y=None,
+                       stream=None):
+    """The 3 x 3 convolution with its taps gathered by the contraction's loads: y fp32 [B*H*W, O]."""
+    import torch
+    _dev(codes3, torch.int8, "codes3")
+    _dev(row_class, torch.uint8, "row_class")
+    rows = B * H * W
+    if y is None:
+        y = torch.empty((rows, weight.out_channels), dtype=torch.float32, device=codes3.device)
+    _dev(y, torch.float32, "y")
+    if tuple(y.shape) != (rows, weight.out_channels):
+        raise ValueError("y has the wrong shape")
+    _check(lib().dgq_linear_conv3x3(groups9.handle, weight.handle, _ptr(codes3), _ptr(row_class), B, H, W,
+                                    _ptr(y), _stream(stream)))
+    return y
 
 
 def dgq_pack_weight(groups: Groups, w, bias, w_bits: int, stream=None) -> Weight:

@@ -268,6 +268,7 @@ void release(Groups *g) {
     (void)hipFree(g->d_taus);
     (void)hipFree(g->d_gchunk);
     (void)hipFree(g->d_fill);
+    (void)hipFree(g->d_fill_blocks);
     delete g;
 }
 
@@ -641,7 +642,21 @@ int dgq_groups_for_conv3x3(const dgq_groups_t *h, dgq_groups_t **out) {
         for (int32_t e = 0; e < Kp / 8; ++e)
             for (int b = 0; b < 4; ++b) fill[4 * e + b] = (uint8_t)(q0[8 * e + b] | (q0[8 * e + 4 + b] << 4));
     }
+    // the fill row as code blocks: 16 rows of 64 B (32 rows of 32 B), 16-byte slots permuted by
+    // row bits, and in 4-bit rows 16..31 the 8-byte halves of a slot swapped
+    const int32_t nch = Kp / kGranule;
+    std::vector<uint8_t> fill_blocks((size_t)nch * 1024, 0);
+    for (int32_t c = 0; c < nch; ++c)
+        for (int t = 0; t < (bits == 8 ? 16 : 32); ++t)
+            for (int b = 0; b < (bits == 8 ? 64 : 32); ++b) {
+                const int slot = b >> 4, in_slot = b & 15;
+                const size_t to = bits == 8
+                    ? (size_t)c * 1024 + t * 64 + ((slot ^ swz64(t)) << 4) + in_slot
+                    : (size_t)c * 1024 + t * 32 + ((slot ^ swz32(t)) << 4) + (in_slot ^ (half32(t) << 3));
+                fill_blocks[to] = fill[(size_t)c * (bits == 8 ? 64 : 32) + b];
+            }
     int rc = upload(&g9->d_fill, fill);
+    if (rc == DGQ_OK) rc = upload(&g9->d_fill_blocks, fill_blocks);
     if (rc == DGQ_OK) rc = upload_tables(g9);
     if (rc != DGQ_OK) {
         release(g9);
@@ -663,6 +678,63 @@ int dgq_conv3x3_codes(const dgq_groups_t *h9, const int8_t *codes, int32_t B, in
     if ((int64_t)B * H * W > ((int64_t)1 << 31))
         return fail(DGQ_EUNSUPPORTED, "dgq_conv3x3_codes: too many pixels");
     DGQ_HIP(launch_conv3x3_codes(*g9, codes, B, H, W, codes9, static_cast<hipStream_t>(stream)));
+    return DGQ_OK;
+}
+
+size_t dgq_conv3x3_codes3_bytes(const dgq_groups_t *h9, int32_t B, int32_t H, int32_t W) {
+    if (!h9 || B < 1 || H < 1 || W < 1) return 0;
+    const Groups *g9 = reinterpret_cast<const Groups *>(h9);
+    if (g9->conv_taps != 9) return 0;
+    const int64_t rpb = g9->info.act_bits == 8 ? 16 : 32;
+    const int64_t rows = (int64_t)B * H * W;
+    return (size_t)(3 * ((rows + rpb - 1) / rpb) * (int64_t)(g9->base_kp / kGranule) * 1024);
+}
+
+int dgq_quantize_act_conv3x3(const dgq_groups_t *h, const dgq_groups_t *h9, const float *x, int32_t B,
+                             int32_t H, int32_t W, int8_t *codes3, uint8_t *row_class, void *stream) {
+    if (!h || !h9 || !x || !codes3 || !row_class)
+        return fail(DGQ_EINVAL, "dgq_quantize_act_conv3x3: null pointer");
+    if (B < 1 || H < 1 || W < 1) return fail(DGQ_EINVAL, "dgq_quantize_act_conv3x3: empty shape");
+    const Groups *g = reinterpret_cast<const Groups *>(h);
+    const Groups *g9 = reinterpret_cast<const Groups *>(h9);
+    if (g9->conv_taps != 9 || g9->base_kp != g->info.k_padded || g9->info.act_bits != g->info.act_bits ||
+        g9->info.channels != 9 * g->info.channels || g->info.n_pixel_classes != 1)
+        return fail(DGQ_ESHAPE, "dgq_quantize_act_conv3x3: g9 does not come from dgq_groups_for_conv3x3(g)");
+    if (W % (g->info.act_bits == 8 ? 16 : 32))
+        return fail(DGQ_EUNSUPPORTED,
+                    "dgq_quantize_act_conv3x3: the image width must be a multiple of 16 (8-bit codes) or "
+                    "32 (4-bit codes); use dgq_quantize_act + dgq_conv3x3_codes otherwise");
+    if (g->info.channels % 4 || g->info.channels >= 65535)
+        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act_conv3x3: channels must be a multiple of 4");
+    if (!aligned16(x) || !aligned16(codes3))
+        return fail(DGQ_EALIGN, "dgq_quantize_act_conv3x3: tensor not 16-byte aligned");
+    if ((int64_t)B * H * W > ((int64_t)1 << 31))
+        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act_conv3x3: too many pixels");
+    if (quantize_act_lds_bytes(*g) > 160 * 1024)
+        return fail(DGQ_EUNSUPPORTED, "dgq_quantize_act_conv3x3: too many channels for the LDS row buffers");
+    const int64_t rows = (int64_t)B * H * W;
+    const int64_t copy_bytes = (int64_t)(dgq_conv3x3_codes3_bytes(h9, B, H, W) / 3);
+    DGQ_HIP(launch_quantize_act(*g, x, rows, codes3, row_class, static_cast<hipStream_t>(stream), W, copy_bytes,
+                                reinterpret_cast<const uint32_t *>(g9->d_fill)));
+    return DGQ_OK;
+}
+
+int dgq_linear_conv3x3(const dgq_groups_t *h9, const dgq_weight_t *hw, const int8_t *codes3,
+                       const uint8_t *row_class, int32_t B, int32_t H, int32_t W, float *y, void *stream) {
+    if (!h9 || !hw || !codes3 || !row_class || !y) return fail(DGQ_EINVAL, "dgq_linear_conv3x3: null pointer");
+    if (B < 1 || H < 1 || W < 1) return fail(DGQ_EINVAL, "dgq_linear_conv3x3: empty shape");
+    const Groups *g9 = reinterpret_cast<const Groups *>(h9);
+    const Weight *w = reinterpret_cast<const Weight *>(hw);
+    if (g9->conv_taps != 9) return fail(DGQ_ESHAPE, "dgq_linear_conv3x3: the handle does not come from dgq_groups_for_conv3x3");
+    if (w->groups != g9) return fail(DGQ_ESHAPE, "dgq_linear_conv3x3: weight was packed for a different group handle");
+    if (w->next_kp) return fail(DGQ_ESHAPE, "dgq_linear_conv3x3: weight was packed for dgq_linear_geglu_requant");
+    if (W % (g9->info.act_bits == 8 ? 16 : 32))
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear_conv3x3: the image width must be a multiple of 16 (8-bit codes) or 32 (4-bit codes)");
+    if (!aligned16(codes3) || !aligned16(y)) return fail(DGQ_EALIGN, "dgq_linear_conv3x3: tensor not 16-byte aligned");
+    const int64_t rows = (int64_t)B * H * W;
+    if (rows > ((int64_t)1 << 31) || (rows + 127) / 128 * (int64_t)(w->O_pad / kTileO) > (int64_t)1 << 30)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear_conv3x3: too many output tiles");
+    DGQ_HIP(launch_linear_conv3x3(*g9, *w, codes3, row_class, B, H, W, y, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 

@@ -64,6 +64,9 @@ struct Groups {
     // (8 bit: q - 128 per position; 4 bit: packed nibbles; padding positions 0).
     int32_t conv_taps = 0, base_kp = 0;
     uint8_t *d_fill = nullptr;
+    // the same row as one 1 KiB code block per chunk (every row of the block the fill row, in
+    // the block's slot order): what the tap-gathering contraction loads outside the image
+    uint8_t *d_fill_blocks = nullptr;
     int device = 0;
     // One reference for the caller's handle and one per weight handle packed for it: the
     // tables live until the last of them is released.
@@ -144,8 +147,15 @@ hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int3
 hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t Kp,
                                 const int32_t *perm, int8_t *wq_out, hipStream_t st);
 
+// conv_w > 0: the rows are pixels of images conv_w wide and the codes are written as the three
+// shifted copies of the tap-gathering 3 x 3 convolution (copy_bytes apart; fill32: the code of
+// the value 0, one dword per output dword of a row).
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
-                               uint8_t *row_class, hipStream_t st);
+                               uint8_t *row_class, hipStream_t st, int32_t conv_w = 0,
+                               int64_t copy_bytes = 0, const uint32_t *fill32 = nullptr);
+hipError_t launch_linear_conv3x3(const Groups &g9, const Weight &w, const int8_t *codes3,
+                                 const uint8_t *row_class, int32_t B, int32_t H, int32_t W, float *y,
+                                 hipStream_t st);
 // LDS bytes a workgroup of the quantizer needs for this layer (tables + one row per wave).
 size_t quantize_act_lds_bytes(const Groups &g);
 

@@ -115,7 +115,12 @@ __global__ __launch_bounds__(256) void k_quantize_act(
     const float *__restrict__ x, int64_t rows, int32_t C, int32_t Kp, int32_t n_chunks,
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
     const float *__restrict__ chunk_inv, const float *__restrict__ taus, int32_t n_tau,
-    int8_t *__restrict__ codes, uint8_t *__restrict__ row_class, int32_t rpw_log2) {
+    int8_t *__restrict__ codes, uint8_t *__restrict__ row_class, int32_t rpw_log2,
+    int32_t conv_w, int64_t copy_bytes, const uint32_t *__restrict__ fill32) {
+    // conv_w > 0: the rows are the pixels of images conv_w wide and the codes are written three
+    // times for the tap-gathering 3 x 3 convolution: copy 1 (codes + copy_bytes) is the map
+    // itself, copy 0 holds in row r the codes of the pixel left of r, copy 2 of the pixel right
+    // of r, and the code of the value 0 (fill32, one dword per output dword) where the image ends.
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     constexpr int kPer = BITS == 8 ? 4 : 8;          // positions per output dword
     constexpr int kDwPerChunk = 64 / kPer;           // 16 or 8
@@ -228,13 +233,27 @@ __global__ __launch_bounds__(256) void k_quantize_act(
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
 
-            // this row's place in the tiled layout: scalar base, per-lane 32-bit offset
-            const uint32_t t16 = (uint32_t)r & (BITS == 8 ? 15u : 31u);
-            int8_t *out_row = codes + (((r >> (BITS == 8 ? 4 : 5)) * n_chunks) << 10) +
-                              t16 * (BITS == 8 ? 64u : 32u);
-            const uint32_t out_off =
-                (out_lane + ((slot_lane ^ (uint32_t)(BITS == 8 ? swz64((int)t16) : swz32((int)t16))) << 4)) ^
-                (BITS == 8 ? 0u : (uint32_t)half32((int)t16) << 3);  // 4 bit: halves swapped in rows 16..31
+            // a row's place in the tiled layout: scalar base, per-lane 32-bit offset
+            auto row_base = [&](int64_t rr) -> int8_t * {
+                const uint32_t t = (uint32_t)rr & (BITS == 8 ? 15u : 31u);
+                return codes + (((rr >> (BITS == 8 ? 4 : 5)) * n_chunks) << 10) + t * (BITS == 8 ? 64u : 32u);
+            };
+            auto row_off = [&](int64_t rr) -> uint32_t {
+                const uint32_t t = (uint32_t)rr & (BITS == 8 ? 15u : 31u);
+                return (out_lane + ((slot_lane ^ (uint32_t)(BITS == 8 ? swz64((int)t) : swz32((int)t))) << 4)) ^
+                       (BITS == 8 ? 0u : (uint32_t)half32((int)t) << 3);  // 4 bit: halves swapped in rows 16..31
+            };
+            int8_t *out_row = row_base(r) + (conv_w > 0 ? copy_bytes : 0);
+            const uint32_t out_off = row_off(r);
+            // the shifted copies (tap-gathering convolution): this row's codes are the left
+            // neighbour of row r + 1 and the right neighbour of row r - 1 of the same image row
+            const int32_t wcol = conv_w > 0 ? (int32_t)(r % conv_w) : 0;
+            const bool to_left = conv_w > 0 && wcol + 1 < conv_w, to_right = conv_w > 0 && wcol > 0;
+            const bool fill_left = conv_w > 0 && wcol == 0, fill_right = conv_w > 0 && wcol + 1 == conv_w;
+            int8_t *rowL = to_left ? row_base(r + 1) : out_row;                       // copy 0, row r + 1
+            int8_t *rowR = to_right ? row_base(r - 1) + 2 * copy_bytes : out_row;     // copy 2, row r - 1
+            const uint32_t offL = to_left ? row_off(r + 1) : 0u, offR = to_right ? row_off(r - 1) : 0u;
+            int8_t *rowF = fill_left ? row_base(r) : row_base(r) + 2 * copy_bytes;     // copy 0 or 2, row r
 
             // NT steps together, so that their LDS round trips overlap
             auto steps = [&](auto nt_tag, const int32_t j0) __attribute__((always_inline)) {
@@ -277,8 +296,19 @@ __global__ __launch_bounds__(256) void k_quantize_act(
                     // positions are cleared to the stored value 0.
                     const uint32_t word = (BITS == 8 ? (lo ^ 0x80808080u) : (lo | (hi << 4))) & km[t];
                     const uint32_t j = (uint32_t)(j0 + t);
-                    if ((int32_t)(lane + 64u * j) < n_dw)
+                    if ((int32_t)(lane + 64u * j) < n_dw) {
                         *reinterpret_cast<uint32_t *>(out_row + (out_off + j * (kChunkStep * 1024u))) = word;
+                        if (to_left) *reinterpret_cast<uint32_t *>(rowL + (offL + j * (kChunkStep * 1024u))) = word;
+                        if (to_right) *reinterpret_cast<uint32_t *>(rowR + (offR + j * (kChunkStep * 1024u))) = word;
+                        if (fill_left || fill_right) {
+                            const uint32_t fw = fill32[lane + 64u * j];
+                            *reinterpret_cast<uint32_t *>(rowF + (out_off + j * (kChunkStep * 1024u))) = fw;
+                            // a one-pixel-wide image has both neighbours outside
+                            if (fill_left && fill_right)
+                                *reinterpret_cast<uint32_t *>(row_base(r) + 2 * copy_bytes +
+                                                              (out_off + j * (kChunkStep * 1024u))) = fw;
+                        }
+                    }
                 }
             };
             int32_t j0 = 0;
@@ -308,7 +338,8 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
     const int32_t *__restrict__ perm, const float *__restrict__ chunk_z,
     const float *__restrict__ chunk_inv, const float *__restrict__ taus, int32_t n_tau,
     int8_t *__restrict__ codes, uint8_t *__restrict__ row_class,
-    int32_t /*rpw_log2: unused, one row per wave*/) {
+    int32_t /*rpw_log2: unused, one row per wave*/, int32_t /*conv_w: not built here*/,
+    int64_t /*copy_bytes*/, const uint32_t * /*fill32*/) {
     extern __shared__ float lds[];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     float *xs = lds + (size_t)wave * C;
@@ -358,7 +389,7 @@ __global__ __launch_bounds__(256) void k_quantize_act_any(
 
 using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const int32_t *,
                       const float *, const float *, const float *, int32_t, int8_t *, uint8_t *,
-                      int32_t);
+                      int32_t, int32_t, int64_t, const uint32_t *);
 
 // A kernel instantiation and the state of its dynamic-LDS limit.
 struct Picked {
@@ -400,9 +431,11 @@ size_t quantize_act_lds_bytes(const Groups &g) {
 }
 
 hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, int8_t *codes,
-                               uint8_t *row_class, hipStream_t st) {
+                               uint8_t *row_class, hipStream_t st, int32_t conv_w, int64_t copy_bytes,
+                               const uint32_t *fill32) {
     const int32_t C = g.info.channels, Kp = g.info.k_padded;
     const bool vec4 = (C % 4) == 0 && C < 65535;
+    if (conv_w > 0 && !vec4) return hipErrorInvalidValue;
     Picked kern;
     size_t lds;
     int64_t blocks;
@@ -437,7 +470,7 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
     }
     hipLaunchKernelGGL(kern.kern, dim3((unsigned)blocks), dim3(256), lds, st, x, rows, C, Kp,
                        g.n_chunks, g.d_perm, g.d_chunk_z, g.d_chunk_inv, g.d_taus, g.n_tab - 1, codes,
-                       row_class, rpw_log2);
+                       row_class, rpw_log2, conv_w, copy_bytes, fill32);
     return hipGetLastError();
 }
 

@@ -139,7 +139,25 @@ struct Cfg {
 // 4-bit field; the single fold and the epilogue read that class's scale and offset from a
 // small LDS table, and the zero-point term is zoff[class] * (sw[o] * wsum[o]) + bias[o],
 // whose two class-independent rows arrive in place of zb[0] and zb[1].
-template <class CF, bool DUMP, int GEGLU, bool MULTI>
+//
+// CONV: the layer is a 3 x 3 convolution (stride 1, zero padding 1) and the nine taps are
+// GATHERED by the direct-to-LDS loads instead of being unfolded in memory.  `codes` holds
+// three copies of the map's code tensor, copy c at codes + c * cv.copy_bytes: copy 1 is the map
+// itself, copy 0 / copy 2 hold in row r the code row of the pixel to the left / right of r
+// (the code of the value 0 where the image ends).  Tap t = 3 (dy + 1) + (dx + 1) of a 16-row
+// (32-row) block of output pixels is then the block dy image rows further in copy dx + 1 --
+// one contiguous 1 KiB piece per chunk, as for a linear layer -- or, outside the image, a block
+// of the code of 0 (cv.fill: one 1 KiB block per chunk).  Needs the image width to be a
+// multiple of the rows of a block.  The K' order is tap-major, K' = 9 K'_map.
+struct ConvGather {
+    int32_t w_blocks = 0;    // image width / rows per code block
+    int32_t height = 0;      // image height
+    int32_t chunks = 0;      // chunks per tap (K'_map / 64)
+    int64_t copy_bytes = 0;  // bytes of one copy of the code tensor
+    const int8_t *fill = nullptr;
+};
+
+template <class CF, bool DUMP, int GEGLU, bool MULTI, bool CONV = false>
 __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int8_t *__restrict__ codes, const uint8_t *__restrict__ row_class,
     const int8_t *__restrict__ wq, const float *__restrict__ sw, const float *__restrict__ zb,
@@ -148,7 +166,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     int32_t O_pad, int32_t Kp, int32_t NG, int32_t tiles_r, int32_t tiles_o, int32_t per_xcd,
     int32_t super_rows, float *__restrict__ y, int32_t *__restrict__ acc_dump,
     const float2 *__restrict__ rq_zi, const uint8_t *__restrict__ rq_keep,
-    uint8_t *__restrict__ rq_cls, int32_t rq_bits) {
+    uint8_t *__restrict__ rq_cls, int32_t rq_bits, ConvGather cv) {
     constexpr int ABITS = CF::ABITS, BR = CF::BR, BO = CF::BO, STAGES = CF::STAGES;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
@@ -183,6 +201,8 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
     const int64_t n_ablocks = (rows + kARows - 1) / kARows;
     const int8_t *src[CF::LOADS];  // uniform per wave
     int dst[CF::LOADS];
+    int64_t a_blk[CF::LOADS];  // CONV: the load's row block (-1: a weight block) and its image row
+    int32_t a_h[CF::LOADS];
     const uint32_t lane16 = lane * 16;
     auto lds_addr = [](const uint8_t *p) {  // 32-bit LDS address of a pointer into `lds`
         return (uint32_t)reinterpret_cast<uintptr_t>(
@@ -197,7 +217,11 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             blk = blk < n_ablocks ? blk : n_ablocks - 1;  // clamp: rows past the end are never stored
             src[j] = codes + ((blk * n_chunks) << 10);
             dst[j] = i * 1024;
+            a_blk[j] = blk;
+            a_h[j] = CONV ? (int32_t)((blk / cv.w_blocks) % cv.height) : 0;
         } else {
+            a_blk[j] = -1;
+            a_h[j] = 0;
             const int ib = i - CF::AINSTR;
             int32_t rb = o0 / 16 + ib;  // 16-row block of the packed weights
             if (GEGLU) {
@@ -208,11 +232,32 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
             dst[j] = CF::ABYTES + ib * 1024;
         }
     }
+    // CONV: chunks are issued strictly in order, so the tap (dy + 1, dx + 1) and the chunk
+    // inside the tap of the next chunk to issue are running counters, not divisions
+    int32_t cv_c = 0, cv_dx = 0, cv_dy = 0;
     auto issue_chunk_at = [&](int32_t ch, int stage) __attribute__((always_inline)) {
         uint8_t *base = lds + stage * CF::STAGE_BYTES;
 #pragma unroll
-        for (int j = 0; j < CF::LOADS; ++j)
-            DGQ_LDS_DMA16(src[j] + ((int64_t)ch << 10), lane16, lds_addr(base + dst[j]));
+        for (int j = 0; j < CF::LOADS; ++j) {
+            const int8_t *p = src[j] + ((int64_t)ch << 10);
+            if (CONV && a_blk[j] >= 0) {
+                const int32_t hh = a_h[j] + cv_dy - 1;
+                const int64_t blk = a_blk[j] + (int64_t)(cv_dy - 1) * cv.w_blocks;
+                p = (uint32_t)hh < (uint32_t)cv.height
+                        ? codes + cv_dx * cv.copy_bytes + ((blk * cv.chunks + cv_c) << 10)
+                        : cv.fill + ((int64_t)cv_c << 10);
+            }
+            DGQ_LDS_DMA16(p, lane16, lds_addr(base + dst[j]));
+        }
+        if (CONV) {
+            if (++cv_c == cv.chunks) {
+                cv_c = 0;
+                if (++cv_dx == 3) {
+                    cv_dx = 0;
+                    ++cv_dy;
+                }
+            }
+        }
     };
     auto issue_chunk = [&](int32_t ch) { issue_chunk_at(ch, ch % STAGES); };
 
@@ -748,10 +793,10 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         run(std::false_type{});
 }
 
-template <class CF, bool DUMP, int GEGLU = 0, bool MULTI = false>
+template <class CF, bool DUMP, int GEGLU = 0, bool MULTI = false, bool CONV = false>
 hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
                       const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,
-                      hipStream_t st, uint8_t *rq_cls = nullptr) {
+                      hipStream_t st, uint8_t *rq_cls = nullptr, const ConvGather *cvp = nullptr) {
     const int32_t tiles_r = (int32_t)((rows + CF::TR - 1) / CF::TR);
     const int32_t tiles_o = (w.O + CF::TO - 1) / CF::TO;  // O_pad is a multiple of every TO
     const int64_t T = (int64_t)tiles_r * tiles_o;
@@ -761,7 +806,8 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
                  (MULTI ? 4 + 8 * (size_t)g.n_tab : 12 * (size_t)g.info.n_groups);
     static_assert(GEGLU == 0 || CF::BO == 2, "the gated epilogue pairs the two blocks of a wave");
     static_assert(!(GEGLU != 0 && MULTI), "the gated epilogue is built for at most two pixel classes");
-    auto kern = k_linear<CF, DUMP, GEGLU, MULTI>;
+    auto kern = k_linear<CF, DUMP, GEGLU, MULTI, CONV>;
+    const ConvGather cv = cvp ? *cvp : ConvGather();
     {
         hipError_t e = DGQ_ENSURE_LDS(kern, kStageBudget);
         if (e != hipSuccess) return e;
@@ -785,12 +831,41 @@ hipError_t launch_cfg(const Groups &g, const Weight &w, const int8_t *codes,
                        w.d_zb, g.d_s, g.d_zoff, g.n_tab, g.d_gchunk, rows, w.O, w.O_pad, w.Kp,
                        g.info.n_groups,
                        tiles_r, tiles_o, per_xcd, super_rows, y, acc_dump, w.d_rq_zi, w.d_rq_keep, rq_cls,
-                       w.next_bits);
+                       w.next_bits, cv);
     return hipGetLastError();
 }
 
 }  // namespace
 
+
+// The 3 x 3 convolution with its taps gathered by the loads (see ConvGather): `codes3` are the
+// three shifted copies of the map's codes, g9 / w the replicated tables and the packed
+// [O, 9 C] kernel.
+hipError_t launch_linear_conv3x3(const Groups &g9, const Weight &w, const int8_t *codes3,
+                                 const uint8_t *row_class, int32_t B, int32_t H, int32_t W, float *y,
+                                 hipStream_t st) {
+    const bool a8 = g9.info.act_bits == 8;
+    const int32_t rpb = a8 ? 16 : 32;
+    if (W % rpb != 0 || g9.conv_taps != 9 || !g9.d_fill_blocks) return hipErrorInvalidValue;
+    const int64_t rows = (int64_t)B * H * W;
+    ConvGather cv;
+    cv.w_blocks = W / rpb;
+    cv.height = H;
+    cv.chunks = g9.base_kp / kGranule;
+    cv.copy_bytes = ((rows + rpb - 1) / rpb) * (int64_t)cv.chunks * 1024;
+    cv.fill = reinterpret_cast<const int8_t *>(g9.d_fill_blocks);
+    const int64_t t128 = ((rows + 127) / 128) * ((w.O + 127) / 128);
+    const int64_t t64x128 = ((rows + 63) / 64) * ((w.O + 127) / 128);
+    const int cfg = t128 >= 512 ? 4 : (t64x128 >= 256 ? 2 : 6);
+    if (cfg == 4)
+        return a8 ? launch_cfg<Cfg<8, 4, 2, 1, 2, 4, 4>, false, 0, false, true>(g9, w, codes3, row_class, rows, y, nullptr, st, nullptr, &cv)
+                  : launch_cfg<Cfg<4, 4, 2, 1, 2, 4, 4>, false, 0, false, true>(g9, w, codes3, row_class, rows, y, nullptr, st, nullptr, &cv);
+    if (cfg == 2)
+        return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 2, 3, 4>, false, 0, false, true>(g9, w, codes3, row_class, rows, y, nullptr, st, nullptr, &cv)
+                  : launch_cfg<Cfg<4, 2, 2, 1, 2, 3, 4>, false, 0, false, true>(g9, w, codes3, row_class, rows, y, nullptr, st, nullptr, &cv);
+    return a8 ? launch_cfg<Cfg<8, 2, 2, 1, 1, 8, 4>, false, 0, false, true>(g9, w, codes3, row_class, rows, y, nullptr, st, nullptr, &cv)
+              : launch_cfg<Cfg<4, 2, 2, 1, 1, 8, 4>, false, 0, false, true>(g9, w, codes3, row_class, rows, y, nullptr, st, nullptr, &cv);
+}
 
 hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
                          const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump,

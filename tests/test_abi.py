@@ -56,6 +56,8 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_selfattn_logq(None, None, None, 1, 8, 1, 8, 8, None, None, None, None, None, 0, None) == -1
     assert lib.dgq_groups_for_conv3x3(None, None) == -1
     assert lib.dgq_conv3x3_codes(None, None, 1, 4, 4, None, None) == -1
+    assert lib.dgq_quantize_act_conv3x3(None, None, None, 1, 4, 16, None, None, None) == -1
+    assert lib.dgq_linear_conv3x3(None, None, None, None, 1, 4, 16, None, None) == -1
     h = C.c_void_p()
     assert lib.dgq_calibrate_groups(None, 4, 64, 8, 64, 2, None, C.byref(h)) == -1
     buf = (C.c_float * 64)()

@@ -68,6 +68,20 @@ def _run(dgq, oracle, B, H, W, C, O, act_bits, kind, seed, sample=None, check_ac
     owq, osw = oracle.quantize_weight(Wt, 8)
     oy, oacc = oracle.linear(og9, oq["q"], oq["cls"], owq, osw, bias, want_acc=check_acc)
     assert_close_fp32(y.cpu().numpy()[sel], oy, "y")
+    # the same convolution with its taps gathered by the contraction's loads (no unfolded
+    # buffer): same arithmetic in the same order, so the two results are equal bit for bit
+    if W % (16 if act_bits == 8 else 32) == 0 and C % 4 == 0:
+        codes3, cls3 = dgq.dgq_quantize_act_conv3x3(g, g9, _dev(X), B, H, W,
+                                                    codes3=torch.full((int(dgq.lib().dgq_conv3x3_codes3_bytes(
+                                                        g9.handle, B, H, W)),), 0x55, dtype=torch.int8,
+                                                        device="cuda"))
+        y3 = dgq.dgq_linear_conv3x3(g9, wt, codes3, cls3, B, H, W)
+        torch.cuda.synchronize()
+        assert int(cls3.max()) == 0
+        # copy 1 of the three is the map's own code tensor
+        n1 = codes.numel()
+        assert torch.equal(codes3[n1:2 * n1].view(-1), codes.view(-1))
+        assert torch.equal(y3.view(torch.int32), y.view(torch.int32))
     if check_acc:
         dump = torch.full((rows, O, og9.NG), -7, dtype=torch.int32, device="cuda")
         dgq.dgq_linear(g9, wt, codes9, cls, acc_dump=dump)
@@ -82,6 +96,8 @@ def _run(dgq, oracle, B, H, W, C, O, act_bits, kind, seed, sample=None, check_ac
 @pytest.mark.parametrize("B,H,W,C,O", [
     (2, 9, 7, 72, 40),      # pixels not a multiple of the 16 / 32-row code blocks
     (1, 16, 16, 128, 128),
+    (2, 6, 32, 72, 40),     # width of one or two code blocks, a ragged last row tile
+    (1, 3, 64, 64, 24),
     (3, 5, 3, 40, 24),      # images smaller than a code block: neighbours cross block borders
     (1, 1, 1, 64, 8),       # a single pixel: eight taps of padding
 ])
@@ -100,6 +116,19 @@ def test_resnet_block_shape_sampled(dgq, oracle):
     _run(dgq, oracle, B, H, W, C, O, 8, "kmeans", 77, sample=sample)
 
 
+@pytest.mark.parametrize("act_bits", [8, 4])
+def test_large_map_tap_gathering(dgq, oracle, act_bits):
+    """2 x 64 x 64 pixels, 320 -> 320 channels in blocks of 64: the launch takes the 128 x 128
+    tiles; the gathered and the unfolded convolution must agree on every output, the oracle
+    checks sampled pixels."""
+    B, H, W, C, O = 2, 64, 64, 320, 1280
+    rng = np.random.default_rng(5)
+    rows = B * H * W
+    sample = np.unique(np.concatenate([rng.choice(rows, 10, replace=False),
+                                       [0, W - 1, W, H * W - 1, H * W, rows - W, rows - 1]]))
+    _run(dgq, oracle, B, H, W, C, O, act_bits, "blocks", 78, sample=sample)
+
+
 def test_argument_errors(dgq):
     x = _dev(di.linear_case(1, 1, 64, 64, 8)["X"])
     g2 = dgq.dgq_calibrate_groups(x, 8, 64, 2)                  # two pixel classes
@@ -114,6 +143,9 @@ def test_argument_errors(dgq):
     g9 = dgq.dgq_groups_for_conv3x3(g1)
     with pytest.raises(dgq.DgqError) as e:                      # nested unfolding
         dgq.dgq_groups_for_conv3x3(g9)
+    assert e.value.code == -4
+    with pytest.raises(dgq.DgqError) as e:                      # width not a multiple of a code block
+        dgq.dgq_quantize_act_conv3x3(g1, g9, x, 1, 8, 8)
     assert e.value.code == -4
     for hnd in (g9, g1, g2):
         hnd.free()
