@@ -65,149 +65,129 @@ struct DevBuf {  // scoped device allocation for the blocking (offline) calls
     T *as() const { return static_cast<T *>(p); }
 };
 
-// Result of the exact two-cluster split of a 1-D sample (Section 3.3 groups
-// vectors "based on their range using K-means"; in one dimension the optimum
-// is a cut of the sorted sample, so it can be found exactly).
-struct Split {
-    int64_t n_lower = 0;         // size of the lower cluster (n if no split exists)
-    float tau = INFINITY;        // value > tau  <=>  upper cluster
-    std::vector<int64_t> order;  // indices sorted by (value, index)
-};
-
-// Every cut between two distinct neighbouring values is scored by the
-// within-cluster sum of squares computed from running sums of v and v^2 in
-// double, taken in sorted order; the first minimum wins.  The threshold is the
-// midpoint of the two cluster means, rounded to fp32 and clamped between the
-// two values it separates.  The order of the floating-point operations is part
-// of the definition: tau must be reproducible bit for bit.
-Split split_two_clusters(const std::vector<float> &v) {
-    Split sp;
-    const int64_t n = (int64_t)v.size();
-    sp.order.resize(n);
-    std::iota(sp.order.begin(), sp.order.end(), (int64_t)0);
-    std::sort(sp.order.begin(), sp.order.end(), [&](int64_t a, int64_t b) {
-        return v[a] < v[b] || (v[a] == v[b] && a < b);
-    });
-    sp.n_lower = n;
-    if (n < 2 || !(v[sp.order.front()] < v[sp.order.back()])) return sp;
-
-    double total = 0.0, total_sq = 0.0;
-    for (int64_t i = 0; i < n; ++i) {
-        const double x = v[sp.order[i]];
-        total = total + x;
-        total_sq = total_sq + x * x;
-    }
-    double run = 0.0, run_sq = 0.0, best_cost = 0.0, best_run = 0.0;
-    int64_t cut = -1;
-    for (int64_t left = 1; left < n; ++left) {
-        const double x = v[sp.order[left - 1]];
-        run = run + x;
-        run_sq = run_sq + x * x;
-        if (!(v[sp.order[left - 1]] < v[sp.order[left]])) continue;
-        const double rest = total - run, rest_sq = total_sq - run_sq;
-        const double cost_lo = run_sq - (run * run) / (double)left;
-        const double cost_hi = rest_sq - (rest * rest) / (double)(n - left);
-        const double cost = cost_lo + cost_hi;
-        if (cut < 0 || cost < best_cost) {
-            best_cost = cost;
-            best_run = run;
-            cut = left;
-        }
-    }
-    const double mean_lo = best_run / (double)cut;
-    const double mean_hi = (total - best_run) / (double)(n - cut);
-    float tau = (float)(0.5 * (mean_lo + mean_hi));
-    const float below = v[sp.order[cut - 1]];
-    const float above = std::nextafterf(v[sp.order[cut]], -INFINITY);
-    tau = std::max(tau, below);
-    tau = std::min(tau, above);
-    sp.tau = tau;
-    sp.n_lower = cut;
-    return sp;
-}
-
-// Exact K-means of a 1-D sample (the grouping "by range using K-means" of
-// Section 3.3).  An optimal 1-D clustering is a partition of the sorted sample into
-// intervals, so the optimum over all partitions into k intervals is reached by a dynamic
-// programme: with running sums S, S2 of the sorted values and their squares (double,
-// sorted order, ties by index)
-//     cost(i, j) = (S2[j] - S2[i]) - (S[j] - S[i])^2 / (j - i)
-//     best[1][j] = cost(0, j),   best[k][j] = min_i best[k-1][i] + cost(i, j)
-// over cuts i between two distinct values, the first minimum winning; k is the smaller
-// of K and the number of distinct values.  The threshold between two neighbouring
-// clusters is the midpoint of their means, rounded to fp32 and clamped between the two
-// values it separates, so "number of thresholds below v" names v's cluster.  The order
-// of the floating-point operations is part of the definition, as in the two-cluster case.
-// Time O(K n^2): calibration is offline.
+// Exact K-means of a 1-D sample (the grouping "by range using K-means" of Section 3.3).
+// An optimal 1-D clustering cuts the sorted sample into intervals, so the optimum over all
+// partitions into k intervals is a shortest path through k layers,
+//     layer_k(j) = min over cuts i < j of layer_{k-1}(i) + within(i, j),
+//     within(i, j) = sum of squared deviations of sorted values i .. j-1 from their mean,
+// where only positions between two DISTINCT values are cuts.  within() satisfies the
+// quadrangle inequality, hence the leftmost best cut of layer_k(j) does not move left as j
+// grows, and a layer is filled by divide and conquer: solve the middle j of a range over its
+// window of candidate cuts, then the left half with the window's lower part and the right half
+// with its upper part -- O(n log n) evaluations per layer instead of the O(n^2) of the
+// definition, which is what lets the pixel dimension take every calibration row (64 prompts of
+// 4096 pixels: 262144).  A range whose middle has no admissible cut keeps the whole window for
+// both halves.  within() comes from running sums of the sorted values and their squares in
+// double; ties go to the leftmost cut; k = min(K, number of distinct values).  The threshold
+// between two neighbouring clusters is the midpoint of their means, rounded to fp32 and clamped
+// between the two values it separates, so "number of thresholds below v" names v's cluster.
 struct Clusters {
     std::vector<int64_t> bounds;  // cluster c = sorted positions [bounds[c], bounds[c+1])
     std::vector<float> taus;      // bounds.size() - 2 thresholds, ascending
     std::vector<int64_t> order;   // indices sorted by (value, index)
 };
-constexpr int64_t kMaxKMeansSamples = 32768;
 
 Clusters cluster_by_range(const std::vector<float> &v, int32_t K) {
     Clusters cl;
     const int64_t n = (int64_t)v.size();
     cl.order.resize(n);
     std::iota(cl.order.begin(), cl.order.end(), (int64_t)0);
-    std::sort(cl.order.begin(), cl.order.end(), [&](int64_t a, int64_t b) {
-        return v[a] < v[b] || (v[a] == v[b] && a < b);
+    std::sort(cl.order.begin(), cl.order.end(), [&](int64_t x, int64_t y) {
+        return v[x] < v[y] || (v[x] == v[y] && x < y);
     });
-    std::vector<float> a(n);
-    for (int64_t i = 0; i < n; ++i) a[i] = v[cl.order[i]];
-    int64_t distinct = 1;
-    for (int64_t i = 1; i < n; ++i) distinct += a[i - 1] < a[i] ? 1 : 0;
-    const int32_t k_use = (int32_t)std::max<int64_t>(1, std::min<int64_t>(K, distinct));
-    std::vector<double> S(n + 1, 0.0), S2(n + 1, 0.0);
+    std::vector<float> sorted(n);
+    std::vector<double> sum1(n + 1, 0.0), sum2(n + 1, 0.0);
+    std::vector<uint8_t> is_cut(n + 1, 0);  // position i separates two distinct values
+    int64_t distinct = n > 0 ? 1 : 0;
     for (int64_t i = 0; i < n; ++i) {
-        const double x = a[i];
-        S[i + 1] = S[i] + x;
-        S2[i + 1] = S2[i] + x * x;
+        sorted[i] = v[cl.order[i]];
+        const double x = sorted[i];
+        sum1[i + 1] = sum1[i] + x;
+        sum2[i + 1] = sum2[i] + x * x;
+        if (i > 0 && sorted[i - 1] < sorted[i]) {
+            is_cut[i] = 1;
+            ++distinct;
+        }
     }
-    auto cost = [&](int64_t i, int64_t j) {
-        const double d = S[j] - S[i];
-        return (S2[j] - S2[i]) - (d * d) / (double)(j - i);
+    const int32_t k_use = (int32_t)std::max<int64_t>(1, std::min<int64_t>(K, distinct));
+    auto within = [&](int64_t i, int64_t j) {
+        const double d = sum1[j] - sum1[i];
+        return (sum2[j] - sum2[i]) - (d * d) / (double)(j - i);
     };
-    // layer k: best total cost of the first j values in k clusters and the cut that reaches it
-    std::vector<std::vector<double>> best(k_use + 1, std::vector<double>(n + 1, 0.0));
-    std::vector<std::vector<int64_t>> cut(k_use + 1, std::vector<int64_t>(n + 1, -1));
+    // value[k][j]: least total cost of the first j values in k clusters; from[k][j]: the cut
+    // that reaches it, -1 where no admissible partition exists
+    std::vector<std::vector<double>> value(k_use + 1, std::vector<double>(n + 1, 0.0));
+    std::vector<std::vector<int64_t>> from(k_use + 1, std::vector<int64_t>(n + 1, -1));
     for (int64_t j = 1; j <= n; ++j) {
-        best[1][j] = cost(0, j);
-        cut[1][j] = 0;
+        value[1][j] = within(0, j);
+        from[1][j] = 0;
     }
-    for (int32_t k = 2; k <= k_use; ++k)
-        for (int64_t j = k; j <= n; ++j) {
-            int64_t arg = -1;
-            double bv = 0.0;
-            const std::vector<double> &prev = best[k - 1];
-            const std::vector<int64_t> &prev_cut = cut[k - 1];
-            for (int64_t i = k - 1; i < j; ++i) {
-                if (prev_cut[i] < 0 || !(a[i - 1] < a[i])) continue;
-                const double t = prev[i] + cost(i, j);
-                if (arg < 0 || t < bv) {
-                    bv = t;
-                    arg = i;
+    struct Range {
+        int64_t j_lo, j_hi, i_lo, i_hi;  // rows j_lo..j_hi, candidate cuts i_lo..i_hi (inclusive)
+    };
+    std::vector<Range> todo;
+    for (int32_t k = 2; k <= k_use; ++k) {
+        const std::vector<double> &below = value[k - 1];
+        const std::vector<int64_t> &below_from = from[k - 1];
+        todo.clear();
+        todo.push_back({(int64_t)k, n, (int64_t)k - 1, n - 1});
+        while (!todo.empty()) {
+            const Range r = todo.back();
+            todo.pop_back();
+            if (r.j_lo > r.j_hi) continue;
+            const int64_t j = r.j_lo + (r.j_hi - r.j_lo) / 2;
+            int64_t pick = -1;
+            double least = 0.0;
+            const int64_t last = std::min(r.i_hi, j - 1);
+            for (int64_t i = r.i_lo; i <= last; ++i) {
+                if (!is_cut[i] || below_from[i] < 0) continue;
+                const double t = below[i] + within(i, j);
+                if (pick < 0 || t < least) {
+                    least = t;
+                    pick = i;
                 }
             }
-            if (arg >= 0) {
-                best[k][j] = bv;
-                cut[k][j] = arg;
+            if (pick >= 0) {
+                value[k][j] = least;
+                from[k][j] = pick;
+                todo.push_back({r.j_lo, j - 1, r.i_lo, pick});
+                todo.push_back({j + 1, r.j_hi, pick, r.i_hi});
+            } else {
+                todo.push_back({r.j_lo, j - 1, r.i_lo, r.i_hi});
+                todo.push_back({j + 1, r.j_hi, r.i_lo, r.i_hi});
             }
         }
+    }
     cl.bounds.assign(k_use + 1, 0);
     cl.bounds[k_use] = n;
-    for (int32_t k = k_use; k >= 1; --k) cl.bounds[k - 1] = cut[k][cl.bounds[k]];
+    for (int32_t k = k_use; k >= 1; --k) cl.bounds[k - 1] = from[k][cl.bounds[k]];
     for (int32_t c = 0; c + 1 < k_use; ++c) {
         const int64_t b0 = cl.bounds[c], b1 = cl.bounds[c + 1], b2 = cl.bounds[c + 2];
-        const double mean_lo = (S[b1] - S[b0]) / (double)(b1 - b0);
-        const double mean_hi = (S[b2] - S[b1]) / (double)(b2 - b1);
+        const double mean_lo = (sum1[b1] - sum1[b0]) / (double)(b1 - b0);
+        const double mean_hi = (sum1[b2] - sum1[b1]) / (double)(b2 - b1);
         float tau = (float)(0.5 * (mean_lo + mean_hi));
-        tau = std::max(tau, a[b1 - 1]);
-        tau = std::min(tau, std::nextafterf(a[b1], -INFINITY));
+        tau = std::max(tau, sorted[b1 - 1]);
+        tau = std::min(tau, std::nextafterf(sorted[b1], -INFINITY));
         cl.taus.push_back(tau);
     }
     return cl;
+}
+
+// The two-cluster case (outlier rows against regular rows, outlier channels against regular
+// channels): the same exact clustering with K = 2.
+struct Split {
+    int64_t n_lower = 0;         // size of the lower cluster (n if no split exists)
+    float tau = INFINITY;        // value > tau  <=>  upper cluster
+    std::vector<int64_t> order;  // indices sorted by (value, index)
+};
+
+Split split_two_clusters(const std::vector<float> &v) {
+    Clusters cl = cluster_by_range(v, 2);
+    Split sp;
+    sp.n_lower = cl.bounds.size() == 3 ? cl.bounds[1] : (int64_t)v.size();
+    if (!cl.taus.empty()) sp.tau = cl.taus[0];
+    sp.order = std::move(cl.order);
+    return sp;
 }
 
 // D_d of Section 3.3 from the per-vector maxima and minima along one dimension.
@@ -487,10 +467,6 @@ int dgq_calibrate_kmeans(const float *x_cal, int64_t rows, int32_t channels, int
     const double d_pixel = variability(rmx, rmn);
     const int32_t dstar = d_pixel > d_channel ? 1 : 0;  // Eq. 5
     const int32_t dim = dimension == DGQ_DIM_AUTO ? dstar : dimension;
-    if (dim == DGQ_DIM_PIXEL && rows > kMaxKMeansSamples)
-        return fail(DGQ_EUNSUPPORTED,
-                    "dgq_calibrate_kmeans: the exact clustering of pixels takes at most 32768 calibration rows");
-
     Groups *g = new (std::nothrow) Groups();
     if (!g) return fail(DGQ_EINVAL, "dgq_calibrate_kmeans: out of host memory");
     const float levels = (float)(1 << act_bits);

@@ -236,10 +236,59 @@ def test_unsupported_combinations(dgq):
     with pytest.raises(dgq.DgqError) as e:
         dgq.dgq_linear(g, w, codes, cls, acc_dump=dump)
     assert e.value.code == -4
+    # more rows than the former limit of the pixel dimension, all of one range: one class
     big = torch.zeros((40000, 64), dtype=torch.float32, device="cuda")
-    with pytest.raises(dgq.DgqError) as e:
-        dgq.dgq_calibrate_kmeans(big, 8, 8, 1)
-    assert e.value.code == -4
+    gb = dgq.dgq_calibrate_kmeans(big, 8, 8, 1)
+    assert gb.info.n_pixel_classes == 1
+    gb.free()
     torch.cuda.synchronize()
     w.free()
     g.free()
+
+
+@pytest.mark.parametrize("K", [8, 16])
+def test_pixel_clustering_of_many_rows_against_the_definition(dgq, oracle, K):
+    """The library clusters by divide and conquer over the monotone best cuts, the oracle by the
+    O(K n^2) definition: thresholds, class sizes and cell tables of 12288 calibration rows
+    (three 64 x 64 latents, heavy-tailed ranges with repeated values) must be equal bit for bit."""
+    rng = np.random.default_rng(60 + K)
+    n, C = 12288, 64
+    X = rng.standard_normal((n, C)).astype(np.float32)
+    X *= np.exp(rng.standard_normal((n, 1)) * 0.8).astype(np.float32)       # ranges over octaves
+    X[rng.choice(n, 40, replace=False)] *= 25.0
+    X[1000:1400] = X[1000]                                                  # repeated ranges
+    og = oracle.calibrate_kmeans(X, 8, K, 1)
+    gg = dgq.dgq_calibrate_kmeans(_dev(X), 8, K, dgq.DIM_PIXEL)
+    _groups_equal(gg, og)
+    gg.free()
+
+
+def test_pixel_clustering_of_a_whole_calibration_set(dgq):
+    """64 prompts x 4096 pixels = 262144 calibration rows (Section 4.1's calibration set; the
+    O(n^2) definition would take hours): the clustering returns, the thresholds ascend, every
+    class is populated at run time, and its cost is no worse than that of equal-count classes."""
+    import torch
+    rng = np.random.default_rng(61)
+    n, C, K = 64 * 4096, 64, 16
+    X = rng.standard_normal((n, C)).astype(np.float32)
+    X *= np.exp(rng.standard_normal((n, 1)) * 0.7).astype(np.float32)
+    X[rng.choice(n, 128, replace=False)] *= 25.0
+    xd = _dev(X)
+    gg = dgq.dgq_calibrate_kmeans(xd, 8, K, dgq.DIM_PIXEL)
+    assert gg.info.n_pixel_classes == K
+    taus = gg.tables()["taus"].astype(np.float64)
+    assert np.all(np.diff(taus) > 0)
+    width = (X.max(1) - X.min(1)).astype(np.float64)
+    cls_ref = (width[:, None] > taus[None, :]).sum(1)
+    codes, cls = dgq.dgq_quantize_act(gg, xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(cls.cpu().numpy(), cls_ref.astype(np.uint8))
+    assert np.bincount(cls_ref, minlength=K).min() > 0
+
+    def sse(labels):
+        return sum(((width[labels == c] - width[labels == c].mean()) ** 2).sum() for c in range(K))
+    order = np.argsort(width, kind="stable")
+    equal = np.empty(n, np.int64)
+    equal[order] = np.arange(n) * K // n
+    assert sse(cls_ref) <= sse(equal)
+    gg.free()
