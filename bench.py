@@ -201,7 +201,6 @@ def main():
         which = (("mfma",) if args.probe_mfma else ()) + (("stream",) if args.probe_stream else ())
         print(json.dumps(dict(probe="ceilings", **measure_ceilings(torch, dgq, dev, which))))
         return
-    ceilings = None if args.no_ceilings else measure_ceilings(torch, dgq, dev)
     if args.probe_selfattn:
         B_, N_, H_, d_ = 16, 4096, 10, 64
         c_ = di.selfattn_case(77, 1, N_, H_, d_)
@@ -213,6 +212,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps(dict(probe="selfattn", B=B_, N=N_, H=H_, d=d_, launches=3)))
         return
+    ceilings = None if args.no_ceilings else measure_ceilings(torch, dgq, dev)
     cfg, desc = workload(args.workload)
 
     def up(a):
