@@ -482,16 +482,22 @@ def main():
     # next to the same layers under the step's pixel-class x channel-group grid; and one
     # layer swept over T = 25 per-timestep table entries (Eq. 7), each step with its own handle.
     def time_calls(fn, a, n_rep=10):
+        # best of three rounds: the chip's clock settles over the first few hundred microseconds
+        # of a new kernel mix, and single rounds of the same call differ by up to 10 %
         for _ in range(2):
             if fn(*a) != 0:
                 raise dgq.DgqError(-1, L.dgq_last_error().decode())
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(n_rep):
-            fn(*a)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / n_rep
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(n_rep):
+                fn(*a)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / n_rep
+            best = us if best is None or us < best else best
+        return best
 
     def step_us(kind, ent):
         ci = [i for i, (k_, key, _) in enumerate(calls) if k_ == kind and key[0] is ent][0]
@@ -594,6 +600,31 @@ def main():
                                   us_two_layers_in_step=round(sep, 2)))
             wt2.free()
             del wk, wv, y2
+
+    # ---------------- beyond the step: 4-bit weights stored two per byte --------------------
+    # A8W4 on two layers: the handle that keeps one weight per byte against the nibble-packed
+    # handle, whose weights a small kernel widens into a workspace before the contraction.
+    w4 = []
+    if args.workload == "config5" and not args.step_only:
+        for ent in layers:
+            if ent["name"] not in ("hi.ff.in", "lo.ff.out", "hi.q"):
+                continue
+            m = ent["modes"][(8, 8)]
+            M = ent["M"]
+            w = up(di.linear_case(ent["seed"], 1, 2, ent["C"], ent["O"])["W"])
+            wide = dgq.dgq_pack_weight(m["g"], w, None, 4)
+            packed = dgq.dgq_pack_weight(m["g"], w, None, 4).pack_nibbles()
+            ws = torch.empty(dgq.dgq_linear_workspace_bytes(m["g"], packed, M), dtype=torch.uint8, device=dev)
+            base = (C.c_void_p(m["g"].handle), None, ptr(m["codes"]), ptr(m["cls"]), C.c_int64(M), ptr(ent["y"]), None)
+            us_w = time_calls(L.dgq_linear, base[:1] + (C.c_void_p(wide.handle),) + base[2:] + (None, C.c_size_t(0), sp))
+            us_p = time_calls(L.dgq_linear, base[:1] + (C.c_void_p(packed.handle),) + base[2:] +
+                              (ptr(ws), C.c_size_t(ws.numel()), sp))
+            w4.append(dict(layer=ent["name"], M=M, C=ent["C"], O=ent["O"], us_byte_per_weight=round(us_w, 2),
+                           us_nibble_packed=round(us_p, 2), weight_bytes=wide.device_bytes(),
+                           weight_bytes_nibble_packed=packed.device_bytes()))
+            wide.free()
+            packed.free()
+            del w, ws
 
     # ---------------- beyond the step: ff.in -> ff.out chained without the fp32 activation --
     # The gated layer writes the following layer's codes (dgq_linear_geglu_requant) against
@@ -785,7 +816,7 @@ def main():
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, ceilings_measured=ceilings, kernels=kernels, linear_a8_layers=per_layer,
                 layer_table=layer_table, ms_whole_unet_from_table=(round(unet_ms, 3) if unet_ms else None),
-                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, prompt_kv_stacked=prompt_kv, value_quant=value_quant, self_attention=self_attn, conv3x3=conv, cpu_baseline=cpu)
+                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, prompt_kv_stacked=prompt_kv, w4_nibble_packed=w4, value_quant=value_quant, self_attention=self_attn, conv3x3=conv, cpu_baseline=cpu)
     print(json.dumps(line))
 
 

@@ -257,6 +257,28 @@ int dgq_pack_weight(const dgq_groups_t *g, const float *w, const float *bias,
    ORIGINAL channel order, sw host fp32 [out_channels]; either may be NULL. */
 int dgq_weight_tables(const dgq_weight_t *w, int8_t *wq, float *sw);
 
+/*
+ * 4-bit weights at half the bytes (Section 4.1 quantizes weights to 4 bits; Table 1's
+ * model-size column counts them as 4 bits each).  dgq_pack_weight keeps every integer
+ * weight in a byte, the operand format of the matrix cores.  This call converts a handle
+ * packed with w_bits = 4 to two weights per byte in place: its device footprint
+ * (dgq_weight_device_bytes) drops from O_pad * K' to O_pad * K' / 2 bytes plus the
+ * 12 * O_pad bytes of sw and zb.  A converted handle is accepted by dgq_linear only, which
+ * then needs a workspace of dgq_linear_workspace_bytes() bytes (O_pad * K', 16-byte
+ * aligned, caller-owned device memory, reusable between layers on one stream): a small
+ * kernel sign-extends the nibbles into it right before the contraction, which runs
+ * unchanged -- results are bit-identical to the unconverted handle's.  (Expanding in the
+ * contraction's own fragment path would cost it twelve more vector instructions per
+ * matrix instruction; the expansion kernel costs a few microseconds per call.)
+ * The other linear entry points return DGQ_EUNSUPPORTED for a converted handle.
+ * Blocks until done; allocates.  Errors: DGQ_EINVAL (null), DGQ_EUNSUPPORTED (w_bits != 4,
+ * or a handle from dgq_pack_weight_gated_for), DGQ_ESHAPE (already converted).
+ */
+int dgq_weight_pack_nibbles(dgq_weight_t *w, void *stream);
+
+/* Device bytes the handle owns (integer weights, sw, zb, and the tables of a gated handle). */
+size_t dgq_weight_device_bytes(const dgq_weight_t *w);
+
 void dgq_weight_free(dgq_weight_t *w);
 
 /*
@@ -298,8 +320,11 @@ size_t dgq_codes_bytes(const dgq_groups_t *g, int64_t rows);
  *   y: fp32 [rows, out_channels]
  *   acc_dump: NULL, or int32 [rows, out_channels, NG] receiving every group
  *             accumulator (debug / parity; slows the kernel down)
- *   workspace: unused by the current kernels (dgq_linear_workspace_bytes
- *             returns 0); pass NULL / 0.
+ *   workspace: device memory of at least dgq_linear_workspace_bytes(g, w, rows) bytes,
+ *             16-byte aligned: 0 bytes (pass NULL / 0) unless w was converted by
+ *             dgq_weight_pack_nibbles, whose expanded weights it receives.  The call only
+ *             enqueues work on `stream`; the workspace may be reused by the next call on
+ *             the same stream.  Too small: DGQ_EWORKSPACE.
  */
 int dgq_linear(const dgq_groups_t *g, const dgq_weight_t *w, const int8_t *codes,
                const uint8_t *row_class, int64_t rows, float *y,

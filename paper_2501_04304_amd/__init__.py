@@ -59,6 +59,9 @@ def lib():
         L.dgq_weight_tables.argtypes = [vp, vp, vp]
         L.dgq_weight_free.argtypes = [vp]
         L.dgq_weight_free.restype = None
+        L.dgq_weight_pack_nibbles.argtypes = [vp, vp]
+        L.dgq_weight_device_bytes.argtypes = [vp]
+        L.dgq_weight_device_bytes.restype = sz
         L.dgq_quantize_act.argtypes = [vp, vp, i64, vp, vp, vp]
         L.dgq_linear.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
         L.dgq_linear_geglu.argtypes = [vp, vp, vp, vp, i64, vp, vp]
@@ -164,6 +167,14 @@ class Weight:
         sw = np.empty(self.out_channels, np.float32)
         _check(lib().dgq_weight_tables(self.handle, wq.ctypes.data, sw.ctypes.data))
         return dict(wq=wq, sw=sw)
+
+    def pack_nibbles(self, stream=None):
+        """Two 4-bit weights per byte (dgq_weight_pack_nibbles); dgq_linear then needs a workspace."""
+        _check(lib().dgq_weight_pack_nibbles(self.handle, _stream(stream)))
+        return self
+
+    def device_bytes(self) -> int:
+        return int(lib().dgq_weight_device_bytes(self.handle))
 
     def free(self):
         if self.handle:
@@ -329,9 +340,14 @@ def dgq_quantize_act(groups: Groups, x, codes=None, row_class=None, stream=None)
     return codes, row_class
 
 
+def dgq_linear_workspace_bytes(groups: Groups, weight: Weight, rows: int) -> int:
+    return int(lib().dgq_linear_workspace_bytes(groups.handle, weight.handle, rows))
+
+
 def dgq_linear(groups: Groups, weight: Weight, codes, row_class, y=None, acc_dump=None,
-               stream=None):
-    """Returns y fp32 [rows, O]; acc_dump (optional) int32 [rows, O, NG] is filled in place."""
+               stream=None, workspace=None):
+    """Returns y fp32 [rows, O]; acc_dump (optional) int32 [rows, O, NG] is filled in place.
+    workspace: uint8 device tensor of dgq_linear_workspace_bytes() bytes (nibble-packed weights)."""
     import torch
     _dev(codes, torch.int8, "codes")
     _dev(row_class, torch.uint8, "row_class")
@@ -348,8 +364,12 @@ def dgq_linear(groups: Groups, weight: Weight, codes, row_class, y=None, acc_dum
         _dev(acc_dump, torch.int32, "acc_dump")
         if tuple(acc_dump.shape) != (rows, O, groups.info.n_groups):
             raise ValueError("acc_dump has the wrong shape")
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        _dev(workspace, torch.uint8, "workspace")
+        ws_ptr, ws_bytes = _ptr(workspace), workspace.numel()
     _check(lib().dgq_linear(groups.handle, weight.handle, _ptr(codes), _ptr(row_class), rows,
-                            _ptr(y), _ptr(acc_dump), None, 0, _stream(stream)))
+                            _ptr(y), _ptr(acc_dump), ws_ptr, ws_bytes, _stream(stream)))
     return y
 
 

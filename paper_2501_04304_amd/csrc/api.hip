@@ -256,6 +256,7 @@ void release(Weight *w) {
     if (!w) return;
     release(const_cast<Groups *>(w->groups));
     (void)hipFree(w->d_wq);
+    (void)hipFree(w->d_wq4);
     (void)hipFree(w->d_sw);
     (void)hipFree(w->d_zb);
     (void)hipFree(w->d_rq_zi);
@@ -704,6 +705,7 @@ int dgq_linear_conv3x3(const dgq_groups_t *h9, const dgq_weight_t *hw, const int
     if (g9->conv_taps != 9) return fail(DGQ_ESHAPE, "dgq_linear_conv3x3: the handle does not come from dgq_groups_for_conv3x3");
     if (w->groups != g9) return fail(DGQ_ESHAPE, "dgq_linear_conv3x3: weight was packed for a different group handle");
     if (w->next_kp) return fail(DGQ_ESHAPE, "dgq_linear_conv3x3: weight was packed for dgq_linear_geglu_requant");
+    if (w->d_wq4) return fail(DGQ_EUNSUPPORTED, "dgq_linear_conv3x3: nibble-packed weights are taken by dgq_linear only");
     if (W % (g9->info.act_bits == 8 ? 16 : 32))
         return fail(DGQ_EUNSUPPORTED, "dgq_linear_conv3x3: the image width must be a multiple of 16 (8-bit codes) or 32 (4-bit codes)");
     if (!aligned16(codes3) || !aligned16(y)) return fail(DGQ_EALIGN, "dgq_linear_conv3x3: tensor not 16-byte aligned");
@@ -852,16 +854,57 @@ int dgq_weight_tables(const dgq_weight_t *h, int8_t *wq, float *sw) {
         return fail(DGQ_EUNSUPPORTED, "dgq_weight_tables: rows of a weight packed for a following layer are not in the original order");
     if (sw) DGQ_HIP(hipMemcpy(sw, w->d_sw, sizeof(float) * w->O, hipMemcpyDeviceToHost));
     if (wq) {
-        DevBuf tmp;
+        DevBuf tmp, wide;
         const size_t bytes = (size_t)w->O * w->C;
         DGQ_HIP(tmp.alloc(bytes));
         DGQ_HIP(hipMemset(tmp.p, 0, bytes));
-        DGQ_HIP(launch_unpack_weight(w->d_wq, w->O, w->C, w->Kp, w->groups->d_perm,
+        const int8_t *src = w->d_wq;
+        if (w->d_wq4) {  // two weights per byte: widen into a temporary first
+            const int64_t n8 = (int64_t)w->O_pad * w->Kp;
+            DGQ_HIP(wide.alloc((size_t)n8));
+            DGQ_HIP(launch_expand_nibbles(w->d_wq4, wide.as<int8_t>(), n8, nullptr));
+            src = wide.as<int8_t>();
+        }
+        DGQ_HIP(launch_unpack_weight(src, w->O, w->C, w->Kp, w->groups->d_perm,
                                      tmp.as<int8_t>(), nullptr));
         DGQ_HIP(hipDeviceSynchronize());
         DGQ_HIP(hipMemcpy(wq, tmp.p, bytes, hipMemcpyDeviceToHost));
     }
     return DGQ_OK;
+}
+
+int dgq_weight_pack_nibbles(dgq_weight_t *h, void *stream) {
+    if (!h) return fail(DGQ_EINVAL, "dgq_weight_pack_nibbles: null handle");
+    Weight *w = reinterpret_cast<Weight *>(h);
+    if (w->d_wq4) return fail(DGQ_ESHAPE, "dgq_weight_pack_nibbles: the handle is already nibble-packed");
+    if (w->w_bits != 4)
+        return fail(DGQ_EUNSUPPORTED, "dgq_weight_pack_nibbles: the weights were quantized to 8 bits");
+    if (w->next_kp)
+        return fail(DGQ_EUNSUPPORTED, "dgq_weight_pack_nibbles: handles of dgq_pack_weight_gated_for feed "
+                                      "dgq_linear_geglu_requant, which takes one weight per byte");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n8 = (int64_t)w->O_pad * w->Kp;  // O_pad and K' are multiples of 64
+    uint8_t *p4 = nullptr;
+    DGQ_HIP(hipMalloc(reinterpret_cast<void **>(&p4), (size_t)(n8 / 2)));
+    hipError_t e = launch_pack_nibbles(w->d_wq, p4, n8, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+        (void)hipFree(p4);
+        return hip_fail(e, "dgq_weight_pack_nibbles");
+    }
+    (void)hipFree(w->d_wq);
+    w->d_wq = nullptr;
+    w->d_wq4 = p4;
+    return DGQ_OK;
+}
+
+size_t dgq_weight_device_bytes(const dgq_weight_t *h) {
+    if (!h) return 0;
+    const Weight *w = reinterpret_cast<const Weight *>(h);
+    const size_t n8 = (size_t)w->O_pad * w->Kp;
+    size_t b = (w->d_wq4 ? n8 / 2 : n8) + sizeof(float) * 3 * (size_t)w->O_pad;
+    if (w->next_kp) b += sizeof(float2) * (size_t)(w->next_kp / kGranule) + (size_t)w->next_kp;
+    return b;
 }
 
 void dgq_weight_free(dgq_weight_t *h) {
@@ -889,13 +932,15 @@ size_t dgq_codes_bytes(const dgq_groups_t *h, int64_t rows) {
     return (size_t)((rows + block_rows - 1) / block_rows) * (size_t)g->n_chunks * 1024;
 }
 
-size_t dgq_linear_workspace_bytes(const dgq_groups_t *, const dgq_weight_t *, int64_t) { return 0; }
+size_t dgq_linear_workspace_bytes(const dgq_groups_t *, const dgq_weight_t *hw, int64_t) {
+    if (!hw) return 0;
+    const Weight *w = reinterpret_cast<const Weight *>(hw);
+    return w->d_wq4 ? (size_t)w->O_pad * w->Kp : 0;  // the weights at one byte each
+}
 
 int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *codes,
                const uint8_t *row_class, int64_t rows, float *y, int32_t *acc_dump, void *workspace,
                size_t workspace_bytes, void *stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!h || !hw || !codes || !row_class || !y) return fail(DGQ_EINVAL, "dgq_linear: null pointer");
     if (rows < 1) return fail(DGQ_EINVAL, "dgq_linear: rows < 1");
     const Groups *g = reinterpret_cast<const Groups *>(h);
@@ -910,6 +955,21 @@ int dgq_linear(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t *code
         return fail(DGQ_EUNSUPPORTED, "dgq_linear: acc_dump needs at most two pixel classes");
     if (w->next_kp)
         return fail(DGQ_ESHAPE, "dgq_linear: weight was packed for dgq_linear_geglu_requant");
+    if (w->d_wq4) {
+        // two weights per byte at rest: widened into the caller's workspace, then the
+        // contraction as for any other handle
+        const size_t need = (size_t)w->O_pad * w->Kp;
+        if (!workspace || workspace_bytes < need)
+            return fail(DGQ_EWORKSPACE, "dgq_linear: nibble-packed weights need a workspace of dgq_linear_workspace_bytes()");
+        if (!aligned16(workspace)) return fail(DGQ_EALIGN, "dgq_linear: workspace not 16-byte aligned");
+        DGQ_HIP(launch_expand_nibbles(w->d_wq4, static_cast<int8_t *>(workspace), (int64_t)need,
+                                      static_cast<hipStream_t>(stream)));
+        Weight wide = *w;
+        wide.d_wq = static_cast<int8_t *>(workspace);
+        DGQ_HIP(launch_linear(*g, wide, codes, row_class, rows, y, acc_dump, 0, nullptr,
+                              static_cast<hipStream_t>(stream)));
+        return DGQ_OK;
+    }
     DGQ_HIP(launch_linear(*g, *w, codes, row_class, rows, y, acc_dump, 0, nullptr,
                           static_cast<hipStream_t>(stream)));
     return DGQ_OK;
@@ -926,6 +986,8 @@ int dgq_linear_geglu(const dgq_groups_t *h, const dgq_weight_t *hw, const int8_t
         return fail(DGQ_ESHAPE, "dgq_linear_geglu: weight was packed for a different group handle");
     if (w->next_kp)
         return fail(DGQ_ESHAPE, "dgq_linear_geglu: weight was packed for dgq_linear_geglu_requant");
+    if (w->d_wq4)
+        return fail(DGQ_EUNSUPPORTED, "dgq_linear_geglu: nibble-packed weights are taken by dgq_linear only");
     if (w->O % 256 != 0)
         return fail(DGQ_EUNSUPPORTED,
                     "dgq_linear_geglu: out_channels must be a multiple of 256 (value and gate "

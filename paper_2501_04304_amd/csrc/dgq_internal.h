@@ -77,6 +77,9 @@ struct Weight {
     const Groups *groups = nullptr;
     int32_t O = 0, O_pad = 0, C = 0, Kp = 0, w_bits = 8;
     int8_t *d_wq = nullptr;  // [O_pad x K'] permuted + padded rows, block-tiled (64 B per row)
+    // the same buffer at two 4-bit weights per byte (byte i = weights 2i and 2i + 1 of d_wq,
+    // low nibble first); d_wq is null while this is set
+    uint8_t *d_wq4 = nullptr;
     float *d_sw = nullptr;   // [O_pad]
     // [2][O_pad].  Two class rows: zb[p][o].  More than two classes (one channel group):
     // row 0 = sw[o] * sum_j wq[o,j], row 1 = bias[o]; zb[p][o] = zoff[p] * row 0 + row 1.
@@ -142,6 +145,11 @@ hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int3
                               const int32_t *gchunk, const float *s, const float *z,
                               int32_t n_classes, const int32_t *row_map, int8_t *wq, float *sw,
                               float *zb, hipStream_t st);
+
+// Two 4-bit weights per byte and back (n_bytes8: size of the one-byte-per-weight buffer, a
+// multiple of 32).
+hipError_t launch_pack_nibbles(const int8_t *wq, uint8_t *wq4, int64_t n_bytes8, hipStream_t st);
+hipError_t launch_expand_nibbles(const uint8_t *wq4, int8_t *wq, int64_t n_bytes8, hipStream_t st);
 
 // Inverse of the K' layout: wq_out [O][C] original order.
 hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t Kp,

@@ -203,6 +203,66 @@ hipError_t launch_pack_weight(const float *w, const float *bias, int32_t O, int3
     return hipGetLastError();
 }
 
+// Two signed 4-bit weights per byte.  A thread converts 32 weights: 16 packed bytes <-> 32.
+__global__ __launch_bounds__(256) void k_pack_nibbles(const int8_t *__restrict__ wq,
+                                                      uint8_t *__restrict__ wq4, int64_t n16) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n16) return;
+    const uint4 a = reinterpret_cast<const uint4 *>(wq)[2 * i];
+    const uint4 b = reinterpret_cast<const uint4 *>(wq)[2 * i + 1];
+    // bytes (w0 w1 w2 w3) of a dword pair -> (w0 | w1 << 4, w2 | w3 << 4, ...)
+    auto two = [](uint32_t lo, uint32_t hi) {
+        auto half = [](uint32_t x) {  // four weights -> two packed bytes
+            const uint32_t n = x & 0x0f0f0f0fu;
+            return ((n | (n >> 4)) & 0xffu) | (((n >> 16) | (n >> 20)) & 0xffu) << 8;
+        };
+        return half(lo) | (half(hi) << 16);
+    };
+    uint4 r;
+    r.x = two(a.x, a.y);
+    r.y = two(a.z, a.w);
+    r.z = two(b.x, b.y);
+    r.w = two(b.z, b.w);
+    reinterpret_cast<uint4 *>(wq4)[i] = r;
+}
+
+__global__ __launch_bounds__(256) void k_expand_nibbles(const uint8_t *__restrict__ wq4,
+                                                        int8_t *__restrict__ wq, int64_t n16) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n16) return;
+    const uint4 p = reinterpret_cast<const uint4 *>(wq4)[i];
+    // two packed bytes -> four sign-extended weights: spread the nibbles over the bytes,
+    // then (n ^ 8) - 8 in every byte without a borrow between bytes: the +0x80 keeps each
+    // byte's subtraction from borrowing and is taken out again by the final xor
+    auto four = [](uint32_t h) {  // h: 16 bits = four nibbles
+        const uint32_t n = (h & 0xfu) | ((h & 0xf0u) << 4) | ((h & 0xf00u) << 8) | ((h & 0xf000u) << 12);
+        return (((n ^ 0x88888888u) - 0x08080808u) ^ 0x80808080u);
+    };
+    uint4 a, b;
+    a.x = four(p.x & 0xffffu);
+    a.y = four(p.x >> 16);
+    a.z = four(p.y & 0xffffu);
+    a.w = four(p.y >> 16);
+    b.x = four(p.z & 0xffffu);
+    b.y = four(p.z >> 16);
+    b.z = four(p.w & 0xffffu);
+    b.w = four(p.w >> 16);
+    reinterpret_cast<uint4 *>(wq)[2 * i] = a;
+    reinterpret_cast<uint4 *>(wq)[2 * i + 1] = b;
+}
+
+hipError_t launch_pack_nibbles(const int8_t *wq, uint8_t *wq4, int64_t n_bytes8, hipStream_t st) {
+    const int64_t n16 = n_bytes8 / 32;
+    hipLaunchKernelGGL(k_pack_nibbles, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, wq, wq4, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_nibbles(const uint8_t *wq4, int8_t *wq, int64_t n_bytes8, hipStream_t st) {
+    const int64_t n16 = n_bytes8 / 32;
+    hipLaunchKernelGGL(k_expand_nibbles, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, wq4, wq, n16);
+    return hipGetLastError();
+}
+
 hipError_t launch_unpack_weight(const int8_t *wq, int32_t O, int32_t C, int32_t Kp,
                                 const int32_t *perm, int8_t *wq_out, hipStream_t st) {
     hipLaunchKernelGGL(k_unpack_weight, dim3(O), dim3(256), 0, st, wq, O, C, Kp, perm, wq_out);

@@ -58,6 +58,11 @@ def test_argument_errors_without_gpu(lib):
     assert lib.dgq_conv3x3_codes(None, None, 1, 4, 4, None, None) == -1
     assert lib.dgq_quantize_act_conv3x3(None, None, None, 1, 4, 16, None, None, None) == -1
     assert lib.dgq_linear_conv3x3(None, None, None, None, 1, 4, 16, None, None) == -1
+    assert lib.dgq_weight_pack_nibbles(None, None) == -1
+    lib.dgq_weight_device_bytes.restype = C.c_size_t
+    assert lib.dgq_weight_device_bytes(None) == 0
+    lib.dgq_linear_workspace_bytes.restype = C.c_size_t
+    assert lib.dgq_linear_workspace_bytes(None, None, 4) == 0
     h = C.c_void_p()
     assert lib.dgq_calibrate_groups(None, 4, 64, 8, 64, 2, None, C.byref(h)) == -1
     buf = (C.c_float * 64)()

@@ -201,3 +201,66 @@ def test_error_paths(dgq):
                                               cls.data_ptr(), None))
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("ab", [8, 4])
+@pytest.mark.parametrize("shape", [(2, 128, 320, 192, 64), (3, 333, 640, 200, 128), (4, 4096, 640, 1280, 128)])
+def test_nibble_packed_weights(dgq, oracle, ab, shape):
+    """4-bit weights stored two per byte: the same result, bit for bit, as the handle that
+    keeps one weight per byte (which the tests above hold to the oracle), half the weight
+    bytes, and the oracle's integer weights read back from the packed form."""
+    import torch
+    B, N, C, O, G = shape
+    run = di.linear_case(9100 + C + O, B, N, C, O)
+    cal = di.linear_case(9100 + C + O, min(B, 2), N, C, O, calib=True)
+    og = oracle.calibrate(cal["X"], ab, G, 2)
+    gg = dgq.dgq_calibrate_groups(_dev(cal["X"]), ab, G, 2)
+    w = _dev(run["W"])
+    bias = _dev(np.linspace(-1, 1, O).astype(np.float32))
+    codes, cls = dgq.dgq_quantize_act(gg, _dev(run["X"]))
+    wide = dgq.dgq_pack_weight(gg, w, bias, 4)
+    packed = dgq.dgq_pack_weight(gg, w, bias, 4)
+    b_wide = packed.device_bytes()
+    assert dgq.dgq_linear_workspace_bytes(gg, packed, B * N) == 0
+    packed.pack_nibbles()
+    o_pad = (O + 127) // 128 * 128
+    assert b_wide == o_pad * og.Kp + 12 * o_pad
+    assert packed.device_bytes() == o_pad * og.Kp // 2 + 12 * o_pad
+    need = dgq.dgq_linear_workspace_bytes(gg, packed, B * N)
+    assert need == o_pad * og.Kp
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    y0 = dgq.dgq_linear(gg, wide, codes, cls)
+    y1 = dgq.dgq_linear(gg, packed, codes, cls, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    # against the oracle directly, too (sampled rows on the large case)
+    owq, osw = oracle.quantize_weight(run["W"], 4)
+    t = packed.tables()
+    assert np.array_equal(t["wq"], owq) and np.array_equal(t["sw"], osw)
+    rows = B * N
+    sel = np.arange(rows) if rows <= 2048 else tile_rows(rows, 5)
+    oq = oracle.quantize_act(og, run["X"][sel])
+    oy, _ = oracle.linear(og, oq["q"], oq["cls"], owq, osw, np.linspace(-1, 1, O).astype(np.float32))
+    assert_close_fp32(y1[torch.from_numpy(sel).cuda()].cpu().numpy(), oy, "y")
+    # a second call through the same workspace (another layer would reuse it)
+    y2 = dgq.dgq_linear(gg, packed, codes, cls, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y2)
+    # error paths: no or short workspace, other entry points, 8-bit weights, twice
+    with pytest.raises(dgq.DgqError) as e:
+        dgq.dgq_linear(gg, packed, codes, cls)
+    assert e.value.code == -6
+    with pytest.raises(dgq.DgqError) as e:
+        dgq.dgq_linear(gg, packed, codes, cls, workspace=ws[:need - 16])
+    assert e.value.code == -6
+    with pytest.raises(dgq.DgqError) as e:
+        packed.pack_nibbles()
+    assert e.value.code == -3
+    if O % 256 == 0:
+        with pytest.raises(dgq.DgqError) as e:
+            dgq.dgq_linear_geglu(gg, packed, codes, cls)
+        assert e.value.code == -4
+    w8 = dgq.dgq_pack_weight(gg, w, None, 8)
+    with pytest.raises(dgq.DgqError) as e:
+        w8.pack_nibbles()
+    assert e.value.code == -4
