@@ -338,10 +338,7 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
 #pragma unroll
         for (int b = 0; b < BO; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                facc[a][b][i] = 0.0f;
-                acc[a][b][i] = 0;
-            }
+            for (int i = 0; i < 16; ++i) facc[a][b][i] = 0.0f;
     // fresh: the group's first k-step starts from C = 0 (no register clearing)
     auto mfma_all = [&](const v4i (&af)[BR], const v4i (&bf)[BO], bool fresh) {
         if (fresh) {
@@ -666,6 +663,12 @@ __global__ __launch_bounds__(CF::THREADS, CF::OCC) void k_linear(
         // the wave's class when it is uniform
         const int32_t p = MULTI ? (MIXED ? 0 : c_first) : ((!MIXED && any1) ? 1 : 0);
         v4i af0[BR], bf0[BO], af1[BR], bf1[BO];
+        // The int32 blocks are not cleared (a group's first MFMA starts from C = 0): the empty
+        // asm statement only tells the compiler that the registers hold a value.
+#pragma unroll
+        for (int a = 0; a < BR; ++a)
+#pragma unroll
+            for (int b = 0; b < BO; ++b) asm volatile("" : "=v"(acc[a][b]));
         load_frags(lds, 0, af0, bf0);
         const float *s_p = tab_s + p * NG;  // MULTI: NG == 1, so s_p[0] is class p's scale
         int32_t g = 0;
