@@ -142,7 +142,7 @@ __device__ __host__ constexpr int key_of(int blk, int i, int hh) {
 }
 
 template <class CF, int PASS, bool DUMP>
-__global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 2 : CF::WAVES_PER_SIMD) void k_xattn_mfma(
+__global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 2 : CF::WAVES_PER_SIMD) void k_xattn_mfma(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
     float qk_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
@@ -168,7 +168,9 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
     const int32_t bx = REV ? (int32_t)(gridDim.x - 1 - blockIdx.x) : (int32_t)blockIdx.x;
     const int32_t b = REV ? (int32_t)(gridDim.z - 1 - blockIdx.z) : (int32_t)blockIdx.z;
     const int32_t head = REV ? (int32_t)(gridDim.y - 1 - blockIdx.y) : (int32_t)blockIdx.y;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    // the wave index is uniform: say so, and the query block, its row pointers and the
+    // loop bounds derived from it live in scalar registers
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
     const int64_t hs = (int64_t)H * d;  // stride between tokens
 
@@ -181,6 +183,48 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
         pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;
         l2s = __log2f(s_eff);
     }
+
+    const int32_t q_begin = bx * qpw;
+    const int32_t q_end = min(q_begin + qpw, N);
+    const float *qbase = q + ((int64_t)b * N * H + head) * d;
+
+    // raw fp32 query slices of this lane: dims 16 s + 8 hh .. + 7 of query qi
+    struct QRaw {
+        float4 x[KS][2];
+        float lse;
+    };
+    // Only the last 16-dimension step can reach past the head dimension (d > 16 (KS - 1),
+    // d % 8 == 0): its slice is clamped (K is zero in LDS there, any finite value will
+    // do); the others sit at fixed distances from one per-lane pointer.
+    const int32_t t_last = min(16 * (KS - 1) + 8 * hh, d - 8) - 8 * hh;
+    // Addresses are a uniform block pointer (scalar registers) plus a 32-bit lane offset:
+    // 64-bit pointers per lane cost two registers each, and this loop has none to spare.
+    const float *lse_base = lse2 + ((int64_t)b * H + head) * N;
+    auto load_q = [&](int32_t q0) {
+        QRaw r;
+        const int32_t q0c = min(q0, N - 1);                      // uniform
+        const int32_t rl = min(n, N - 1 - q0c);                   // a row past the end re-reads the last one
+        const char *blk = reinterpret_cast<const char *>(qbase + (int64_t)q0c * hs);
+        const uint32_t lo = (uint32_t)(rl * (int32_t)hs + 8 * hh) * 4u;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const uint32_t os = s < KS - 1 ? lo + 64u * s : lo + 4u * (uint32_t)t_last;
+            r.x[s][0] = *reinterpret_cast<const float4 *>(blk + os);
+            r.x[s][1] = *reinterpret_cast<const float4 *>(blk + os + 16);
+        }
+        r.lse = 0.0f;
+        if (PASS == 2)
+            r.lse = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lse_base + q0c) + 4u * (uint32_t)rl);
+        return r;
+    };
+
+    float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
+
+    const int32_t q_first = q_begin + 32 * wave;
+    const int32_t n_it = q_first < q_end ? (q_end - q_first + 32 * kXWaves - 1) / (32 * kXWaves) : 0;
+    auto q_of = [&](int32_t it) { return q_first + (REV ? n_it - 1 - it : it) * (32 * kXWaves); };
+    // the wave's first query block travels while K and V^T are staged
+    QRaw cur = load_q(n_it > 0 ? q_of(0) : q_first);
 
     // ---- stage K (two fp16 pieces), the start values and, in pass 2, V^T ---------------
     {
@@ -224,40 +268,6 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
     }
     __syncthreads();
 
-    const int32_t q_begin = bx * qpw;
-    const int32_t q_end = min(q_begin + qpw, N);
-    const float *qbase = q + ((int64_t)b * N * H + head) * d;
-
-    // raw fp32 query slices of this lane: dims 16 s + 8 hh .. + 7 of query qi
-    struct QRaw {
-        float4 x[KS][2];
-        float lse;
-    };
-    // Only the last 16-dimension step can reach past the head dimension (d > 16 (KS - 1),
-    // d % 8 == 0): its slice is clamped (K is zero in LDS there, any finite value will
-    // do); the others sit at fixed distances from one per-lane pointer.
-    const int32_t t_last = min(16 * (KS - 1) + 8 * hh, d - 8) - 8 * hh;
-    auto load_q = [&](int32_t q0) {
-        QRaw r;
-        const int32_t qi = min(q0 + n, N - 1);
-        const float *p = qbase + (int64_t)qi * hs + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const float *ps = s < KS - 1 ? p + 16 * s : p + t_last;
-            r.x[s][0] = *reinterpret_cast<const float4 *>(ps);
-            r.x[s][1] = *reinterpret_cast<const float4 *>(ps + 4);
-        }
-        r.lse = 0.0f;
-        if (PASS == 2) r.lse = lse2[((int64_t)b * H + head) * N + qi];
-        return r;
-    };
-
-    float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
-
-    const int32_t q_first = q_begin + 32 * wave;
-    const int32_t n_it = q_first < q_end ? (q_end - q_first + 32 * kXWaves - 1) / (32 * kXWaves) : 0;
-    auto q_of = [&](int32_t it) { return q_first + (REV ? n_it - 1 - it : it) * (32 * kXWaves); };
-    QRaw cur = load_q(n_it > 0 ? q_of(0) : q_first);
     for (int32_t it = 0; it < n_it; ++it) {
         const int32_t q0 = q_of(it);
         const int32_t qi = q0 + n;
@@ -325,6 +335,10 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
         // product above: the split query is dead now and the raw one takes its registers;
         // issued earlier the two overlap, registers spill, and every reload of a spilled
         // value waits for ALL outstanding vector memory, i.e. for this very prefetch.
+        // (Passes 2 and 3 are built for two waves per SIMD: at four, 128 registers do not
+        // hold the 48 logits, the packed codes and the prefetched query together, and the
+        // reloads' waits, which cover all outstanding vector memory, undo the prefetch:
+        // 105 us against 77 us for pass 2 on 16 x 10 x 4096 x 64.)
         {
             int32_t qn = it + 1 < n_it ? q_of(it + 1) : q0;
             asm volatile("" : "+v"(qn) : "v"(sm[NKB - 1][15]));  // not before the last MFMA
@@ -416,9 +430,15 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
             if (hh == 1) pk[NKB - 1][7] = (a2 >> 16) | a3;  // key slots NKP-2 and NKP-1
         }
 
-        // ---- Out^T = V^T P^T, one block of 32 output dimensions after the other (both at once
-        // would hold 32 more accumulator registers than the file has left) ----------------
-        float *orow = out + ((int64_t)b * N * H + head) * d + (int64_t)qi * hs;
+        // ---- Out = P V, one block of 32 output dimensions after the other (both at once would
+        // hold 32 more accumulator registers than the file has left).  The probabilities are
+        // the A operand (a lane's registers are its query's row of P) and V^T's rows the B
+        // operand, so that a lane of the result holds ONE output dimension of sixteen queries:
+        // a store instruction then writes 128 contiguous bytes of each of two rows.  (With
+        // the operands the other way round a lane held four dimensions of one query, every
+        // store touched 32 rows 32 bytes at a time, and the stores cost a third of the call.)
+        float *oblk = out + ((int64_t)b * N * H + head) * d + (int64_t)q0 * hs;  // uniform
+        const uint32_t o_lane = (uint32_t)(4 * hh * hs + n) * 4u;  // row 4 hh, dimension n
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             v16f o;
@@ -447,19 +467,27 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
                 pb.z = pk[s16 >> 1][4 * (s16 & 1) + 2];
                 pb.w = pk[s16 >> 1][4 * (s16 & 1) + 3];
                 const v8bf bp = __builtin_bit_cast(v8bf, pb);
-                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vh[s16 & 1]), bp, o, 0, 0, 0);
-                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vl[s16 & 1]), bp, o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bp, __builtin_bit_cast(v8bf, vh[s16 & 1]), o, 0, 0, 0);
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bp, __builtin_bit_cast(v8bf, vl[s16 & 1]), o, 0, 0, 0);
             }
+            // register i: query q0 + 8 (i / 4) + 4 hh + i % 4, dimension 32 db + n
+            if (q0 + 32 <= N && 32 * db + 32 <= d) {
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int dim = 32 * db + 8 * a + 4 * hh;
-                if (valid && dim < d) {
-                    float4 t;
-                    t.x = o[4 * a + 0];
-                    t.y = o[4 * a + 1];
-                    t.z = o[4 * a + 2];
-                    t.w = o[4 * a + 3];
-                    *reinterpret_cast<float4 *>(orow + dim) = t;
+                for (int i = 0; i < 16; ++i) {
+                    char *rowp = reinterpret_cast<char *>(oblk + (int64_t)(8 * (i >> 2) + (i & 3)) * hs + 32 * db);
+                    *reinterpret_cast<float *>(rowp + o_lane) = o[i];
+                }
+            } else {
+                // the last query block of a (prompt, head) pair or a head dimension that ends inside
+                // this block: every element predicated.  The opaque copy keeps the sixteen
+                // addresses from being computed (and spilled) ahead of the loop.
+                int32_t rows_left = N - q0;
+                int64_t hs_here = hs;
+                asm volatile("" : "+s"(rows_left), "+s"(hs_here));
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int32_t rl = 8 * (i >> 2) + 4 * hh + (i & 3);
+                    if (rl < rows_left && 32 * db + n < d) oblk[(int64_t)rl * hs_here + 32 * db + n] = o[i];
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -481,6 +509,9 @@ __global__ __launch_bounds__(kXThreads, (PASS == 3 && CF::WAVES_PER_SIMD > 2) ? 
     }
 }
 
+// Workgroup slots the kernels that write the product are cut for (they run one workgroup per CU).
+constexpr int kTargetWgs2 = 512;
+
 template <class CF>
 hipError_t launch_mfma(const float *q, const float *k, const float *v, const float *key_bias,
                        int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
@@ -497,16 +528,18 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     // a (prompt, head) pair is cut into as few pieces as still give every workgroup slot
     // of the chip (two per CU) something to do.
     constexpr int kPerTrip = 32 * kXWaves;
-    int target_wgs = 512;
-#ifdef DGQ_TUNING  // tuning builds only: the slot count
-    if (const int v = tuning_value(kTuneXattnWgs); v > 0) target_wgs = v;
+    auto queries_per_wg = [&](int target_wgs) {
+        int64_t pieces = target_wgs / ((int64_t)B * H);
+        pieces = pieces < 1 ? 1 : pieces;
+        int64_t per_piece = (N + pieces - 1) / pieces;
+        return (int32_t)((per_piece + kPerTrip - 1) / kPerTrip * kPerTrip);
+    };
+    int target_wgs = 512, target_wgs2 = kTargetWgs2;
+#ifdef DGQ_TUNING  // tuning builds only: the slot count of the second (or only) kernel
+    if (const int v = tuning_value(kTuneXattnWgs); v > 0) target_wgs2 = v;
 #endif
-    int64_t pieces = target_wgs / ((int64_t)B * H);
-    pieces = pieces < 1 ? 1 : pieces;
-    int64_t per_piece = (N + pieces - 1) / pieces;
-    per_piece = (per_piece + kPerTrip - 1) / kPerTrip * kPerTrip;
-    const int32_t qpw = (int32_t)per_piece;
-    const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B);
+    const int32_t qpw = queries_per_wg(target_wgs), qpw2 = queries_per_wg(target_wgs2);
+    const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B), grid2((unsigned)((N + qpw2 - 1) / qpw2), H, B);
     const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
     if (scale_in) {  // given scale: one kernel, Q read once
         auto k3 = codes_dump ? k_xattn_mfma<CF, 3, true> : k_xattn_mfma<CF, 3, false>;
@@ -515,15 +548,15 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
         if (e != hipSuccess) return e;
         if (scale_out)
             hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
-        hipLaunchKernelGGL(k3, grid, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d,
-                           nk, bits, qk_scale, qpw, out, scale_out, nullptr, codes_dump, scale_in);
+        hipLaunchKernelGGL(k3, grid2, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d,
+                           nk, bits, qk_scale, qpw2, out, scale_out, nullptr, codes_dump, scale_in);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
     hipLaunchKernelGGL(k1, grid, dim3(kXThreads), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
                        bits, qk_scale, qpw, out, scale_out, lse2, codes_dump, nullptr);
-    hipLaunchKernelGGL(k2, grid, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump, nullptr);
+    hipLaunchKernelGGL(k2, grid2, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
+                       bits, qk_scale, qpw2, out, scale_out, lse2, codes_dump, nullptr);
     return hipGetLastError();
 }
 
