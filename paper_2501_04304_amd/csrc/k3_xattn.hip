@@ -34,11 +34,15 @@
 // max_{j>=1} 2^(S_ij - lse2_i) into scale_out[b].  Pass 2 recomputes S^T the
 // same way (bit-identical), turns each register into its code, and builds
 // 2^-code directly as a bf16 bit pattern (an exact power of two).  The
-// accumulator layout of S^T is, register for register, the B-operand layout of
-// the next product Out^T = V^T P^T (v_mfma_f32_32x32x16_bf16) once the key order
-// inside each 16-key step is permuted the same way on the V^T side, so the
-// probabilities never leave the registers.  V is split into two bf16 pieces
-// (2^-17 relative).  The <start> column is carried through the same product:
+// accumulator layout of S^T is, register for register, an operand layout of the
+// next product (v_mfma_f32_32x32x16_bf16: a lane supplies eight keys of its
+// query, as the A and the B operand alike) once the key order inside each 16-key
+// step is permuted the same way on the V^T side, so the probabilities never
+// leave the registers.  They go in as the A operand, Out = P V: a lane of the
+// result then holds one output dimension of sixteen queries and a store writes
+// 128 contiguous bytes per row (as the B operand, Out^T = V^T P^T, every store
+// touched 32 rows 32 bytes at a time and the stores cost a third of the call).
+// V is split into two bf16 pieces (2^-17 relative).  The <start> column is carried through the same product:
 // a' = A_i0 / s_b, split into three bf16 pieces (24 bits), occupies key slot 0
 // and the last two padding slots, whose V^T columns hold V_0.  The result is
 // multiplied by s_b on the way out.
@@ -118,8 +122,13 @@ __device__ inline HiLo split_h2(float a, float b) {
     // this opaque copy the compiler converts twice, with the packed and with the scalar
     // instruction, and the two do not round alike next to a tie, which breaks hi + lo = x.
     asm("" : "+v"(r.hi));
-    const v2h hr = __builtin_bit_cast(v2h, r.hi);
-    r.lo = pack_h2(fmaf((float)hr.x, -1.0f, a), fmaf((float)hr.y, -1.0f, b));
+    // a - float(hi.x), b - float(hi.y): the mixed-precision multiply-add reads the fp16 halves
+    // directly (one instruction each instead of a conversion and a subtraction; the result is
+    // the same exactly rounded difference)
+    float la, lb;
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(la) : "v"(r.hi), "v"(a));
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(lb) : "v"(r.hi), "v"(b));
+    r.lo = pack_h2(la, lb);
     return r;
 }
 
@@ -145,7 +154,7 @@ template <class CF, int PASS, bool DUMP>
 __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 2 : CF::WAVES_PER_SIMD) void k_xattn_mfma(
     const float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
-    float qk_scale, int32_t qpw, float *__restrict__ out, float *__restrict__ scale,
+    float qk_scale, int32_t trips_per_wg, int32_t n_pairs, float *__restrict__ out, float *__restrict__ scale,
     float *__restrict__ lse2, uint8_t *__restrict__ codes_dump,
     const float *__restrict__ scale_in) {
     // PASS 3: both passes in one, for a prompt scale that is GIVEN (scale_in): the soft-max
@@ -161,18 +170,28 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
     uint16_t *Vl = Vh + DP * VROW;
     __shared__ float red[kXWaves];
 
-    // (Walking pass 2 in the reverse of pass 1's order, workgroups and query blocks alike, so
-    // that it meets the rows of Q pass 1 read last while they might still sit in the memory-side
-    // cache, was measured: 5 % slower.  REV stays as a switch.)
-    constexpr bool REV = false;
-    const int32_t bx = REV ? (int32_t)(gridDim.x - 1 - blockIdx.x) : (int32_t)blockIdx.x;
-    const int32_t b = REV ? (int32_t)(gridDim.z - 1 - blockIdx.z) : (int32_t)blockIdx.z;
-    const int32_t head = REV ? (int32_t)(gridDim.y - 1 - blockIdx.y) : (int32_t)blockIdx.y;
     // the wave index is uniform: say so, and the query block, its row pointers and the
     // loop bounds derived from it live in scalar registers
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
     const int64_t hs = (int64_t)H * d;  // stride between tokens
+
+    // Work is counted in trips: one trip = the workgroup's eight waves taking 32 queries each of
+    // one (prompt, head) pair.  The trips of all pairs, in order, are cut into equal ranges,
+    // one per workgroup, so that every workgroup slot of the chip carries the same load (cut
+    // per pair, the pieces of 4096 queries come out as 6 + 6 + 4 trips and the kernel waits for
+    // the long ones with a third of its slots idle).  A range that crosses into the next pair
+    // stages that pair's K and V^T again.
+    const int32_t trips_per_pair = (N + 32 * kXWaves - 1) / (32 * kXWaves);
+    const int32_t total_trips = n_pairs * trips_per_pair;
+    int32_t trip = (int32_t)blockIdx.x * trips_per_wg;
+    const int32_t trip_end = min(trip + trips_per_wg, total_trips);
+    for (bool first_pair = true; trip < trip_end; first_pair = false) {
+    const int32_t pair = trip / trips_per_pair, trip0 = trip - pair * trips_per_pair;
+    const int32_t n_trips = min(trip_end - trip, trips_per_pair - trip0);
+    const int32_t b = pair / H, head = pair - b * H;
+    trip += n_trips;
+    if (!first_pair) __syncthreads();  // every wave is done with the previous pair's K and V^T
 
     float s_b = 0.0f, s_eff = 1.0f, l2s = 0.0f;
     uint32_t pmask = 0xFFFFFFFFu;
@@ -184,8 +203,8 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
         l2s = __log2f(s_eff);
     }
 
-    const int32_t q_begin = bx * qpw;
-    const int32_t q_end = min(q_begin + qpw, N);
+    const int32_t q_begin = trip0 * (32 * kXWaves);
+    const int32_t q_end = min(q_begin + n_trips * (32 * kXWaves), N);
     const float *qbase = q + ((int64_t)b * N * H + head) * d;
 
     // raw fp32 query slices of this lane: dims 16 s + 8 hh .. + 7 of query qi
@@ -219,10 +238,15 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
     };
 
     float run_l2 = -INFINITY;  // pass 1: running max of log2 A over this lane's queries
+    // Registers 4 g .. 4 g + 3 of the last key block hold keys 32 (NKB - 1) + 8 g .. + 7 (both lane
+    // halves): with 77 keys in three blocks the upper two groups are padding only (logit -inf,
+    // weight 0), and the statistics and the code generation skip them.
+    const int32_t live4 = min(4, (nk - 32 * (NKB - 1) + 7) >> 3);  // uniform
+    auto live = [&](int blk, int i) { return blk < NKB - 1 || (i >> 2) < live4; };
 
     const int32_t q_first = q_begin + 32 * wave;
     const int32_t n_it = q_first < q_end ? (q_end - q_first + 32 * kXWaves - 1) / (32 * kXWaves) : 0;
-    auto q_of = [&](int32_t it) { return q_first + (REV ? n_it - 1 - it : it) * (32 * kXWaves); };
+    auto q_of = [&](int32_t it) { return q_first + it * (32 * kXWaves); };
     // the wave's first query block travels while K and V^T are staged
     QRaw cur = load_q(n_it > 0 ? q_of(0) : q_first);
 
@@ -353,7 +377,7 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
             for (int blk = 0; blk < NKB; ++blk)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (blk || i) rest = fmaxf(rest, sm[blk][i]);
+                    if ((blk || i) && live(blk, i)) rest = fmaxf(rest, sm[blk][i]);
             const float s00 = sm[0][0];  // key 0 in the lower lane half, key 4 in the upper
             float m = fmaxf(rest, s00);
             float m1 = fmaxf(rest, hh == 0 ? -INFINITY : s00);
@@ -363,7 +387,8 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
 #pragma unroll
             for (int blk = 0; blk < NKB; ++blk)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(sm[blk][i] - m);
+                for (int i = 0; i < 16; ++i)
+                    if (live(blk, i)) sum += __builtin_amdgcn_exp2f(sm[blk][i] - m);
             sum += __shfl_xor(sum, 32, kWave);
             const float lse = m + __log2f(sum);
             if (valid) {
@@ -397,6 +422,10 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
             for (int blk = 0; blk < NKB; ++blk)
 #pragma unroll
                 for (int i = 0; i < 16; i += 2) {
+                    if (!live(blk, i)) {  // padding keys only: V^T is zero there, any weight will do
+                        pk[blk][i >> 1] = 0;
+                        continue;
+                    }
                     int32_t e[2];
 #pragma unroll
                     for (int u = 0; u < 2; ++u) {
@@ -507,10 +536,11 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
                       __float_as_uint(__builtin_amdgcn_exp2f(amax)));
         }
     }
+    }  // pairs of this workgroup's range
 }
 
-// Workgroup slots the kernels that write the product are cut for (they run one workgroup per CU).
-constexpr int kTargetWgs2 = 512;
+// Workgroup slots of the chip for the kernels that write the product (one workgroup per CU).
+constexpr int kTargetWgs2 = 256;
 
 template <class CF>
 hipError_t launch_mfma(const float *q, const float *k, const float *v, const float *key_bias,
@@ -524,22 +554,23 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
     e = codes_dump ? DGQ_ENSURE_LDS((k_xattn_mfma<CF, 2, true>), (int)CF::lds_pass2)
                    : DGQ_ENSURE_LDS((k_xattn_mfma<CF, 2, false>), (int)CF::lds_pass2);
     if (e != hipSuccess) return e;
-    // Queries per workgroup.  Staging K and V costs as much as a few hundred queries, so
-    // a (prompt, head) pair is cut into as few pieces as still give every workgroup slot
-    // of the chip (two per CU) something to do.
+    // Trips (8 x 32 queries of one pair) per workgroup: all trips of the call, in order, in as
+    // many equal ranges as the chip has workgroup slots for the kernel.
     constexpr int kPerTrip = 32 * kXWaves;
-    auto queries_per_wg = [&](int target_wgs) {
-        int64_t pieces = target_wgs / ((int64_t)B * H);
-        pieces = pieces < 1 ? 1 : pieces;
-        int64_t per_piece = (N + pieces - 1) / pieces;
-        return (int32_t)((per_piece + kPerTrip - 1) / kPerTrip * kPerTrip);
-    };
-    int target_wgs = 512, target_wgs2 = kTargetWgs2;
-#ifdef DGQ_TUNING  // tuning builds only: the slot count of the second (or only) kernel
-    if (const int v = tuning_value(kTuneXattnWgs); v > 0) target_wgs2 = v;
+    const int32_t n_pairs = B * H;
+    const int64_t total_trips = (int64_t)n_pairs * ((N + kPerTrip - 1) / kPerTrip);
+    // (pass 1 could hold two workgroups per CU when the head dimension is at most 64; one per CU,
+    // twice as long, measured faster: 114 against 127 us for the call on 16 x 10 x 4096 x 64)
+    int target_wgs = 256, target_wgs2 = kTargetWgs2;
+#ifdef DGQ_TUNING  // tuning builds only: the slot counts (pass 1: 1000 x value)
+    if (const int v = tuning_value(kTuneXattnWgs); v > 0) {
+        if (v % 1000) target_wgs2 = v % 1000 * 8;
+        if (v / 1000) target_wgs = v / 1000 * 8;
+    }
 #endif
-    const int32_t qpw = queries_per_wg(target_wgs), qpw2 = queries_per_wg(target_wgs2);
-    const dim3 grid((unsigned)((N + qpw - 1) / qpw), H, B), grid2((unsigned)((N + qpw2 - 1) / qpw2), H, B);
+    const int32_t tpw = (int32_t)((total_trips + target_wgs - 1) / target_wgs);
+    const int32_t tpw2 = (int32_t)((total_trips + target_wgs2 - 1) / target_wgs2);
+    const dim3 grid((unsigned)((total_trips + tpw - 1) / tpw)), grid2((unsigned)((total_trips + tpw2 - 1) / tpw2));
     const float qk_scale = (float)(1.4426950408889634 / sqrt((double)d));
     if (scale_in) {  // given scale: one kernel, Q read once
         auto k3 = codes_dump ? k_xattn_mfma<CF, 3, true> : k_xattn_mfma<CF, 3, false>;
@@ -549,14 +580,14 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
         if (scale_out)
             hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
         hipLaunchKernelGGL(k3, grid2, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d,
-                           nk, bits, qk_scale, qpw2, out, scale_out, nullptr, codes_dump, scale_in);
+                           nk, bits, qk_scale, tpw2, n_pairs, out, scale_out, nullptr, codes_dump, scale_in);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
     hipLaunchKernelGGL(k1, grid, dim3(kXThreads), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, qpw, out, scale_out, lse2, codes_dump, nullptr);
+                       bits, qk_scale, tpw, n_pairs, out, scale_out, lse2, codes_dump, nullptr);
     hipLaunchKernelGGL(k2, grid2, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, qpw2, out, scale_out, lse2, codes_dump, nullptr);
+                       bits, qk_scale, tpw2, n_pairs, out, scale_out, lse2, codes_dump, nullptr);
     return hipGetLastError();
 }
 
