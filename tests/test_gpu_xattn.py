@@ -91,6 +91,16 @@ def test_guarded_shapes(dgq, oracle, B, N, H, d, nk, bits):
     _compare(dgq, oracle, c, bits, exact=True)
 
 
+@pytest.mark.parametrize("bits", [4, 8])
+def test_workgroup_ranges_cross_pairs(dgq, oracle, bits):
+    """More 256-query trips than CUs and a trip count per (prompt, head) pair that the range
+    length does not divide: workgroups walk from one pair into the next and stage its keys and
+    values again; the last trip of every pair is ragged (2600 = 10 x 256 + 40)."""
+    from oracle.guard import guarded_attention_case
+    c, _ = guarded_attention_case(7700, 5, 2600, 9, 64, bits_list=(bits,))
+    _compare(dgq, oracle, c, bits, exact=True)
+
+
 def test_without_key_bias(dgq, oracle):
     from oracle.guard import guarded_attention_case
     c, _ = guarded_attention_case(11, 2, 96, 2, 40, bits_list=(8,))
