@@ -886,6 +886,11 @@ hipError_t launch_linear(const Groups &g, const Weight &w, const int8_t *codes,
     const int64_t t128 = ((rows + 127) / 128) * ((w.O + 127) / 128);
     const int64_t t64x128 = ((rows + 63) / 64) * ((w.O + 127) / 128);
     int cfg = t128 >= 512 ? 4 : (t64x128 >= 256 ? 2 : 6);
+    // Wide outputs (32 column tiles and more: the first feed-forward projections) run 2-4 % fewer
+    // clocks on 64 x 128 tiles, four workgroups per CU, than on 128 x 128 (measured with the
+    // launch's clock counter on 65536 x 640 -> 5120 and 16384 x 1280 -> 10240, both code widths);
+    // every other large shape is 3-9 % slower there.
+    if (cfg == 4 && !geglu && (w.O + 127) / 128 >= 32) cfg = 2;
 #ifdef DGQ_TUNING  // tuning builds only: a forced tile shape
     if (const int v = tuning_value(kTuneLinearCfg); v > 0) cfg = v;
 #endif

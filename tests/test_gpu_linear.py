@@ -81,11 +81,12 @@ def _run_layer(dgq, oracle, run, cal, act_bits, w_bits, G, P=2, bias=None, sampl
 
 
 def tile_rows(M, seed, extra=()):
-    """One row of every 128-row tile (a random offset in each), the tensor's first and last
-    rows, and `extra`: a fault tied to a tile index cannot hide between the samples."""
+    """One row of every 64-row tile (a random offset in each; the kernels' row tiles are 64 or
+    128 rows), the tensor's first and last rows, and `extra`: a fault tied to a tile index
+    cannot hide between the samples."""
     rng = np.random.default_rng(seed)
-    starts = np.arange(0, M, 128)
-    picks = np.minimum(starts + rng.integers(0, 128, size=len(starts)), M - 1)
+    starts = np.arange(0, M, 64)
+    picks = np.minimum(starts + rng.integers(0, 64, size=len(starts)), M - 1)
     return np.unique(np.concatenate([picks, np.asarray(extra, dtype=np.int64), [0, M - 1]]))
 
 
