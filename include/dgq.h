@@ -271,7 +271,8 @@ int dgq_weight_tables(const dgq_weight_t *w, int8_t *wq, float *sw);
  * contraction's own fragment path would cost it twelve more vector instructions per
  * matrix instruction; the expansion kernel costs a few microseconds per call.)
  * The other linear entry points return DGQ_EUNSUPPORTED for a converted handle.
- * Blocks until done; allocates.  Errors: DGQ_EINVAL (null), DGQ_EUNSUPPORTED (w_bits != 4,
+ * Blocks until done; allocates.  The handle must not be in use by any stream while it is
+ * converted (it is the one call that changes a handle after creation).  Errors: DGQ_EINVAL (null), DGQ_EUNSUPPORTED (w_bits != 4,
  * or a handle from dgq_pack_weight_gated_for), DGQ_ESHAPE (already converted).
  */
 int dgq_weight_pack_nibbles(dgq_weight_t *w, void *stream);
