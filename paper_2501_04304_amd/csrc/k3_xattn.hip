@@ -409,14 +409,17 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
         }
 
         // ---- pass 2: codes -> bf16 powers of two, packed as the next B operand --------------
-        // code = clamp(rne(t)), t = c0 - S.  Adding 1.5 * 2^23 leaves rne(t) in the low
-        // mantissa bits, so rounding, clamping (an integer median) and the bf16 exponent
-        // 127 - code are all integer work.  A probability that rounds to zero in fp32
+        // code = clamp(rne(t)), t = c0 - S.  Adding 1.5 * 2^23 to -t leaves -rne(t) in the low
+        // mantissa bits (round-to-nearest-even is symmetric), so rounding and clamping (an
+        // integer median m = magic - code) are integer work, and the bf16 exponents 127 - code
+        // of a pair of keys are two shift-and-adds of m onto one constant:
+        // (m0 << 7) + (m1 << 23) - ((magic - 127) << 7) - ((magic - 127) << 23) mod 2^32.  A probability that rounds to zero in fp32
         // (t above l2s + 150) takes the top code; with 4-bit codes the clamp already does
         // that unless the prompt scale is below 2^-135, so the common 4-bit path skips it.
         const float c0 = l2s + lse_i;
         const float thr = l2s + 150.0f;
         constexpr int32_t kMagic = 0x4B400000;  // bit pattern of 12582912.0f
+        constexpr uint32_t kPairBase = 0u - (((uint32_t)(kMagic - 127) << 7) + ((uint32_t)(kMagic - 127) << 23));
         const int32_t cq = (1 << bits) - 1;
         const int32_t ce = cq < 127 ? cq : 127;  // 2^-127 and below leave the product as zero
         uint8_t *cd = nullptr;
@@ -432,20 +435,20 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
                         pk[blk][i >> 1] = 0;
                         continue;
                     }
-                    int32_t e[2];
+                    uint32_t m[2];
 #pragma unroll
                     for (int u = 0; u < 2; ++u) {
-                        float t = c0 - sm[blk][i + u];
-                        if (RULE) t = t > thr ? 300.0f : t;
+                        float t = sm[blk][i + u] - c0;  // minus the code before rounding
+                        if (RULE) t = t < -thr ? -300.0f : t;
                         const int32_t r = __float_as_int(t + 12582912.0f);
                         if (DUMP) {
                             const int key = key_of(blk, i + u, hh);
-                            const int32_t c = clamp_i32(r, kMagic, kMagic + cq) - kMagic;
+                            const int32_t c = kMagic - clamp_i32(r, kMagic - cq, kMagic);
                             if (valid && key >= 1 && key < nk) cd[key - 1] = (uint8_t)c;
                         }
-                        e[u] = (kMagic + 127) - clamp_i32(r, kMagic, kMagic + ce);
+                        m[u] = (uint32_t)clamp_i32(r, kMagic - ce, kMagic);
                     }
-                    pk[blk][i >> 1] = ((uint32_t)(e[0] | (e[1] << 16)) << 7) & pmask;
+                    pk[blk][i >> 1] = ((m[0] << 7) + ((m[1] << 23) + kPairBase)) & pmask;
                 }
         };
         if (thr < (float)cq)
@@ -877,6 +880,8 @@ __global__ __launch_bounds__(64 * kSWaves, CF::OCC) void k_selfattn(
     const float c0 = l2s + lse;
     const float thr = l2s + 150.0f;
     constexpr int32_t kMagic = 0x4B400000;  // bit pattern of 12582912.0f
+    // exponents 127 - code of two keys from m = magic - code: (m0 << 7) + (m1 << 23) + this
+    constexpr uint32_t kPairBase = 0u - (((uint32_t)(kMagic - 127) << 7) + ((uint32_t)(kMagic - 127) << 23));
     const int32_t cq = (1 << bits) - 1;
     const int32_t ce = cq < 127 ? cq : 127;  // 2^-127 and below leave the product as zero
     uint8_t *cd = nullptr;
@@ -914,22 +919,22 @@ __global__ __launch_bounds__(64 * kSWaves, CF::OCC) void k_selfattn(
         uint32_t pk[8];
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
-            int32_t e[2];
+            uint32_t m[2];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                float t = c0 - sm[i + u];
+                float t = sm[i + u] - c0;  // minus the code before rounding
                 // a probability that is zero in fp32 takes the top code; the product does not
                 // need the rule (every code above 126 gives a zero weight anyway)
-                if (DUMP) t = t > thr ? 300.0f : t;
+                if (DUMP) t = t < -thr ? -300.0f : t;
                 const int32_t r = __float_as_int(t + 12582912.0f);
                 if (DUMP) {
                     const int32_t key = 32 * kt + key_of(0, i + u, hh);
-                    const int32_t c = clamp_i32(r, kMagic, kMagic + cq) - kMagic;
+                    const int32_t c = kMagic - clamp_i32(r, kMagic - cq, kMagic);
                     if (valid && key < nk) cd[key] = (uint8_t)c;
                 }
-                e[u] = (kMagic + 127) - clamp_i32(r, kMagic, kMagic + ce);
+                m[u] = (uint32_t)clamp_i32(r, kMagic - ce, kMagic);
             }
-            pk[i >> 1] = ((uint32_t)(e[0] | (e[1] << 16)) << 7) & pmask;
+            pk[i >> 1] = ((m[0] << 7) + ((m[1] << 23) + kPairBase)) & pmask;
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
