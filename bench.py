@@ -576,30 +576,38 @@ def main():
     # values).  The step times them as the two layers they are; here the context is quantized
     # once and contracted with the two weight matrices stacked ([O_k + O_v, C]), whose
     # output's column halves are K and V.
-    prompt_kv = []
+    prompt_kv, qkv = [], []
     if args.workload == "config5" and not args.step_only:
-        for pre in ("hi", "lo"):
-            pair = [e for e in layers if e["name"] in (pre + ".xk", pre + ".xv")]
-            if len(pair) != 2:
-                continue
-            ek, ev_ = pair
-            m = ek["modes"][(8, 8)]
-            M = ek["M"]
-            wk = up(di.linear_case(ek["seed"], 1, 2, ek["C"], ek["O"])["W"])
-            wv = up(di.linear_case(ev_["seed"], 1, 2, ev_["C"], ev_["O"])["W"])
-            wt2 = dgq.dgq_pack_weight(m["g"], torch.cat([wk, wv], 0).contiguous(), None, 8)
-            y2 = torch.empty((M, ek["O"] + ev_["O"]), dtype=torch.float32, device=dev)
-            us_q = time_calls(L.dgq_quantize_act, (C.c_void_p(m["g"].handle), ptr(ek["x"]), C.c_int64(M),
+        def stacked(names):
+            group = [e for e in layers if e["name"] in names]
+            if len(group) != len(names):
+                return None
+            e0 = group[0]
+            m = e0["modes"][(8, 8)]
+            M = e0["M"]
+            ws_ = [up(di.linear_case(e["seed"], 1, 2, e["C"], e["O"])["W"]) for e in group]
+            wt2 = dgq.dgq_pack_weight(m["g"], torch.cat(ws_, 0).contiguous(), None, 8)
+            O2 = sum(e["O"] for e in group)
+            y2 = torch.empty((M, O2), dtype=torch.float32, device=dev)
+            us_q = time_calls(L.dgq_quantize_act, (C.c_void_p(m["g"].handle), ptr(e0["x"]), C.c_int64(M),
                                                    ptr(m["codes"]), ptr(m["cls"]), sp))
             us_l = time_calls(L.dgq_linear, (C.c_void_p(m["g"].handle), C.c_void_p(wt2.handle),
                                              ptr(m["codes"]), ptr(m["cls"]), C.c_int64(M), ptr(y2), None,
                                              None, C.c_size_t(0), sp))
-            sep = sum(step_us("quantize_a8", e) + step_us("linear_a8", e) for e in pair)
-            prompt_kv.append(dict(layers=[ek["name"], ev_["name"]], M=M, C=ek["C"], O=ek["O"] + ev_["O"],
-                                  us_quantize_once=round(us_q, 2), us_linear_stacked=round(us_l, 2),
-                                  us_two_layers_in_step=round(sep, 2)))
+            sep = sum(step_us("quantize_a8", e) + step_us("linear_a8", e) for e in group)
             wt2.free()
-            del wk, wv, y2
+            return dict(layers=[e["name"] for e in group], M=M, C=e0["C"], O=O2,
+                        us_quantize_once=round(us_q, 2), us_linear_stacked=round(us_l, 2),
+                        us_layers_in_step=round(sep, 2))
+        for pre in ("hi", "lo"):
+            r = stacked((pre + ".xk", pre + ".xv"))
+            if r:
+                r["us_two_layers_in_step"] = r["us_layers_in_step"]
+                prompt_kv.append(r)
+            # the q, k and v projections of a self-attention block read one tensor as well
+            r = stacked((pre + ".q", pre + ".k", pre + ".v"))
+            if r:
+                qkv.append(r)
 
     # ---------------- beyond the step: 4-bit weights stored two per byte --------------------
     # A8W4 on two layers: the handle that keeps one weight per byte against the nibble-packed
@@ -816,7 +824,7 @@ def main():
                             calls_per_step=len(calls), setup_s=round(t_setup, 1)),
                 roofline=roofline, ceilings_measured=ceilings, kernels=kernels, linear_a8_layers=per_layer,
                 layer_table=layer_table, ms_whole_unet_from_table=(round(unet_ms, 3) if unet_ms else None),
-                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, prompt_kv_stacked=prompt_kv, w4_nibble_packed=w4, value_quant=value_quant, self_attention=self_attn, conv3x3=conv, cpu_baseline=cpu)
+                linear_geglu=fused, ff_chain=chain, kmeans_grouping=kmeans, timestep_sweep=sweep, prompt_kv_stacked=prompt_kv, self_qkv_stacked=qkv, w4_nibble_packed=w4, value_quant=value_quant, self_attention=self_attn, conv3x3=conv, cpu_baseline=cpu)
     print(json.dumps(line))
 
 
