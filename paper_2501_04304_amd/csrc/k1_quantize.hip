@@ -392,19 +392,47 @@ using Kern = void (*)(const float *, int64_t, int32_t, int32_t, int32_t, const i
                       int32_t, int32_t, int64_t, const uint32_t *);
 
 // A kernel instantiation and the state of its dynamic-LDS limit.
+// Workgroups of a kernel that one CU holds at a given LDS size, as the runtime's occupancy
+// calculation gives it (registers count too: the 640-channel kernel needs 71, seven
+// workgroups per CU where LDS alone would admit eight).  Remembered per device together with
+// the LDS size it was asked for.
+struct Residency {
+    std::atomic<uint64_t> v[kMaxDevices];  // (LDS bytes + 1) << 8 | workgroups per CU; 0 = not asked yet
+};
 struct Picked {
     Kern kern;
     LdsLimit *lim;
+    Residency *res;
 };
 template <int BITS, int NV>
 Picked vec_kernel() {
     static LdsLimit lim;
-    return {k_quantize_act<BITS, NV>, &lim};
+    static Residency res;
+    return {k_quantize_act<BITS, NV>, &lim, &res};
+}
+hipError_t resident_workgroups(const Picked &k, size_t lds, int *per_cu) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    const uint64_t key = (uint64_t)lds + 1;
+    const uint64_t cur = k.res->v[dev].load(std::memory_order_acquire);
+    if ((cur >> 8) == key) {
+        *per_cu = (int)(cur & 0xff);
+        return hipSuccess;
+    }
+    int n = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(k.kern), 256, lds);
+    if (e != hipSuccess) return e;
+    n = n < 1 ? 1 : (n > 255 ? 255 : n);
+    k.res->v[dev].store(key << 8 | (uint64_t)n, std::memory_order_release);
+    *per_cu = n;
+    return hipSuccess;
 }
 template <int BITS>
 Picked any_kernel() {
     static LdsLimit lim;
-    return {k_quantize_act_any<BITS>, &lim};
+    return {k_quantize_act_any<BITS>, &lim, nullptr};
 }
 
 // NV = float4 loads per lane per row; exact for the usual channel counts (320 .. 5120).
@@ -449,9 +477,16 @@ hipError_t launch_quantize_act(const Groups &g, const float *x, int64_t rows, in
             rpw_log2 = 0;
             blocks = (rows + 3) / 4;
         }
-        // resident workgroups per CU by LDS; every workgroup walks several units
-        int per_cu = (int)((160 * 1024) / lds);
-        per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+        // As many workgroups as the chip holds at once, every one walking several units: one
+        // more than that and the last ones start when the first are done, with their whole
+        // share of the rows still to do on a mostly idle chip.
+        if (lds > 64 * 1024) {
+            hipError_t e = raise_lds_limit(*kern.lim, reinterpret_cast<const void *>(kern.kern), 160 * 1024);
+            if (e != hipSuccess) return e;
+        }
+        int per_cu = 1;
+        if (hipError_t e = resident_workgroups(kern, lds, &per_cu); e != hipSuccess) return e;
+        per_cu = per_cu > 8 ? 8 : per_cu;
 #ifdef DGQ_TUNING  // tuning builds only: cap on resident workgroups per CU
         if (const int cap_t = tuning_value(kTuneQuantWgPerCu); cap_t > 0 && per_cu > cap_t) per_cu = cap_t;
 #endif
