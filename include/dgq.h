@@ -400,8 +400,11 @@ size_t dgq_linear_workspace_bytes(const dgq_groups_t *g, const dgq_weight_t *w,
  * Column 0 (the <start> token) bypasses the quantizer; no renormalisation.
  *   q, out: fp32 [B, N, H, d];  k, v: fp32 [B, nk, H, d];  key_bias: fp32 [nk] or NULL
  *   scale_out: fp32 [B] (written);  codes_dump: NULL or uint8 [B, H, N, nk-1]
- *   workspace: device scratch of at least dgq_xattn_workspace_bytes(...) bytes,
- *              16-byte aligned; contents are overwritten.
+ *   workspace: device scratch of dgq_xattn_workspace_bytes(...) bytes, 16-byte aligned;
+ *              contents are overwritten.  One float per (b, h, query), rounded up to 256
+ *              bytes, is the least that is accepted (DGQ_EWORKSPACE below that); with the
+ *              full size the maxima behind scale_out travel through the workspace as well
+ *              and the call is one kernel launch shorter.  Same results either way.
  * Limits: 2 <= nk <= 128, 1 <= d <= 256, attn_bits in {4, 8}.
  * Two kernels run back to back on `stream` (all probabilities must be known
  * before any of them can be coded).  Shapes with d a multiple of 8 up to 96 and
@@ -426,8 +429,9 @@ size_t dgq_xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d,
  * query) kept between the two kernels lives in a fixed array inside the library's device
  * image instead of a caller's workspace.  The call allocates nothing and frees nothing.
  *   Limit: B * H * N <= DGQ_XATTN_NOALLOC_MAX_ROWS (4 MiB of floats; DGQ_EWORKSPACE beyond,
- *          nothing is enqueued).  Every GPU the library runs on holds those 4 MiB from the
- *          first call on it until the process ends.
+ *          nothing is enqueued).  Every GPU the library runs on holds the array (those 4 MiB
+ *          and 0.3 MiB for the maxima behind scale_out) from the first call on it until the
+ *          process ends.
  *   Sharing: all calls on one GPU use the same array, whichever stream they run on, and the
  *          array keeps the last call's contents (nothing in it needs clearing: the first
  *          kernel writes every entry the second one reads).  Two calls that overlap in time

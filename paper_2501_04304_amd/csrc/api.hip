@@ -1042,11 +1042,11 @@ int dgq_xattn_logq(const float *q, const float *k, const float *v, const float *
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) ||
         (key_bias && !aligned16(key_bias)))
         return fail(DGQ_EALIGN, "dgq_xattn_logq: tensor not 16-byte aligned");
-    const size_t need = xattn_workspace_bytes(B, N, H, d, nk);
+    const size_t need = xattn_workspace_min_bytes(B, N, H, d, nk);
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace)))
         return fail(DGQ_EWORKSPACE, "dgq_xattn_logq: workspace missing, too small or misaligned");
     DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
-                         workspace, nullptr, static_cast<hipStream_t>(stream)));
+                         workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 
@@ -1058,7 +1058,8 @@ int dgq_xattn_logq(const float *q, const float *k, const float *v, const float *
 // hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
 }  // extern "C"
 
-constexpr size_t kScratchFloats = DGQ_XATTN_NOALLOC_MAX_ROWS;
+// the row statistics of DGQ_XATTN_NOALLOC_MAX_ROWS rows and the per-piece maxima behind them
+constexpr size_t kScratchFloats = DGQ_XATTN_NOALLOC_MAX_ROWS + (DGQ_XATTN_NOALLOC_MAX_ROWS >> 4) + 4096 + 64;
 static __device__ __align__(256) float scratch[kScratchFloats];
 
 namespace {
@@ -1099,8 +1100,8 @@ int dgq_xattn_logq_noalloc(const float *q, const float *k, const float *v, const
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) ||
         (key_bias && !aligned16(key_bias)))
         return fail(DGQ_EALIGN, "dgq_xattn_logq_noalloc: tensor not 16-byte aligned");
-    const size_t need = xattn_workspace_bytes(B, N, H, d, nk);
-    if (need > sizeof(float) * kScratchFloats)
+    const size_t need = xattn_workspace_min_bytes(B, N, H, d, nk);
+    if (need > sizeof(float) * DGQ_XATTN_NOALLOC_MAX_ROWS)
         return fail(DGQ_EWORKSPACE,
                     "dgq_xattn_logq_noalloc: B * H * N exceeds DGQ_XATTN_NOALLOC_MAX_ROWS; use "
                     "dgq_xattn_logq with a workspace");
@@ -1110,7 +1111,7 @@ int dgq_xattn_logq_noalloc(const float *q, const float *k, const float *v, const
         if (rc != DGQ_OK) return rc;
     }
     DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
-                         ws, nullptr, static_cast<hipStream_t>(stream)));
+                         ws, sizeof(float) * kScratchFloats, nullptr, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 
@@ -1133,7 +1134,7 @@ int dgq_xattn_logq_static(const float *q, const float *k, const float *v, const 
         (key_bias && !aligned16(key_bias)))
         return fail(DGQ_EALIGN, "dgq_xattn_logq_static: tensor not 16-byte aligned");
     DGQ_HIP(launch_xattn(q, k, v, key_bias, B, N, H, d, nk, attn_bits, out, scale_out, codes_dump,
-                         nullptr, scale_in, static_cast<hipStream_t>(stream)));
+                         nullptr, 0, scale_in, static_cast<hipStream_t>(stream)));
     return DGQ_OK;
 }
 

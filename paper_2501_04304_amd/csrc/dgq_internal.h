@@ -183,7 +183,7 @@ hipError_t launch_conv3x3_codes(const Groups &g9, const int8_t *codes, int32_t B
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
                         float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
-                        const float *scale_in, hipStream_t st);
+                        size_t workspace_bytes, const float *scale_in, hipStream_t st);
 
 // The attention on V^'s integer codes with 4-bit probability codes (shift-and-add product).
 hipError_t launch_xattn_intv(const float *q, const float *k, const uint8_t *vq, const float *vparams,
@@ -203,5 +203,8 @@ hipError_t launch_selfattn(const float *q, const float *k, const float *v, int32
 size_t selfattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d);
 
 size_t xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk);
+// the least the attention can work with (the row statistics alone; its maximum then goes
+// through atomics on scale[] and one more launch that clears it)
+size_t xattn_workspace_min_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk);
 
 }  // namespace dgq

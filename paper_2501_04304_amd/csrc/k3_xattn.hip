@@ -156,7 +156,14 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
     const float *__restrict__ key_bias, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
     float qk_scale, int32_t trips_per_wg, int32_t n_pairs, float *__restrict__ out, float *__restrict__ scale,
     float *__restrict__ lse2, uint8_t *__restrict__ codes_dump,
-    const float *__restrict__ scale_in) {
+    const float *__restrict__ scale_in, float *__restrict__ part_max, int32_t tpw1) {
+    // part_max (passes 1 and 2; may be null): instead of folding its maximum into scale[b] with
+    // an atomic, which needs scale[] cleared by a launch of its own before pass 1 (5 us of a
+    // 110 us call), a pass-1 workgroup stores the maximum of every piece it walks, of pair p in
+    // its range w, at part_max[p + w] (p + w grows along the sequence of pieces, so every piece
+    // has a slot of its own, n_pairs + ranges slots in all, each written once per call); pass 2
+    // takes the maximum over the slots of its prompt's pairs (tpw1 = pass 1's trips per range
+    // tells which exist) and the workgroup that holds the prompt's first trip writes scale[b].
     // PASS 3: both passes in one, for a prompt scale that is GIVEN (scale_in): the soft-max
     // statistics of a query block are taken and used at once, Q is read a single time, and
     // `scale` (if not null) still collects this call's own maximum.
@@ -201,8 +208,21 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
 
     float s_b = 0.0f, s_eff = 1.0f, l2s = 0.0f;
     uint32_t pmask = 0xFFFFFFFFu;
-    if (PASS >= 2) {
+    if (PASS == 2 && part_max != nullptr) {
+        // every wave takes the maximum over the slots of prompt b by itself
+        const int32_t per = (trips_per_pair + tpw1 - 1) / tpw1 + 1;  // pieces of a pair, at most
+        float m = 0.0f;  // the slots hold probabilities (>= 0)
+        for (int32_t idx = lane; idx < H * per; idx += kWave) {
+            const int32_t p = b * H + idx / per, j = idx % per;
+            const int32_t w = (p * trips_per_pair) / tpw1 + j;
+            if (w <= ((p + 1) * trips_per_pair - 1) / tpw1) m = fmaxf(m, part_max[p + w]);
+        }
+        s_b = wave_max(m);
+        if (tid == 0 && head == 0 && trip0 == 0) scale[b] = s_b;
+    } else if (PASS >= 2) {
         s_b = PASS == 3 ? scale_in[b] : scale[b];
+    }
+    if (PASS >= 2) {
         // no probability above zero outside the <start> column: only that column contributes
         s_eff = s_b > 0.0f ? s_b : 1.0f;
         pmask = s_b > 0.0f ? 0xFFFFFFFFu : 0u;
@@ -545,8 +565,11 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
 #pragma unroll
             for (int w = 1; w < kXWaves; ++w) amax = fmaxf(amax, red[w]);
             // probabilities are non-negative: their bit patterns order like unsigned ints
-            atomicMax(reinterpret_cast<unsigned int *>(scale + b),
-                      __float_as_uint(__builtin_amdgcn_exp2f(amax)));
+            if (PASS == 1 && part_max != nullptr)
+                part_max[pair + (int32_t)blockIdx.x] = __builtin_amdgcn_exp2f(amax);
+            else
+                atomicMax(reinterpret_cast<unsigned int *>(scale + b),
+                          __float_as_uint(__builtin_amdgcn_exp2f(amax)));
         }
     }
     }  // pairs of this workgroup's range
@@ -555,11 +578,16 @@ __global__ __launch_bounds__(kXThreads, (PASS >= 2 && CF::WAVES_PER_SIMD > 2) ? 
 // Workgroup slots of the chip for the kernels that write the product (one workgroup per CU).
 constexpr int kTargetWgs2 = 256;
 
+// bytes of the per-row statistics at the start of the attention's workspace
+inline size_t xattn_lse_bytes(int32_t B, int32_t N, int32_t H) {
+    return ((size_t)B * H * N * sizeof(float) + 255) / 256 * 256;
+}
+
 template <class CF>
 hipError_t launch_mfma(const float *q, const float *k, const float *v, const float *key_bias,
                        int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
                        float *out, float *scale_out, uint8_t *codes_dump, float *lse2,
-                       const float *scale_in, hipStream_t st) {
+                       size_t ws_bytes, const float *scale_in, hipStream_t st) {
     auto k1 = k_xattn_mfma<CF, 1, false>;
     auto k2 = codes_dump ? k_xattn_mfma<CF, 2, true> : k_xattn_mfma<CF, 2, false>;
     hipError_t e = DGQ_ENSURE_LDS((k_xattn_mfma<CF, 1, false>), (int)CF::lds_pass1);
@@ -593,14 +621,21 @@ hipError_t launch_mfma(const float *q, const float *k, const float *v, const flo
         if (scale_out)
             hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
         hipLaunchKernelGGL(k3, grid2, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d,
-                           nk, bits, qk_scale, tpw2, n_pairs, out, scale_out, nullptr, codes_dump, scale_in);
+                           nk, bits, qk_scale, tpw2, n_pairs, out, scale_out, nullptr, codes_dump, scale_in,
+                           nullptr, 0);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
+    // the per-piece maxima behind the row statistics, if the workspace has room for them
+    // (a workspace of xattn_workspace_bytes() has); otherwise atomics on a cleared scale[]
+    const size_t lse_bytes = xattn_lse_bytes(B, N, H);
+    float *part_max = nullptr;
+    if (ws_bytes >= lse_bytes + sizeof(float) * ((size_t)n_pairs + grid.x))
+        part_max = reinterpret_cast<float *>(reinterpret_cast<char *>(lse2) + lse_bytes);
+    if (!part_max) hipLaunchKernelGGL(k_fill_zero, dim3((B + 63) / 64), dim3(64), 0, st, scale_out, B);
     hipLaunchKernelGGL(k1, grid, dim3(kXThreads), CF::lds_pass1, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, tpw, n_pairs, out, scale_out, lse2, codes_dump, nullptr);
+                       bits, qk_scale, tpw, n_pairs, out, scale_out, lse2, codes_dump, nullptr, part_max, tpw);
     hipLaunchKernelGGL(k2, grid2, dim3(kXThreads), CF::lds_pass2, st, q, k, v, key_bias, N, H, d, nk,
-                       bits, qk_scale, tpw2, n_pairs, out, scale_out, lse2, codes_dump, nullptr);
+                       bits, qk_scale, tpw2, n_pairs, out, scale_out, lse2, codes_dump, nullptr, part_max, tpw);
     return hipGetLastError();
 }
 
@@ -1322,9 +1357,16 @@ hipError_t launch_passes(const float *q, const float *k, const float *v, const f
 
 // The matrix-core path keeps one float (log2 of the soft-max denominator, shifted by the
 // row maximum) per (prompt, head, query) between its two passes.
+size_t xattn_workspace_min_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk) {
+    if (!mfma_shape(d, nk)) return 0;
+    return xattn_lse_bytes(B, N, H);
+}
+
+// The row statistics plus one slot per piece of pass 1 (pairs + ranges, with room for a
+// tuning build's larger range counts).
 size_t xattn_workspace_bytes(int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk) {
     if (!mfma_shape(d, nk)) return 0;
-    return ((size_t)B * H * N * sizeof(float) + 255) / 256 * 256;
+    return xattn_lse_bytes(B, N, H) + (sizeof(float) * ((size_t)B * H + 4096) + 255) / 256 * 256;
 }
 
 hipError_t launch_quantize_value(const float *v, int32_t B, int32_t nk, int32_t H, int32_t d,
@@ -1373,7 +1415,7 @@ hipError_t launch_xattn_intv(const float *q, const float *k, const uint8_t *vq, 
 hipError_t launch_xattn(const float *q, const float *k, const float *v, const float *key_bias,
                         int32_t B, int32_t N, int32_t H, int32_t d, int32_t nk, int32_t bits,
                         float *out, float *scale_out, uint8_t *codes_dump, void *workspace,
-                        const float *scale_in, hipStream_t st) {
+                        size_t workspace_bytes, const float *scale_in, hipStream_t st) {
     if (mfma_shape(d, nk)) {
         float *lse2 = static_cast<float *>(workspace);
         const int ks = d <= 48 ? 3 : (d <= 64 ? 4 : (d <= 96 ? 6 : 10));
@@ -1381,7 +1423,7 @@ hipError_t launch_xattn(const float *q, const float *k, const float *v, const fl
 #define DGQ_XATTN_CASE(NKB, KS)                                                              \
     if (nkb == NKB && ks == KS)                                                              \
         return launch_mfma<XCfg<NKB, KS>>(q, k, v, key_bias, B, N, H, d, nk, bits, out,       \
-                                          scale_out, codes_dump, lse2, scale_in, st);
+                                          scale_out, codes_dump, lse2, workspace_bytes, scale_in, st);
         DGQ_XATTN_CASE(3, 3)
         DGQ_XATTN_CASE(3, 4)
         DGQ_XATTN_CASE(3, 6)

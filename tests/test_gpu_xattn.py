@@ -101,6 +101,35 @@ def test_workgroup_ranges_cross_pairs(dgq, oracle, bits):
     _compare(dgq, oracle, c, bits, exact=True)
 
 
+@pytest.mark.parametrize("bits", [4, 8])
+def test_least_workspace_gives_the_same_results(dgq, bits):
+    """With the full workspace the maxima behind the prompt scale travel through it; with one
+    float per (prompt, head, query) and nothing more they go through atomics on scale_out,
+    cleared by a launch of its own.  Both must give the same scale, codes and product, on ranges
+    that cross pairs and prompts (5 prompts x 9 heads, 11 trips per pair)."""
+    import torch
+    from oracle.guard import guarded_attention_case
+    c, _ = guarded_attention_case(7701, 5, 2600, 9, 64, bits_list=(bits,))
+    B, N, H, d = c["Q"].shape
+    nk = c["K"].shape[1]
+    dev = [_dev(c[n]) for n in ("Q", "K", "V", "key_bias")]
+    res = []
+    full = dgq.dgq_xattn_workspace_bytes(B, N, H, d, nk)
+    least = (B * H * N * 4 + 255) // 256 * 256
+    assert least < full
+    for nbytes in (full, least):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        codes = torch.full((B, H, N, nk - 1), 0xEE, dtype=torch.uint8, device="cuda")
+        s = torch.full((B,), 123.0, dtype=torch.float32, device="cuda")  # stale values must not survive
+        out, s = dgq.dgq_xattn_logq(*dev, bits, scale_out=s, codes_dump=codes, workspace=ws)
+        torch.cuda.synchronize()
+        res.append((out.cpu().numpy(), s.cpu().numpy(), codes.cpu().numpy()))
+    for a, b in zip(res[0], res[1]):
+        assert np.array_equal(a, b)
+    with pytest.raises(dgq.DgqError):
+        dgq.dgq_xattn_logq(*dev, bits, workspace=torch.empty(least - 256, dtype=torch.uint8, device="cuda"))
+
+
 def test_without_key_bias(dgq, oracle):
     from oracle.guard import guarded_attention_case
     c, _ = guarded_attention_case(11, 2, 96, 2, 40, bits_list=(8,))
