@@ -80,6 +80,7 @@ SHAPES = [
     (1, 257, 2, 8, 10),    # few keys
     (1, 40, 2, 40, 100),   # more than 80 keys
     (3, 1, 1, 16, 2),      # one query, one quantized key
+    (100, 100, 3, 16, 10), # 300 one-trip pairs on 150 ranges: a range holds two pairs, of two prompts every third time
 ]
 
 
